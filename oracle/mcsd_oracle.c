@@ -1,0 +1,393 @@
+/*
+ * CPU oracle for the verification step of Multi-Candidate Speculative Decoding.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference the GPU
+ * library is checked against.  It shares no code, header, table or helper with
+ * the HIP path, and nothing in the product path may call it (only tests/, the
+ * smoke check and the cpu_baseline leg of the bench do).
+ *
+ * Everything is computed in fp64 from inputs converted exactly out of their
+ * storage type (fp32, or bf16 bit patterns).  Loops follow the definitions in
+ * the order the paper states them; there is no blocking, fusion or reordering.
+ * OpenMP is used only across independent units (one query row, one tree node).
+ *
+ * What each function follows:
+ *   mcsd_oracle_tree_attn      Sec. 3.3 (Tree Attention) and the caption of its
+ *                              figure: softmax attention in which a candidate
+ *                              sees the whole shared prefix, its ancestors and
+ *                              itself.
+ *   mcsd_oracle_verify_parent  Algorithm 1 (candidates drawn with replacement)
+ *                              and Algorithm 2 (without replacement, q-bar of
+ *                              Eq. (1)); the k=1 case is the speculative
+ *                              sampling rule of Sec. 2.
+ *   mcsd_oracle_verify         Sec. 3, the paragraph describing verification as
+ *                              a walk from the root of the candidate tree to a
+ *                              leaf, with the endpoint rules of Sec. 2.
+ *
+ * Pins (tests/test_oracle_*.py): exact enumeration of the output distribution
+ * against the theorems of Appendix A and B, the per-round accept / reject
+ * masses of Appendix A, hand-derived rational examples, the k=1 textbook rule,
+ * the Appendix C inequality, the argmax behaviour stated in Sec. 4.4, and
+ * brute-force per-path causal attention.  No function here is unpinned.
+ *
+ * Readings taken where the paper is silent (listed in full in the design notes
+ * of this repository): self is attendable; the root is the last context token
+ * and is not a query row; accept iff u <= min(1, p/q); q(x)=0 gives ratio 1 if
+ * p(x)>0 else 0; a zero residual mass leaves p unchanged; the endpoint is drawn
+ * by inverse CDF in token-id order from one supplied uniform; ties in argmax go
+ * to the lowest id; Algorithm 2's residual uses q before the rejected token is
+ * removed (as in Appendix B's definition of p-bar_n).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_FP32 0
+#define ORACLE_BF16 1
+
+#define VARIANT_WITH_REPLACEMENT 0
+#define VARIANT_WITHOUT_REPLACEMENT 1
+
+static double load_elem(const void *base, int dtype, size_t idx)
+{
+    if (dtype == ORACLE_FP32)
+        return (double)((const float *)base)[idx];
+    uint32_t bits = (uint32_t)((const uint16_t *)base)[idx] << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+int mcsd_oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------ attention
+ * One output row: query (b, node, head) attends to prefix keys 0..L_b-1 and to
+ * the tree keys in A(node) = {node} U A(parent[node]), A(-1) = {} (Sec. 3.3).
+ * q        [B][N][H_q][d]
+ * k_prefix [B][H_kv][L_stride][d], v_prefix same
+ * k_tree   [B][H_kv][N][d],        v_tree   same
+ * The KV head of query head h is h / (H_q / H_kv).
+ */
+static void attn_one_row(int b, int node, int h, int N, int H_q, int H_kv, int d, int dtype,
+                         long L_stride, double scale, const void *q, const void *k_prefix,
+                         const void *v_prefix, const int32_t *prefix_len, const void *k_tree,
+                         const void *v_tree, const int32_t *parent, double *out)
+{
+    int g = h / (H_q / H_kv);
+    long L = prefix_len[b];
+    /* ancestor set, self included */
+    int *anc = (int *)malloc(sizeof(int) * (size_t)(N > 0 ? N : 1));
+    int n_anc = 0;
+    for (int a = node; a >= 0; a = parent[a])
+        anc[n_anc++] = a;
+    long n_keys = L + n_anc;
+    double *s = (double *)malloc(sizeof(double) * (size_t)n_keys);
+    size_t q_off = (((size_t)b * N + node) * H_q + h) * (size_t)d;
+    size_t pre_off = ((size_t)b * H_kv + g) * (size_t)L_stride * d;
+    size_t tree_off = ((size_t)b * H_kv + g) * (size_t)N * d;
+
+    for (long j = 0; j < L; ++j) {
+        double acc = 0.0;
+        for (int c = 0; c < d; ++c)
+            acc += load_elem(q, dtype, q_off + c) * load_elem(k_prefix, dtype, pre_off + (size_t)j * d + c);
+        s[j] = scale * acc;
+    }
+    for (int t = 0; t < n_anc; ++t) {
+        double acc = 0.0;
+        for (int c = 0; c < d; ++c)
+            acc += load_elem(q, dtype, q_off + c) * load_elem(k_tree, dtype, tree_off + (size_t)anc[t] * d + c);
+        s[L + t] = scale * acc;
+    }
+    double m = -INFINITY;
+    for (long j = 0; j < n_keys; ++j)
+        if (s[j] > m) m = s[j];
+    double denom = 0.0;
+    for (long j = 0; j < n_keys; ++j) {
+        s[j] = exp(s[j] - m);
+        denom += s[j];
+    }
+    for (int c = 0; c < d; ++c) {
+        double acc = 0.0;
+        for (long j = 0; j < L; ++j)
+            acc += s[j] * load_elem(v_prefix, dtype, pre_off + (size_t)j * d + c);
+        for (int t = 0; t < n_anc; ++t)
+            acc += s[L + t] * load_elem(v_tree, dtype, tree_off + (size_t)anc[t] * d + c);
+        out[c] = acc / denom;
+    }
+    free(s);
+    free(anc);
+}
+
+/* sel == NULL: all rows, out is [B][N][H_q][d].
+ * sel != NULL: n_sel triples (b, node, head), out is [n_sel][d]. */
+int mcsd_oracle_tree_attn(int B, int N, int H_q, int H_kv, int d, int dtype, long L_stride,
+                          double scale, const void *q, const void *k_prefix, const void *v_prefix,
+                          const int32_t *prefix_len, const void *k_tree, const void *v_tree,
+                          const int32_t *parent, const int32_t *sel, long n_sel, double *out,
+                          int n_threads)
+{
+    if (B < 0 || N < 0 || H_q <= 0 || H_kv <= 0 || H_q % H_kv != 0 || d <= 0)
+        return -1;
+    for (int i = 0; i < N; ++i)
+        if (parent[i] < -1 || parent[i] >= i)
+            return -2;
+    long total = sel ? n_sel : (long)B * N * H_q;
+    if (n_threads < 1) n_threads = 1;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(n_threads)
+    for (long r = 0; r < total; ++r) {
+        int b, node, h;
+        if (sel) {
+            b = sel[3 * r]; node = sel[3 * r + 1]; h = sel[3 * r + 2];
+        } else {
+            b = (int)(r / ((long)N * H_q));
+            node = (int)((r / H_q) % N);
+            h = (int)(r % H_q);
+        }
+        attn_one_row(b, node, h, N, H_q, H_kv, d, dtype, L_stride, scale, q, k_prefix, v_prefix,
+                     prefix_len, k_tree, v_tree, parent, out + (size_t)r * d);
+    }
+    return 0;
+}
+
+/* --------------------------------------------------------------- verification */
+static void softmax_T(const float *z, int V, double T, double *p)
+{
+    double m = -INFINITY;
+    for (int x = 0; x < V; ++x) {
+        double t = (double)z[x] / T;
+        if (t > m) m = t;
+    }
+    double sum = 0.0;
+    for (int x = 0; x < V; ++x) {
+        p[x] = exp((double)z[x] / T - m);
+        sum += p[x];
+    }
+    for (int x = 0; x < V; ++x)
+        p[x] /= sum;
+}
+
+static int argmax_lowest(const float *z, int V)
+{
+    int best = 0;
+    for (int x = 1; x < V; ++x)
+        if (z[x] > z[best]) best = x;
+    return best;
+}
+
+/* Smallest x with sum_{y<=x} p(y) > u; if rounding leaves none, the largest x
+ * with p(x) > 0.  *margin receives the distance from u to the nearer edge of
+ * the chosen token's CDF interval. */
+static int inverse_cdf(const double *p, int V, double u, double *margin)
+{
+    double cdf = 0.0;
+    int last_pos = -1;
+    for (int x = 0; x < V; ++x) {
+        double lo = cdf;
+        cdf += p[x];
+        if (p[x] > 0.0) last_pos = x;
+        if (cdf > u) {
+            double m_lo = fabs(u - lo), m_hi = fabs(cdf - u);
+            *margin = m_lo < m_hi ? m_lo : m_hi;
+            return x;
+        }
+    }
+    *margin = fabs(u - cdf);
+    return last_pos < 0 ? V - 1 : last_pos;
+}
+
+/*
+ * Algorithm 1 / Algorithm 2 for one parent.
+ *   z_p, z_q   logit rows [V]; p = softmax(z_p / T), q = softmax(z_q / T)
+ *   tok[k]     candidate ids in sampling order;  u_acc[k] their uniforms
+ *   u_end      uniform for the endpoint draw
+ *   T == 0     argmax behaviour (Sec. 4.4): accept the first candidate equal to
+ *              argmax z_p, otherwise the endpoint is that argmax; z_q, uniforms
+ *              unused.  k == 0 is a leaf: endpoint ~ softmax(z_p / T).
+ * Outputs: *accepted = index in 0..k-1 of the accepted candidate or -1;
+ *   *endpoint = endpoint token when nothing was accepted, else -1;
+ *   ratio[k] = min(1, p/q) actually tested, NaN for candidates not reached;
+ *   *margin = smallest |uniform - threshold| over the decisions taken;
+ *   residual[V] (nullable) = the distribution p held when the loop ended.
+ */
+int mcsd_oracle_verify_parent(int V, int k, int variant, double T, const float *z_p,
+                              const float *z_q, const int32_t *tok, const float *u_acc,
+                              double u_end, int32_t *accepted, int32_t *endpoint, double *ratio,
+                              double *margin, double *residual)
+{
+    *accepted = -1;
+    *endpoint = -1;
+    *margin = INFINITY;
+    for (int i = 0; i < k; ++i)
+        ratio[i] = NAN;
+
+    if (T == 0.0) {
+        int g = argmax_lowest(z_p, V);
+        for (int i = 0; i < k; ++i)
+            if (tok[i] == g) {
+                *accepted = i;
+                break;
+            }
+        if (*accepted < 0) *endpoint = g;
+        if (residual) {
+            for (int x = 0; x < V; ++x) residual[x] = 0.0;
+            residual[g] = 1.0;
+        }
+        return 0;
+    }
+
+    double *p = (double *)malloc(sizeof(double) * (size_t)V);
+    double *q = (double *)malloc(sizeof(double) * (size_t)V);
+    softmax_T(z_p, V, T, p);
+    if (k > 0) softmax_T(z_q, V, T, q);
+
+    for (int i = 0; i < k; ++i) {
+        int x = tok[i];
+        if (x < 0 || x >= V) {
+            free(p); free(q);
+            return -3;
+        }
+        double r = (double)u_acc[i];
+        double rat;
+        if (q[x] > 0.0) {
+            rat = p[x] / q[x];
+            if (rat > 1.0) rat = 1.0;
+        } else {
+            rat = p[x] > 0.0 ? 1.0 : 0.0;
+        }
+        ratio[i] = rat;
+        double mg = fabs(r - rat);
+        if (mg < *margin) *margin = mg;
+        if (r <= rat) {
+            *accepted = i;
+            break;
+        }
+        /* rejected: p := max(0, p - q) / sum max(0, p - q), with the q of this
+         * round (Appendix B defines p-bar_n from q-bar_{n-1}) */
+        double S = 0.0;
+        for (int y = 0; y < V; ++y) {
+            double w = p[y] - q[y];
+            S += w > 0.0 ? w : 0.0;
+        }
+        if (S > 0.0) {
+            for (int y = 0; y < V; ++y) {
+                double w = p[y] - q[y];
+                p[y] = (w > 0.0 ? w : 0.0) / S;
+            }
+        } /* else: impossible after a rejection in exact arithmetic; p is left unchanged */
+        if (variant == VARIANT_WITHOUT_REPLACEMENT) {
+            q[x] = 0.0;
+            double sq = 0.0;
+            for (int y = 0; y < V; ++y) sq += q[y];
+            if (sq > 0.0)
+                for (int y = 0; y < V; ++y) q[y] /= sq;
+        }
+    }
+
+    if (*accepted < 0) {
+        double mg;
+        *endpoint = inverse_cdf(p, V, u_end, &mg);
+        if (mg < *margin) *margin = mg;
+    }
+    if (residual) memcpy(residual, p, sizeof(double) * (size_t)V);
+    free(p);
+    free(q);
+    return 0;
+}
+
+/*
+ * Whole step: every row owner (root row 0, node i -> row 1+i) is evaluated, then
+ * the walk of Sec. 3 picks the path.
+ *   target_logits [B][1+N][V], draft_logits [B][P][V], q_row [1+N] (-1: leaf)
+ *   parent [N], cand_tok [B][N], u_accept [B][N], u_endpoint [B][1+N], temperature [B]
+ * Per-row outputs: acc_child [B][1+N] (node id or -1), endpoint [B][1+N] (-1 when a
+ *   child was accepted), ratio [B][N], margin [B][1+N], residual [B][1+N][V] or NULL.
+ * Walk outputs: n_accepted [B], accepted_path [B][gamma_max] (-1 padded),
+ *   out_tokens [B][gamma_max+1] (accepted tokens then the endpoint, -1 padded).
+ */
+int mcsd_oracle_verify(int B, int N, int V, int P, int variant, const float *target_logits,
+                       const float *draft_logits, const int32_t *q_row, const int32_t *parent,
+                       const int32_t *cand_tok, const float *u_accept, const float *u_endpoint,
+                       const float *temperature, int32_t *acc_child, int32_t *endpoint,
+                       double *ratio, double *margin, double *residual, int32_t *n_accepted,
+                       int32_t *accepted_path, int32_t *out_tokens, int gamma_max, int n_threads)
+{
+    for (int i = 0; i < N; ++i)
+        if (parent[i] < -1 || parent[i] >= i) return -2;
+    for (int r = 0; r <= N; ++r)
+        if (q_row[r] >= P) return -1;
+    if (n_threads < 1) n_threads = 1;
+    int status = 0;
+    long rows = (long)B * (1 + N);
+    for (long i = 0; i < (long)B * N; ++i) ratio[i] = NAN;
+
+#pragma omp parallel for schedule(dynamic, 1) num_threads(n_threads)
+    for (long r = 0; r < rows; ++r) {
+        int b = (int)(r / (1 + N));
+        int row = (int)(r % (1 + N));
+        int v = row - 1; /* node id, -1 for the root */
+        int kids[1024];
+        int k = 0;
+        for (int i = 0; i < N && k < 1024; ++i)
+            if (parent[i] == v) kids[k++] = i;
+        int32_t toks[1024];
+        float us[1024];
+        double rat[1024];
+        for (int i = 0; i < k; ++i) {
+            toks[i] = cand_tok[(size_t)b * N + kids[i]];
+            us[i] = u_accept[(size_t)b * N + kids[i]];
+        }
+        const float *zp = target_logits + ((size_t)b * (1 + N) + row) * V;
+        const float *zq = (k > 0 && q_row[row] >= 0)
+                              ? draft_logits + ((size_t)b * P + q_row[row]) * V
+                              : zp;
+        int32_t acc, endp;
+        double mg;
+        int rc = mcsd_oracle_verify_parent(V, k, variant, (double)temperature[b], zp, zq, toks, us,
+                                           (double)u_endpoint[(size_t)b * (1 + N) + row], &acc,
+                                           &endp, rat, &mg,
+                                           residual ? residual + (size_t)r * V : NULL);
+        if (rc != 0) {
+#pragma omp critical
+            status = rc;
+        }
+        acc_child[r] = acc >= 0 ? kids[acc] : -1;
+        endpoint[r] = endp;
+        margin[r] = mg;
+        for (int i = 0; i < k; ++i)
+            ratio[(size_t)b * N + kids[i]] = rat[i];
+    }
+    if (status != 0) return status;
+
+    for (int b = 0; b < B; ++b) {
+        for (int i = 0; i < gamma_max; ++i) accepted_path[(size_t)b * gamma_max + i] = -1;
+        for (int i = 0; i <= gamma_max; ++i) out_tokens[(size_t)b * (gamma_max + 1) + i] = -1;
+        int row = 0, n = 0;
+        for (;;) {
+            size_t r = (size_t)b * (1 + N) + row;
+            int c = acc_child[r];
+            if (c >= 0 && n >= gamma_max) return -4; /* tree deeper than gamma_max */
+            if (c < 0) {
+                /* all candidates rejected, or a leaf: the endpoint closes the block */
+                out_tokens[(size_t)b * (gamma_max + 1) + n] = endpoint[r];
+                break;
+            }
+            accepted_path[(size_t)b * gamma_max + n] = c;
+            out_tokens[(size_t)b * (gamma_max + 1) + n] = cand_tok[(size_t)b * N + c];
+            ++n;
+            row = 1 + c;
+        }
+        n_accepted[b] = n;
+    }
+    return 0;
+}
