@@ -1,0 +1,205 @@
+/*
+ * mcsd.h - C ABI of libmcsd: the target-side verification step of
+ * Multi-Candidate Speculative Decoding (MCSD) on one AMD MI355X (gfx950).
+ *
+ * Three operations, all enqueued asynchronously on a caller-supplied HIP stream:
+ *
+ *   mcsd_tree_attn      Tree attention (Sec. 3.3 of the paper): all candidate
+ *                       tokens of the draft tree are scored in one pass against
+ *                       the shared prefix KV cache; a candidate attends to the
+ *                       whole prefix, to its ancestors in the tree and to itself.
+ *   mcsd_verify_sample  Multi-candidate speculative sampling, Algorithm 1 (with
+ *                       replacement) and Algorithm 2 (without replacement), run
+ *                       for every node that has children, the endpoint draws of
+ *                       Sec. 2 / Sec. 3, and the root-to-leaf walk of Sec. 3 that
+ *                       turns the per-node outcomes into the accepted path.
+ *   mcsd_verify_step    Both, back to back on one stream: one layer's tree
+ *                       attention followed by one verification.
+ *
+ * Conventions
+ *   - Plain C, plain-old-data structs; the first field of every struct is its
+ *     own size in bytes (set it with sizeof) so the layout can be versioned.
+ *   - Every data pointer in a *_bufs struct is a DEVICE pointer that the caller
+ *     owns; the library never allocates, frees or keeps device memory.  Scratch
+ *     space comes in through `workspace` (size from mcsd_*_workspace_bytes) and
+ *     may be reused by the caller as soon as the stream has passed the call.
+ *     Descriptor structs and the arguments of mcsd_tree_validate are HOST memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls return after enqueueing; outputs are valid once the stream is
+ *     synchronised.  Two calls that share a workspace must be stream-ordered.
+ *   - Return value: MCSD_OK or a negative MCSD_E_* code.  On error nothing has
+ *     been enqueued.  mcsd_last_error() gives a thread-local message.  No call
+ *     aborts, throws or synchronises the device.
+ *   - Errors in the DATA (token id out of range, zero draft probability, ...)
+ *     cannot be seen from the host without a sync; they set bits in the
+ *     `flags` output instead (MCSD_FLAG_*).
+ *   - Tree layout: nodes 0..N-1 exclude the root, which is the last context
+ *     token (already in the prefix cache).  parent[i] == -1 marks a child of the
+ *     root; parent[i] < i is required (any order in which parents precede
+ *     children, e.g. generation order).  The children of a node are verified
+ *     in ascending node id, which must be the order they were sampled in
+ *     (Algorithm 2 depends on it).  "Row" r means the root for r == 0 and node
+ *     r-1 otherwise.  N <= MCSD_MAX_NODES.
+ */
+#ifndef MCSD_H
+#define MCSD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MCSD_MAX_NODES 128      /* tree nodes per sequence (root excluded) */
+#define MCSD_MAX_VOCAB 32768    /* both logit rows of a node stay in registers */
+#define MCSD_MAX_HEAD_DIM 256
+
+enum {
+    MCSD_OK = 0,
+    MCSD_E_NULL = -1,         /* a required pointer is NULL */
+    MCSD_E_SHAPE = -2,        /* a size is non-positive / inconsistent / struct_size wrong */
+    MCSD_E_UNSUPPORTED = -3,  /* valid request this build has no kernel for */
+    MCSD_E_TREE = -4,         /* N > MCSD_MAX_NODES or parent[] not in parents-first order */
+    MCSD_E_WORKSPACE = -5,    /* workspace missing, too small or misaligned (256 B) */
+    MCSD_E_HIP = -6           /* the HIP runtime reported an error at launch */
+};
+
+enum { MCSD_DTYPE_FP32 = 0, MCSD_DTYPE_BF16 = 1 };
+enum { MCSD_WITH_REPLACEMENT = 0, MCSD_WITHOUT_REPLACEMENT = 1 };
+
+/* bits of mcsd_verify_bufs.flags[b][row] */
+enum {
+    MCSD_FLAG_NEAR_TIE_ACCEPT = 1,    /* an accept test had |u - ratio| < near_tie_eps */
+    MCSD_FLAG_NEAR_TIE_ENDPOINT = 2,  /* u_endpoint within near_tie_eps of an edge of the chosen CDF interval */
+    MCSD_FLAG_BAD_TOKEN = 4,          /* candidate id outside [0, V): treated as rejected */
+    MCSD_FLAG_ZERO_DRAFT_PROB = 8,    /* q(candidate) == 0: ratio taken as 1 if p > 0 else 0 */
+    MCSD_FLAG_ZERO_RESIDUAL = 16,     /* sum max(0, p - q) was not positive after a rejection */
+    MCSD_FLAG_NONFINITE = 32,         /* a softmax normaliser was not finite and positive */
+    MCSD_FLAG_BAD_TREE = 64           /* a row with children has no valid q_row entry: handled as a leaf */
+};
+
+const char *mcsd_last_error(void);
+const char *mcsd_version(void);
+
+/* Host-side check of a parent array (host pointer): MCSD_OK or MCSD_E_TREE / MCSD_E_NULL. */
+int32_t mcsd_tree_validate(const int32_t *parent_host, int32_t n_nodes);
+
+/* ------------------------------------------------------------- tree attention
+ * Sec. 3.3.  For sequence b, query head h (KV head g = h / (H_q / H_kv)) and node i:
+ *   keys   = prefix positions 0 .. prefix_len[b]-1  and  tree nodes in A(i),
+ *            A(i) = {i} U A(parent[i]),  A(-1) = {}
+ *   out[b][i][h][:] = softmax_over_keys(scale * <q[b][i][h], K>) . V
+ * Inputs are expected to be position-encoded already (each candidate keeps the
+ * position it has in its own sequence, i.e. prefix_len + depth - 1).
+ * fp32 accumulation; bf16 inputs use the matrix cores when d == 128.
+ */
+typedef struct {
+    uint32_t struct_size;
+    int32_t B;              /* sequences */
+    int32_t N;              /* tree nodes per sequence, 1..MCSD_MAX_NODES */
+    int32_t H_q, H_kv;      /* query / KV heads, H_q % H_kv == 0 */
+    int32_t d;              /* head dim: multiple of 4 (fp32) or 8 (bf16), <= MCSD_MAX_HEAD_DIM */
+    int32_t dtype;          /* MCSD_DTYPE_* of q, k_*, v_*, out */
+    int32_t L_stride;       /* rows allocated per (sequence, KV head) in the prefix cache; prefix_len[b] <= L_stride */
+    float scale;            /* softmax scale, normally 1/sqrt(d) */
+    int32_t parent_per_seq; /* 0: one parent[N] shared by the batch; 1: parent[B][N] */
+} mcsd_attn_desc;
+
+typedef struct {
+    uint32_t struct_size;
+    const void *q;               /* [B][N][H_q][d] */
+    const void *k_prefix;        /* [B][H_kv][L_stride][d] */
+    const void *v_prefix;        /* [B][H_kv][L_stride][d] */
+    const int32_t *prefix_len;   /* [B], 0 <= prefix_len[b] <= L_stride */
+    const void *k_tree;          /* [B][H_kv][N][d] */
+    const void *v_tree;          /* [B][H_kv][N][d] */
+    const int32_t *parent;       /* [N] or [B][N] */
+    void *out;                   /* [B][N][H_q][d] */
+    void *workspace;             /* >= mcsd_attn_workspace_bytes(desc), 256-byte aligned */
+    size_t workspace_bytes;
+} mcsd_attn_bufs;
+
+/* Bytes of scratch mcsd_tree_attn needs for this descriptor (0 on a bad descriptor). */
+size_t mcsd_attn_workspace_bytes(const mcsd_attn_desc *desc);
+int32_t mcsd_tree_attn(const mcsd_attn_desc *desc, const mcsd_attn_bufs *bufs, void *stream);
+
+/* --------------------------------------------------------------- verification
+ * Algorithm 1 / Algorithm 2 for every row that has children, endpoint draws,
+ * and the walk (Sec. 3).  Per sequence b with temperature T = temperature[b]:
+ *   p_r = softmax(target_logits[b][r] / T),  q_r = softmax(draft_logits[b][q_row[r]] / T)
+ *   for the children c_1 < c_2 < ... of row r, x = cand_tok[b][c_i]:
+ *       ratio = min(1, p_r(x) / q_r(x));  accept c_i iff u_accept[b][c_i] <= ratio
+ *       else p_r := max(0, p_r - q_r) / sum_x max(0, p_r - q_r)
+ *            and, without replacement only, q_r(x) := 0, q_r := q_r / sum q_r
+ *   no child accepted, or r is a leaf: endpoint = inverse CDF of p_r (token-id
+ *       order, smallest x whose cumulative probability exceeds u_endpoint[b][r])
+ *   walk: r = 0; while a child c of r was accepted: emit cand_tok[c], r = 1 + c;
+ *       then emit the endpoint of r.
+ *   T == 0 (argmax sampling, Sec. 4.1/4.4): accept the first child whose token is
+ *       argmax target_logits[b][r] (lowest id on ties), otherwise that argmax is
+ *       the endpoint; draft logits and uniforms are not read.
+ * Every row is evaluated (not only the rows on the accepted path), so results do
+ * not depend on evaluation order; uniforms are indexed by slot for the same reason.
+ * Elementwise math in fp32 with fp64 reductions; the quantities that decide an
+ * accept test are evaluated in fp64.
+ */
+typedef struct {
+    uint32_t struct_size;
+    int32_t B;
+    int32_t N;              /* tree nodes per sequence, 1..MCSD_MAX_NODES */
+    int32_t V;              /* vocabulary, 1..MCSD_MAX_VOCAB */
+    int32_t P;              /* rows of draft_logits per sequence (rows of the tree that have children) */
+    int32_t variant;        /* MCSD_WITH_REPLACEMENT | MCSD_WITHOUT_REPLACEMENT */
+    int32_t gamma_max;      /* depth bound: row length of accepted_path; out_tokens rows have gamma_max+1 */
+    float near_tie_eps;     /* threshold of the MCSD_FLAG_NEAR_TIE_* bits, e.g. 1e-6 */
+} mcsd_verify_desc;
+
+typedef struct {
+    uint32_t struct_size;
+    const float *target_logits;  /* [B][1+N][V]   row 0 = root */
+    const float *draft_logits;   /* [B][P][V] */
+    const int32_t *q_row;        /* [1+N] row of draft_logits for each tree row, -1 for leaves */
+    const int32_t *parent;       /* [N] shared by the batch */
+    const int32_t *cand_tok;     /* [B][N] candidate token of each node */
+    const float *u_accept;       /* [B][N]   uniform in (0,1) for each node's accept test */
+    const float *u_endpoint;     /* [B][1+N] uniform in (0,1) for each row's endpoint draw */
+    const float *temperature;    /* [B], 0 = argmax sampling */
+    int32_t *n_accepted;         /* [B] out: accepted candidates, 0..gamma_max */
+    int32_t *accepted_path;      /* [B][gamma_max] out: node ids root-to-leaf, -1 padded */
+    int32_t *out_tokens;         /* [B][gamma_max+1] out: accepted tokens then the endpoint, -1 padded */
+    int32_t *acc_child;          /* [B][1+N] out: accepted child of each row or -1 */
+    int32_t *endpoint;           /* [B][1+N] out: endpoint token of each row, -1 if a child was accepted */
+    float *ratio;                /* [B][N] out, nullable: min(1, p/q) tested for each node, NaN if not reached */
+    uint32_t *flags;             /* [B][1+N] out: MCSD_FLAG_* bits */
+    float *residual_out;         /* [B][1+N][V] out, nullable (parity checks only): p_r when the loop ended */
+    void *workspace;             /* unused by this build: may be NULL when mcsd_verify_workspace_bytes is 0 */
+    size_t workspace_bytes;
+} mcsd_verify_bufs;
+
+size_t mcsd_verify_workspace_bytes(const mcsd_verify_desc *desc);
+int32_t mcsd_verify_sample(const mcsd_verify_desc *desc, const mcsd_verify_bufs *bufs, void *stream);
+
+/* One verification step: mcsd_tree_attn then mcsd_verify_sample on `stream`.
+ * Both argument sets are validated before anything is enqueued. */
+int32_t mcsd_verify_step(const mcsd_attn_desc *attn_desc, const mcsd_attn_bufs *attn_bufs,
+                         const mcsd_verify_desc *verify_desc, const mcsd_verify_bufs *verify_bufs,
+                         void *stream);
+
+/* ------------------------------------------------------------ profiling aid
+ * Not part of the verification step.  mcsd_kernel_timing(1) makes every kernel
+ * launch of the calls above be bracketed by a pair of HIP events on the launch
+ * stream (totals are reset); mcsd_kernel_timing(0) stops.  mcsd_kernel_timing_read
+ * waits for the recorded events and returns the summed duration (ms) and the number
+ * of launches of kernel `id` (0 .. mcsd_kernel_count()-1, named by mcsd_kernel_name).
+ * Events are host objects; no device memory is allocated.
+ */
+int32_t mcsd_kernel_timing(int32_t enable);
+int32_t mcsd_kernel_count(void);
+const char *mcsd_kernel_name(int32_t id);
+int32_t mcsd_kernel_timing_read(int32_t id, double *total_ms, int64_t *launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MCSD_H */

@@ -1,0 +1,262 @@
+"""ctypes binding of libmcsd.so: argument marshalling only.
+
+Every function here fills the C structs of include/mcsd.h from torch tensors
+(device pointers, shapes) and calls the entry point of the same name; all
+computation happens in the HIP kernels.  There is no fallback: if the library
+is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmcsd.so")
+
+DTYPE_FP32, DTYPE_BF16 = 0, 1
+WITH_REPLACEMENT, WITHOUT_REPLACEMENT = 0, 1
+MAX_NODES, MAX_VOCAB = 128, 32768
+
+FLAG_NEAR_TIE_ACCEPT, FLAG_NEAR_TIE_ENDPOINT, FLAG_BAD_TOKEN = 1, 2, 4
+FLAG_ZERO_DRAFT_PROB, FLAG_ZERO_RESIDUAL, FLAG_NONFINITE, FLAG_BAD_TREE = 8, 16, 32, 64
+
+EXPORTS = ["mcsd_last_error", "mcsd_version", "mcsd_tree_validate", "mcsd_attn_workspace_bytes",
+           "mcsd_tree_attn", "mcsd_verify_workspace_bytes", "mcsd_verify_sample", "mcsd_verify_step",
+           "mcsd_kernel_timing", "mcsd_kernel_count", "mcsd_kernel_name", "mcsd_kernel_timing_read"]
+
+
+class McsdError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libmcsd error {code}: {msg}")
+        self.code = code
+
+
+class AttnDesc(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("B", C.c_int32), ("N", C.c_int32), ("H_q", C.c_int32),
+                ("H_kv", C.c_int32), ("d", C.c_int32), ("dtype", C.c_int32), ("L_stride", C.c_int32),
+                ("scale", C.c_float), ("parent_per_seq", C.c_int32)]
+
+
+class AttnBufs(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("q", C.c_void_p), ("k_prefix", C.c_void_p),
+                ("v_prefix", C.c_void_p), ("prefix_len", C.c_void_p), ("k_tree", C.c_void_p),
+                ("v_tree", C.c_void_p), ("parent", C.c_void_p), ("out", C.c_void_p),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+
+
+class VerifyDesc(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("B", C.c_int32), ("N", C.c_int32), ("V", C.c_int32),
+                ("P", C.c_int32), ("variant", C.c_int32), ("gamma_max", C.c_int32),
+                ("near_tie_eps", C.c_float)]
+
+
+class VerifyBufs(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32)] + [(n, C.c_void_p) for n in (
+        "target_logits", "draft_logits", "q_row", "parent", "cand_tok", "u_accept", "u_endpoint",
+        "temperature", "n_accepted", "accepted_path", "out_tokens", "acc_child", "endpoint", "ratio",
+        "flags", "residual_out", "workspace")] + [("workspace_bytes", C.c_size_t)]
+
+
+_lib: Optional[C.CDLL] = None
+
+
+def lib() -> C.CDLL:
+    """Loads the in-tree library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2401_06706_amd.build` "
+                "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        L.mcsd_last_error.restype = C.c_char_p
+        L.mcsd_version.restype = C.c_char_p
+        L.mcsd_tree_validate.argtypes = [C.c_void_p, C.c_int32]
+        L.mcsd_tree_validate.restype = C.c_int32
+        L.mcsd_attn_workspace_bytes.argtypes = [C.POINTER(AttnDesc)]
+        L.mcsd_attn_workspace_bytes.restype = C.c_size_t
+        L.mcsd_verify_workspace_bytes.argtypes = [C.POINTER(VerifyDesc)]
+        L.mcsd_verify_workspace_bytes.restype = C.c_size_t
+        L.mcsd_tree_attn.argtypes = [C.POINTER(AttnDesc), C.POINTER(AttnBufs), C.c_void_p]
+        L.mcsd_tree_attn.restype = C.c_int32
+        L.mcsd_verify_sample.argtypes = [C.POINTER(VerifyDesc), C.POINTER(VerifyBufs), C.c_void_p]
+        L.mcsd_verify_sample.restype = C.c_int32
+        L.mcsd_verify_step.argtypes = [C.POINTER(AttnDesc), C.POINTER(AttnBufs), C.POINTER(VerifyDesc),
+                                       C.POINTER(VerifyBufs), C.c_void_p]
+        L.mcsd_verify_step.restype = C.c_int32
+        L.mcsd_kernel_timing.argtypes = [C.c_int32]
+        L.mcsd_kernel_timing.restype = C.c_int32
+        L.mcsd_kernel_count.restype = C.c_int32
+        L.mcsd_kernel_name.argtypes = [C.c_int32]
+        L.mcsd_kernel_name.restype = C.c_char_p
+        L.mcsd_kernel_timing_read.argtypes = [C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        L.mcsd_kernel_timing_read.restype = C.c_int32
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise McsdError(rc, lib().mcsd_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None, name: str = "tensor") -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream
+    return int(stream)
+
+
+def version() -> str:
+    return lib().mcsd_version().decode()
+
+
+def mcsd_tree_validate(parent_host) -> None:
+    """parent_host: int32 numpy array / CPU tensor [N]."""
+    import numpy as np
+    a = np.ascontiguousarray(parent_host, dtype=np.int32)
+    _check(lib().mcsd_tree_validate(a.ctypes.data_as(C.c_void_p), a.shape[0]))
+
+
+# ------------------------------------------------------------------ tree attention
+@dataclass
+class AttnArgs:
+    desc: AttnDesc
+    bufs: AttnBufs
+    keep: tuple       # tensors referenced by the raw pointers
+
+
+def attn_desc(B, N, H_q, H_kv, d, dtype, L_stride, scale, parent_per_seq=False) -> AttnDesc:
+    return AttnDesc(C.sizeof(AttnDesc), B, N, H_q, H_kv, d, dtype, L_stride, float(scale),
+                    1 if parent_per_seq else 0)
+
+
+def mcsd_attn_workspace_bytes(desc: AttnDesc) -> int:
+    n = lib().mcsd_attn_workspace_bytes(C.byref(desc))
+    return int(n)
+
+
+def attn_args(q, k_prefix, v_prefix, prefix_len, k_tree, v_tree, parent, out, scale,
+              workspace: Optional[torch.Tensor] = None) -> AttnArgs:
+    """Shapes: q/out [B][N][H_q][d]; k/v_prefix [B][H_kv][L_stride][d]; k/v_tree [B][H_kv][N][d];
+    prefix_len int32 [B]; parent int32 [N] or [B][N]."""
+    B, N, H_q, d = q.shape
+    H_kv, L_stride = k_prefix.shape[1], k_prefix.shape[2]
+    if q.dtype == torch.float32:
+        dt = DTYPE_FP32
+    elif q.dtype == torch.bfloat16:
+        dt = DTYPE_BF16
+    else:
+        raise ValueError(f"unsupported dtype {q.dtype}")
+    if tuple(k_prefix.shape) != (B, H_kv, L_stride, d) or tuple(v_prefix.shape) != (B, H_kv, L_stride, d):
+        raise ValueError("k_prefix / v_prefix shape mismatch")
+    if tuple(k_tree.shape) != (B, H_kv, N, d) or tuple(v_tree.shape) != (B, H_kv, N, d):
+        raise ValueError("k_tree / v_tree shape mismatch")
+    if tuple(out.shape) != (B, N, H_q, d) or tuple(prefix_len.shape) != (B,):
+        raise ValueError("out / prefix_len shape mismatch")
+    if tuple(parent.shape) not in ((N,), (B, N)):
+        raise ValueError("parent must be [N] or [B][N]")
+    desc = attn_desc(B, N, H_q, H_kv, d, dt, L_stride, scale, parent.dim() == 2)
+    bufs = AttnBufs(C.sizeof(AttnBufs), _ptr(q, q.dtype, "q"), _ptr(k_prefix, q.dtype, "k_prefix"),
+                    _ptr(v_prefix, q.dtype, "v_prefix"), _ptr(prefix_len, torch.int32, "prefix_len"),
+                    _ptr(k_tree, q.dtype, "k_tree"), _ptr(v_tree, q.dtype, "v_tree"),
+                    _ptr(parent, torch.int32, "parent"), _ptr(out, q.dtype, "out"),
+                    _ptr(workspace, None, "workspace"),
+                    0 if workspace is None else workspace.numel() * workspace.element_size())
+    return AttnArgs(desc, bufs, (q, k_prefix, v_prefix, prefix_len, k_tree, v_tree, parent, out, workspace))
+
+
+def mcsd_tree_attn(args: AttnArgs, stream=None) -> None:
+    _check(lib().mcsd_tree_attn(C.byref(args.desc), C.byref(args.bufs), _stream(stream)))
+
+
+# -------------------------------------------------------------------- verification
+@dataclass
+class VerifyArgs:
+    desc: VerifyDesc
+    bufs: VerifyBufs
+    keep: tuple
+
+
+def verify_args(target_logits, draft_logits, q_row, parent, cand_tok, u_accept, u_endpoint, temperature,
+                n_accepted, accepted_path, out_tokens, acc_child, endpoint, flags, variant: int,
+                ratio=None, residual_out=None, near_tie_eps: float = 1e-6) -> VerifyArgs:
+    """Shapes: target_logits [B][1+N][V]; draft_logits [B][P][V]; q_row int32 [1+N]; parent int32 [N];
+    cand_tok int32 [B][N]; u_accept [B][N]; u_endpoint [B][1+N]; temperature [B];
+    outputs n_accepted [B], accepted_path [B][gamma_max], out_tokens [B][gamma_max+1],
+    acc_child / endpoint / flags [B][1+N], ratio [B][N] (optional), residual_out [B][1+N][V] (optional)."""
+    B, rows, V = target_logits.shape
+    N = rows - 1
+    P = draft_logits.shape[1]
+    gamma_max = accepted_path.shape[1]
+    f32, i32 = torch.float32, torch.int32
+    shapes = [(draft_logits, (B, P, V)), (q_row, (1 + N,)), (parent, (N,)), (cand_tok, (B, N)),
+              (u_accept, (B, N)), (u_endpoint, (B, 1 + N)), (temperature, (B,)), (n_accepted, (B,)),
+              (accepted_path, (B, gamma_max)), (out_tokens, (B, gamma_max + 1)), (acc_child, (B, 1 + N)),
+              (endpoint, (B, 1 + N)), (flags, (B, 1 + N))]
+    if ratio is not None:
+        shapes.append((ratio, (B, N)))
+    if residual_out is not None:
+        shapes.append((residual_out, (B, 1 + N, V)))
+    for t, shp in shapes:
+        if tuple(t.shape) != shp:
+            raise ValueError(f"shape mismatch: got {tuple(t.shape)}, expected {shp}")
+    desc = VerifyDesc(C.sizeof(VerifyDesc), B, N, V, P, int(variant), gamma_max, float(near_tie_eps))
+    bufs = VerifyBufs(C.sizeof(VerifyBufs),
+                      _ptr(target_logits, f32, "target_logits"), _ptr(draft_logits, f32, "draft_logits"),
+                      _ptr(q_row, i32, "q_row"), _ptr(parent, i32, "parent"), _ptr(cand_tok, i32, "cand_tok"),
+                      _ptr(u_accept, f32, "u_accept"), _ptr(u_endpoint, f32, "u_endpoint"),
+                      _ptr(temperature, f32, "temperature"), _ptr(n_accepted, i32, "n_accepted"),
+                      _ptr(accepted_path, i32, "accepted_path"), _ptr(out_tokens, i32, "out_tokens"),
+                      _ptr(acc_child, i32, "acc_child"), _ptr(endpoint, i32, "endpoint"),
+                      _ptr(ratio, f32, "ratio"), _ptr(flags, i32, "flags"),
+                      _ptr(residual_out, f32, "residual_out"), None, 0)
+    return VerifyArgs(desc, bufs, (target_logits, draft_logits, q_row, parent, cand_tok, u_accept,
+                                   u_endpoint, temperature, n_accepted, accepted_path, out_tokens,
+                                   acc_child, endpoint, ratio, flags, residual_out))
+
+
+def mcsd_verify_workspace_bytes(desc: VerifyDesc) -> int:
+    return int(lib().mcsd_verify_workspace_bytes(C.byref(desc)))
+
+
+def mcsd_verify_sample(args: VerifyArgs, stream=None) -> None:
+    _check(lib().mcsd_verify_sample(C.byref(args.desc), C.byref(args.bufs), _stream(stream)))
+
+
+def mcsd_verify_step(attn: AttnArgs, verify: VerifyArgs, stream=None) -> None:
+    _check(lib().mcsd_verify_step(C.byref(attn.desc), C.byref(attn.bufs), C.byref(verify.desc),
+                                  C.byref(verify.bufs), _stream(stream)))
+
+
+# ------------------------------------------------------------------- profiling aid
+def mcsd_kernel_timing(enable: bool) -> None:
+    _check(lib().mcsd_kernel_timing(1 if enable else 0))
+
+
+def mcsd_kernel_timing_read() -> dict:
+    """{kernel name: (total ms, launches)} since timing was enabled; waits for the events."""
+    out = {}
+    L = lib()
+    for i in range(L.mcsd_kernel_count()):
+        ms, n = C.c_double(0.0), C.c_int64(0)
+        _check(L.mcsd_kernel_timing_read(i, C.byref(ms), C.byref(n)))
+        out[L.mcsd_kernel_name(i).decode()] = (ms.value, n.value)
+    return out

@@ -1,0 +1,213 @@
+// C ABI of libmcsd: argument validation, error reporting, optional per-kernel
+// event timing.  All compute happens in tree_attn.hip and verify_sample.hip.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <mutex>
+#include <vector>
+
+#include "mcsd_internal.h"
+
+namespace mcsd {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+}
+
+// ------------------------------------------------------------------ event timing
+// Off by default.  When on, every kernel launch is bracketed by a pair of events on
+// the launch stream; mcsd_kernel_timing_read waits for them and adds up durations.
+namespace {
+struct EventPair { hipEvent_t a, b; int id; };
+std::mutex g_tmutex;
+bool g_timing = false;
+std::vector<EventPair> g_pending;
+hipEvent_t g_open[K_COUNT];
+double g_total_ms[K_COUNT];
+long long g_count[K_COUNT];
+const char *const g_names[K_COUNT] = {"tree_attn_mfma", "tree_attn_generic", "tree_attn_combine",
+                                      "verify_rows", "walk"};
+}  // namespace
+
+void timing_begin(int id, hipStream_t stream)
+{
+    if (!g_timing) return;
+    std::lock_guard<std::mutex> lk(g_tmutex);
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return;
+    (void)hipEventRecord(e, stream);
+    g_open[id] = e;
+}
+
+void timing_end(int id, hipStream_t stream)
+{
+    if (!g_timing) return;
+    std::lock_guard<std::mutex> lk(g_tmutex);
+    if (!g_open[id]) return;
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return;
+    (void)hipEventRecord(e, stream);
+    g_pending.push_back({g_open[id], e, id});
+    g_open[id] = nullptr;
+}
+
+}  // namespace mcsd
+
+using namespace mcsd;
+
+extern "C" {
+
+const char *mcsd_last_error(void) { return g_err; }
+const char *mcsd_version(void) { return "libmcsd 0.1 (gfx950)"; }
+
+// Profiling aid (not part of the verification step): enable != 0 starts bracketing
+// every kernel launch with HIP events; 0 stops.  Totals are reset when enabled.
+int32_t mcsd_kernel_timing(int32_t enable)
+{
+    std::lock_guard<std::mutex> lk(g_tmutex);
+    g_timing = enable != 0;
+    if (g_timing) {
+        for (auto &p : g_pending) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+        g_pending.clear();
+        for (int i = 0; i < K_COUNT; ++i) { g_total_ms[i] = 0.0; g_count[i] = 0; g_open[i] = nullptr; }
+    }
+    return MCSD_OK;
+}
+
+int32_t mcsd_kernel_count(void) { return K_COUNT; }
+const char *mcsd_kernel_name(int32_t id) { return (id >= 0 && id < K_COUNT) ? g_names[id] : ""; }
+
+// Waits for the recorded events (synchronises with them) and returns the summed
+// duration in ms and the number of launches of kernel `id` since timing was enabled.
+int32_t mcsd_kernel_timing_read(int32_t id, double *total_ms, int64_t *launches)
+{
+    if (id < 0 || id >= K_COUNT || !total_ms || !launches) return MCSD_E_SHAPE;
+    std::lock_guard<std::mutex> lk(g_tmutex);
+    for (auto &p : g_pending) {
+        float ms = 0.f;
+        if (hipEventSynchronize(p.b) == hipSuccess && hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess) {
+            g_total_ms[p.id] += ms;
+            g_count[p.id] += 1;
+        }
+        (void)hipEventDestroy(p.a);
+        (void)hipEventDestroy(p.b);
+    }
+    g_pending.clear();
+    *total_ms = g_total_ms[id];
+    *launches = g_count[id];
+    return MCSD_OK;
+}
+
+int32_t mcsd_tree_validate(const int32_t *parent, int32_t n)
+{
+    if (!parent) { set_error("parent is NULL"); return MCSD_E_NULL; }
+    if (n < 1 || n > MCSD_MAX_NODES) { set_error("n_nodes %d outside 1..%d", n, MCSD_MAX_NODES); return MCSD_E_TREE; }
+    for (int i = 0; i < n; ++i)
+        if (parent[i] < -1 || parent[i] >= i) {
+            set_error("parent[%d] = %d violates -1 <= parent[i] < i", i, parent[i]);
+            return MCSD_E_TREE;
+        }
+    return MCSD_OK;
+}
+
+static int32_t check_attn(const mcsd_attn_desc *d, const mcsd_attn_bufs *b, AttnPlan *plan)
+{
+    if (!d) { set_error("attn desc is NULL"); return MCSD_E_NULL; }
+    if (d->struct_size != sizeof(mcsd_attn_desc)) { set_error("attn desc struct_size %u != %zu", d->struct_size, sizeof(mcsd_attn_desc)); return MCSD_E_SHAPE; }
+    if (d->B < 1 || d->H_q < 1 || d->H_kv < 1 || d->d < 1 || d->L_stride < 0) { set_error("attn: non-positive size"); return MCSD_E_SHAPE; }
+    if (d->N < 1 || d->N > MCSD_MAX_NODES) { set_error("attn: N %d outside 1..%d", d->N, MCSD_MAX_NODES); return MCSD_E_TREE; }
+    if (d->H_q % d->H_kv != 0) { set_error("attn: H_q %d not a multiple of H_kv %d", d->H_q, d->H_kv); return MCSD_E_SHAPE; }
+    if (d->dtype != MCSD_DTYPE_FP32 && d->dtype != MCSD_DTYPE_BF16) { set_error("attn: unknown dtype %d", d->dtype); return MCSD_E_UNSUPPORTED; }
+    if (d->d > MCSD_MAX_HEAD_DIM || d->d % (d->dtype == MCSD_DTYPE_BF16 ? 8 : 4) != 0) { set_error("attn: head dim %d unsupported", d->d); return MCSD_E_UNSUPPORTED; }
+    if (!(d->scale == d->scale)) { set_error("attn: scale is NaN"); return MCSD_E_SHAPE; }
+    if (!make_attn_plan(*d, plan)) { set_error("attn: no kernel for this shape"); return MCSD_E_UNSUPPORTED; }
+    if (!b) return MCSD_OK;
+    if (b->struct_size != sizeof(mcsd_attn_bufs)) { set_error("attn bufs struct_size %u != %zu", b->struct_size, sizeof(mcsd_attn_bufs)); return MCSD_E_SHAPE; }
+    if (!b->q || !b->k_tree || !b->v_tree || !b->prefix_len || !b->parent || !b->out) { set_error("attn: NULL buffer"); return MCSD_E_NULL; }
+    if (d->L_stride > 0 && (!b->k_prefix || !b->v_prefix)) { set_error("attn: NULL prefix cache"); return MCSD_E_NULL; }
+    if (plan->ws_bytes > 0) {
+        if (!b->workspace) { set_error("attn: workspace is NULL, %zu bytes needed", plan->ws_bytes); return MCSD_E_WORKSPACE; }
+        if (b->workspace_bytes < plan->ws_bytes) { set_error("attn: workspace %zu < %zu bytes", b->workspace_bytes, plan->ws_bytes); return MCSD_E_WORKSPACE; }
+        if (((uintptr_t)b->workspace & 255u) != 0) { set_error("attn: workspace not 256-byte aligned"); return MCSD_E_WORKSPACE; }
+    }
+    const uintptr_t al = (uintptr_t)b->q | (uintptr_t)b->k_prefix | (uintptr_t)b->v_prefix | (uintptr_t)b->k_tree |
+                         (uintptr_t)b->v_tree | (uintptr_t)b->out;
+    if (al & 15u) { set_error("attn: tensors must be 16-byte aligned"); return MCSD_E_SHAPE; }
+    return MCSD_OK;
+}
+
+static int32_t check_verify(const mcsd_verify_desc *d, const mcsd_verify_bufs *b)
+{
+    if (!d) { set_error("verify desc is NULL"); return MCSD_E_NULL; }
+    if (d->struct_size != sizeof(mcsd_verify_desc)) { set_error("verify desc struct_size %u != %zu", d->struct_size, sizeof(mcsd_verify_desc)); return MCSD_E_SHAPE; }
+    if (d->B < 1 || d->V < 1 || d->P < 1 || d->gamma_max < 1) { set_error("verify: non-positive size"); return MCSD_E_SHAPE; }
+    if (d->N < 1 || d->N > MCSD_MAX_NODES) { set_error("verify: N %d outside 1..%d", d->N, MCSD_MAX_NODES); return MCSD_E_TREE; }
+    if (d->P > 1 + d->N) { set_error("verify: P %d > 1+N", d->P); return MCSD_E_SHAPE; }
+    if (d->B > 65535) { set_error("verify: B %d > 65535", d->B); return MCSD_E_UNSUPPORTED; }
+    if (d->V > MCSD_MAX_VOCAB) { set_error("verify: V %d > %d", d->V, MCSD_MAX_VOCAB); return MCSD_E_UNSUPPORTED; }
+    if (d->variant != MCSD_WITH_REPLACEMENT && d->variant != MCSD_WITHOUT_REPLACEMENT) { set_error("verify: unknown variant %d", d->variant); return MCSD_E_UNSUPPORTED; }
+    if (!(d->near_tie_eps >= 0.f)) { set_error("verify: near_tie_eps must be >= 0"); return MCSD_E_SHAPE; }
+    if (!b) return MCSD_OK;
+    if (b->struct_size != sizeof(mcsd_verify_bufs)) { set_error("verify bufs struct_size %u != %zu", b->struct_size, sizeof(mcsd_verify_bufs)); return MCSD_E_SHAPE; }
+    if (!b->target_logits || !b->draft_logits || !b->q_row || !b->parent || !b->cand_tok || !b->u_accept ||
+        !b->u_endpoint || !b->temperature || !b->n_accepted || !b->accepted_path || !b->out_tokens ||
+        !b->acc_child || !b->endpoint || !b->flags) { set_error("verify: NULL buffer"); return MCSD_E_NULL; }
+    if (d->V % 4 == 0 && (((uintptr_t)b->target_logits | (uintptr_t)b->draft_logits | (uintptr_t)b->residual_out) & 15u)) {
+        set_error("verify: logit arrays must be 16-byte aligned");
+        return MCSD_E_SHAPE;
+    }
+    return MCSD_OK;
+}
+
+size_t mcsd_attn_workspace_bytes(const mcsd_attn_desc *desc)
+{
+    AttnPlan plan;
+    if (check_attn(desc, nullptr, &plan) != MCSD_OK) return 0;
+    return plan.ws_bytes;
+}
+
+size_t mcsd_verify_workspace_bytes(const mcsd_verify_desc *desc)
+{
+    (void)desc;
+    return 0;
+}
+
+int32_t mcsd_tree_attn(const mcsd_attn_desc *desc, const mcsd_attn_bufs *bufs, void *stream)
+{
+    AttnPlan plan;
+    if (!bufs) { set_error("attn bufs is NULL"); return MCSD_E_NULL; }
+    int32_t rc = check_attn(desc, bufs, &plan);
+    if (rc != MCSD_OK) return rc;
+    return launch_tree_attn(*desc, *bufs, plan, (hipStream_t)stream);
+}
+
+int32_t mcsd_verify_sample(const mcsd_verify_desc *desc, const mcsd_verify_bufs *bufs, void *stream)
+{
+    if (!bufs) { set_error("verify bufs is NULL"); return MCSD_E_NULL; }
+    int32_t rc = check_verify(desc, bufs);
+    if (rc != MCSD_OK) return rc;
+    return launch_verify(*desc, *bufs, (hipStream_t)stream);
+}
+
+int32_t mcsd_verify_step(const mcsd_attn_desc *ad, const mcsd_attn_bufs *ab, const mcsd_verify_desc *vd,
+                         const mcsd_verify_bufs *vb, void *stream)
+{
+    AttnPlan plan;
+    if (!ab || !vb) { set_error("bufs is NULL"); return MCSD_E_NULL; }
+    int32_t rc = check_attn(ad, ab, &plan);
+    if (rc != MCSD_OK) return rc;
+    rc = check_verify(vd, vb);
+    if (rc != MCSD_OK) return rc;
+    rc = launch_tree_attn(*ad, *ab, plan, (hipStream_t)stream);
+    if (rc != MCSD_OK) return rc;
+    return launch_verify(*vd, *vb, (hipStream_t)stream);
+}
+
+}  // extern "C"

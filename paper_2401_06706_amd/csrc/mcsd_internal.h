@@ -1,0 +1,41 @@
+// Internal declarations shared by the translation units of libmcsd (HIP, gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mcsd.h"
+
+namespace mcsd {
+
+// Kernel ids for the optional per-kernel event timing.
+enum KernelId { K_ATTN_MFMA = 0, K_ATTN_GENERIC = 1, K_ATTN_COMBINE = 2, K_VERIFY_ROWS = 3, K_WALK = 4, K_COUNT = 5 };
+
+void set_error(const char *fmt, ...);
+
+// Brackets a launch with events when timing is enabled (no-ops otherwise).
+void timing_begin(int kernel_id, hipStream_t stream);
+void timing_end(int kernel_id, hipStream_t stream);
+
+// ---- tree attention -------------------------------------------------------
+struct AttnPlan {
+    bool use_mfma;        // bf16, d == 128: matrix-core kernel; otherwise the generic ALU kernel
+    int rows_per_kv;      // M = N * (H_q / H_kv) query rows that share one KV head
+    int row_tile;         // query rows per workgroup (32 or 64) for the MFMA kernel
+    int n_row_tiles;
+    int tiles_prefix_max; // 32-key tiles needed for L_stride prefix keys
+    int tiles_tree;       // 32-key tiles needed for N tree keys
+    int chunk_tiles;      // 32-key tiles per workgroup
+    int n_chunks_max;     // grid extent along the key axis
+    size_t partial_stride_rows; // rows per (b, g) in the partial buffers = n_row_tiles * row_tile
+    size_t ws_bytes;
+};
+
+bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan);
+int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const AttnPlan &plan,
+                         hipStream_t stream);
+
+// ---- verification ---------------------------------------------------------
+int32_t launch_verify(const mcsd_verify_desc &d, const mcsd_verify_bufs &b, hipStream_t stream);
+
+}  // namespace mcsd

@@ -1,0 +1,623 @@
+// Tree attention (Sec. 3.3 of the paper) on gfx950.
+//
+// All candidate tokens of the draft tree are scored in one pass over the shared
+// prefix KV cache: the cache is streamed from HBM once and every tree node (times
+// the query heads that share a KV head) is a row of the same tile, which is the
+// saving the paper attributes to tree attention.  A node additionally attends to
+// its ancestors and itself among the tree's own keys; that mask is a 128-bit
+// ancestor bitmask per node held in LDS.
+//
+// Work decomposition (bf16, d = 128: tree_attn_mfma_kernel)
+//   keys of a sequence = ceil(L/32) prefix tiles followed by ceil(N/32) tree tiles
+//   workgroup (4 waves) = (sequence b, KV head g, tile of 32/64 query rows, chunk of
+//                          `chunk_tiles` consecutive key tiles)
+//   wave w takes key tiles t_begin + w, + 4, ... : every wave runs an independent
+//   online softmax over its tiles with no workgroup barrier in the main loop.
+//   S^T = K Q^T  : v_mfma_f32_16x16x32_bf16, A = K tile straight from global memory
+//                  (a lane's operand is 16 contiguous bytes of one key row),
+//                  B = Q held in registers for the whole kernel.
+//   O^T += V^T P^T: A = V tile transposed through a wave-private LDS buffer,
+//                  B = P taken from the S^T accumulators without leaving the lane.
+//   The waves' (max, sum, O) are merged through LDS; if the sequence has more than
+//   one chunk the partial goes to the workspace and tree_attn_combine_kernel merges
+//   the chunks by log-sum-exp, otherwise the output row is written directly.
+//
+// Everything else (fp32 storage, other head dims) runs tree_attn_generic_kernel on
+// the vector ALUs.
+#include <math.h>
+#include <stdlib.h>
+
+#include "mcsd_internal.h"
+
+namespace mcsd {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float LOG2E_F = 1.44269504088896340736f;
+constexpr float M_INIT = -1.0e30f;     // "no key seen yet" running max (finite so that differences stay finite)
+constexpr float RESCALE_GAP = 8.0f;    // running max is only raised when a score exceeds it by 2^8
+constexpr int KT = 32;                 // keys per tile
+constexpr int WAVES = 4;
+constexpr int OBUF_LD = 68;            // leading dimension (rows) of the merge buffer, padded
+
+struct AttnParams {
+    const void *q, *k_prefix, *v_prefix, *k_tree, *v_tree;
+    const int32_t *prefix_len, *parent;
+    void *out;
+    float *part_m, *part_l, *part_o;
+    int B, N, H_q, H_kv, G, d, L_stride, M;
+    int n_row_tiles, chunk_tiles, n_chunks_max, tiles_tree, parent_per_seq, dtype;
+    int R;                // rows per (b, g) in the partial buffers
+    float scale_log2;     // scale * log2(e)
+};
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    bf16x2 v = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16)
+{
+    return __uint_as_float(bits16 << 16);
+}
+
+// anc[i] = {i} U anc[parent[i]]: one 128-bit mask per node, built by walking up.
+__device__ __forceinline__ void build_ancestor_masks(const int32_t *parent, int N, uint32_t (*s_anc)[4])
+{
+    for (int i = threadIdx.x; i < MCSD_MAX_NODES; i += blockDim.x) {
+        uint32_t m[4] = {0u, 0u, 0u, 0u};
+        if (i < N) {
+            int a = i;
+            for (int step = 0; step < MCSD_MAX_NODES && a >= 0; ++step) {
+                m[a >> 5] |= 1u << (a & 31);
+                int pa = parent[a];
+                a = (pa < a) ? pa : -1;      // a malformed array can not loop or index out of range
+            }
+        }
+        s_anc[i][0] = m[0]; s_anc[i][1] = m[1]; s_anc[i][2] = m[2]; s_anc[i][3] = m[3];
+    }
+}
+
+// --------------------------------------------------------------------- MFMA path
+template <int MT>
+__global__ __launch_bounds__(WAVES * 64) void tree_attn_mfma_kernel(AttnParams p)
+{
+    constexpr int ROWS = 16 * MT;
+    constexpr int D = 128;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lj = lane >> 4, lc = lane & 15;
+    const int rt = blockIdx.x % p.n_row_tiles;
+    const int chunk = blockIdx.x / p.n_row_tiles;
+    const int g = blockIdx.y, b = blockIdx.z;
+
+    int L = p.prefix_len[b];
+    L = max(0, min(L, p.L_stride));
+    const int tilesP = (L + KT - 1) / KT;
+    const int total_tiles = tilesP + p.tiles_tree;
+    const int t_begin = chunk * p.chunk_tiles;
+    if (t_begin >= total_tiles) return;
+    const int t_end = min(total_tiles, t_begin + p.chunk_tiles);
+    const int n_chunks = (total_tiles + p.chunk_tiles - 1) / p.chunk_tiles;
+
+    __shared__ __attribute__((aligned(16))) uint32_t s_vt[WAVES][64 * 8 * 4];   // V transpose staging, 8 KB per wave
+    __shared__ float s_obuf[D * OBUF_LD];
+    __shared__ uint32_t s_anc[MCSD_MAX_NODES][4];
+    __shared__ float s_m[WAVES][64], s_l[WAVES][64];
+    __shared__ float s_mstar[64], s_lstar[64];
+
+    const bool has_tree = t_end > tilesP;
+    if (has_tree) {
+        build_ancestor_masks(p.parent + (p.parent_per_seq ? (size_t)b * p.N : 0), p.N, s_anc);
+        __syncthreads();
+    }
+
+    const uint16_t *qb = static_cast<const uint16_t *>(p.q);
+    const int row0 = rt * ROWS;
+
+    // Q operand: lane (lj, lc) holds Q[row0 + 16 mt + lc][32 kk + 8 lj .. +7]
+    bf16x8 qreg[MT][4];
+    int node_of[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int r = row0 + 16 * mt + lc;
+        const bool ok = r < p.M;
+        const int rr = ok ? r : p.M - 1;
+        const int node = rr / p.G, hh = rr % p.G;
+        node_of[mt] = node;
+        const uint16_t *src = qb + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + 8 * lj;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            u32x4 v = *reinterpret_cast<const u32x4 *>(src + 32 * kk);
+            if (!ok) v = (u32x4){0u, 0u, 0u, 0u};
+            qreg[mt][kk] = __builtin_bit_cast(bf16x8, v);
+        }
+    }
+
+    f32x4 oacc[8][MT];
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) oacc[nt][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float m_used[MT], l_part[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) { m_used[mt] = M_INIT; l_part[mt] = 0.f; }
+
+    const size_t kv_head = (size_t)b * p.H_kv + g;
+    const uint16_t *kpre = static_cast<const uint16_t *>(p.k_prefix) + kv_head * (size_t)p.L_stride * D;
+    const uint16_t *vpre = static_cast<const uint16_t *>(p.v_prefix) + kv_head * (size_t)p.L_stride * D;
+    const uint16_t *ktre = static_cast<const uint16_t *>(p.k_tree) + kv_head * (size_t)p.N * D;
+    const uint16_t *vtre = static_cast<const uint16_t *>(p.v_tree) + kv_head * (size_t)p.N * D;
+
+    // Tile addressing.  Rows past the end of a partial tile are clamped to its last valid
+    // row (their scores are masked below), so no load leaves the arrays.
+    auto tile_base = [&](int t, const uint16_t *&kb, const uint16_t *&vb, int &nvalid) {
+        if (t < tilesP) {
+            kb = kpre + (size_t)t * KT * D; vb = vpre + (size_t)t * KT * D;
+            nvalid = min(KT, L - t * KT);
+        } else {
+            const int tt = t - tilesP;
+            kb = ktre + (size_t)tt * KT * D; vb = vtre + (size_t)tt * KT * D;
+            nvalid = min(KT, p.N - tt * KT);
+        }
+    };
+    u32x4 kraw[2][4];
+    // K: lane (lj, lc) reads key row 16 sub + lc, 16 bytes at column 32 kk + 8 lj
+    auto load_k = [&](int t) {
+        const uint16_t *kb, *vb;
+        int nvalid;
+        tile_base(t, kb, vb, nvalid);
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const int row = min(16 * sub + lc, nvalid - 1);
+            const uint16_t *src = kb + (size_t)row * D + 8 * lj;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) kraw[sub][kk] = *reinterpret_cast<const u32x4 *>(src + 32 * kk);
+        }
+    };
+
+    uint32_t *vt = s_vt[wave];
+    int t = t_begin + wave;
+    if (t < t_end) load_k(t);
+    for (; t < t_end; t += WAVES) {
+        // this tile's K operands leave the load registers, which are refilled for the next tile;
+        // this tile's V is requested now and consumed after the scores and the softmax
+        bf16x8 kop[2][4];
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) kop[sub][kk] = __builtin_bit_cast(bf16x8, kraw[sub][kk]);
+        u32x4 vcur[8];
+        {
+            // V: lane (lj, lc) reads the 8 key rows of its k-slot group at columns 8 lc .. 8 lc + 7
+            const uint16_t *kb, *vb;
+            int nv;
+            tile_base(t, kb, vb, nv);
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                const int row = min(((s < 4) ? 0 : 16) + 4 * lj + (s & 3), nv - 1);
+                vcur[s] = *reinterpret_cast<const u32x4 *>(vb + (size_t)row * D + 8 * lc);
+            }
+        }
+        if (t + WAVES < t_end) load_k(t + WAVES);
+
+        const bool is_tree = t >= tilesP;
+        const int tt = t - tilesP;
+        const int nvalid = is_tree ? min(KT, p.N - tt * KT) : min(KT, L - t * KT);
+
+        // S^T[key][row] = sum_d K[key][d] Q[row][d]
+        f32x4 sacc[2][MT];
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[sub][kk], qreg[mt][kk], acc, 0, 0, 0);
+                sacc[sub][mt] = acc * p.scale_log2;
+            }
+        // lane (lj, lc) now holds, for row 16 mt + lc, keys 16 sub + 4 lj + i
+        if (nvalid < KT || is_tree) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const uint32_t vis = is_tree ? s_anc[node_of[mt]][tt] : 0xffffffffu;
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int key = 16 * sub + 4 * lj + i;
+                        const bool on = (key < nvalid) && ((vis >> key) & 1u);
+                        if (!on) sacc[sub][mt][i] = -INFINITY;
+                    }
+            }
+        }
+        // online softmax with a lazily raised running max
+        bool raise = false;
+        float lmax[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            float m0 = fmaxf(fmaxf(sacc[0][mt][0], sacc[0][mt][1]), fmaxf(sacc[0][mt][2], sacc[0][mt][3]));
+            float m1 = fmaxf(fmaxf(sacc[1][mt][0], sacc[1][mt][1]), fmaxf(sacc[1][mt][2], sacc[1][mt][3]));
+            lmax[mt] = fmaxf(m0, m1);
+            raise |= lmax[mt] > m_used[mt] + RESCALE_GAP;
+        }
+        if (__any(raise)) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                float rm = lmax[mt];
+                rm = fmaxf(rm, __shfl_xor(rm, 16));
+                rm = fmaxf(rm, __shfl_xor(rm, 32));
+                const float m_new = fmaxf(m_used[mt], rm);
+                const float alpha = exp2f(m_used[mt] - m_new);
+                m_used[mt] = m_new;
+                l_part[mt] *= alpha;
+#pragma unroll
+                for (int nt = 0; nt < 8; ++nt) oacc[nt][mt] *= alpha;
+            }
+        }
+        bf16x8 pop[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            float pv[8];
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) pv[4 * sub + i] = exp2f(sacc[sub][mt][i] - m_used[mt]);
+            l_part[mt] += ((pv[0] + pv[1]) + (pv[2] + pv[3])) + ((pv[4] + pv[5]) + (pv[6] + pv[7]));
+            u32x4 pk = {pack_bf16(pv[0], pv[1]), pack_bf16(pv[2], pv[3]), pack_bf16(pv[4], pv[5]), pack_bf16(pv[6], pv[7])};
+            pop[mt] = __builtin_bit_cast(bf16x8, pk);
+        }
+
+        // V tile -> V^T operands.  In-lane 8x8 transpose of 16-bit elements: the lane
+        // holds 8 key rows x 8 columns and needs, per column, the 8 keys packed.
+        // Then an exchange inside each 16-lane group through LDS: column 8 lc + e
+        // belongs to lane 8 (lc & 1) + e of the operand for d-tile lc >> 1.
+        {
+            const int nt_w = lc >> 1, cb = 8 * (lc & 1);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int w = e >> 1;
+                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+                u32x4 o;
+                o[0] = __builtin_amdgcn_perm(vcur[1][w], vcur[0][w], sel);
+                o[1] = __builtin_amdgcn_perm(vcur[3][w], vcur[2][w], sel);
+                o[2] = __builtin_amdgcn_perm(vcur[5][w], vcur[4][w], sel);
+                o[3] = __builtin_amdgcn_perm(vcur[7][w], vcur[6][w], sel);
+                const int slot = (lj * 8 + nt_w) * 16 + ((cb + e) ^ nt_w);
+                *reinterpret_cast<u32x4 *>(vt + 4 * slot) = o;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // O^T[d][row] += sum_key V[key][d] P[row][key]
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) {
+            const int slot = (lj * 8 + nt) * 16 + (lc ^ nt);
+            const bf16x8 vop = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(vt + 4 * slot));
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                oacc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pop[mt], oacc[nt][mt], 0, 0, 0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // ---- merge the four waves: (m, l) per row through LDS, O through s_obuf[d][row]
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        float lt = l_part[mt];
+        lt += __shfl_xor(lt, 16);
+        lt += __shfl_xor(lt, 32);
+        if (lj == 0) { s_m[wave][16 * mt + lc] = m_used[mt]; s_l[wave][16 * mt + lc] = lt; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int r = 16 * mt + lc;
+        const float ms = fmaxf(fmaxf(s_m[0][r], s_m[1][r]), fmaxf(s_m[2][r], s_m[3][r]));
+        const float f = exp2f(m_used[mt] - ms);
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) oacc[nt][mt] *= f;
+    }
+    if (tid < ROWS) {
+        const float ms = fmaxf(fmaxf(s_m[0][tid], s_m[1][tid]), fmaxf(s_m[2][tid], s_m[3][tid]));
+        float ls = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) ls += exp2f(s_m[w][tid] - ms) * s_l[w][tid];
+        s_mstar[tid] = ms;
+        s_lstar[tid] = ls;
+    }
+    for (int w = 0; w < WAVES; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int nt = 0; nt < 8; ++nt)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int idx = (16 * nt + 4 * lj + i) * OBUF_LD + 16 * mt + lc;
+                        if (w == 0) s_obuf[idx] = oacc[nt][mt][i];
+                        else s_obuf[idx] += oacc[nt][mt][i];
+                    }
+        }
+        __syncthreads();
+    }
+
+    const int rows_valid = min(ROWS, p.M - row0);
+    if (n_chunks == 1) {
+        // the only chunk of this sequence: normalise and write the output rows
+        uint16_t *ob = static_cast<uint16_t *>(p.out);
+        for (int idx = tid; idx < rows_valid * (D / 8); idx += WAVES * 64) {
+            const int r = idx / (D / 8), d8 = idx % (D / 8);
+            const float inv = 1.0f / s_lstar[r];
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = s_obuf[(8 * d8 + e) * OBUF_LD + r] * inv;
+            u32x4 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
+            const int gr = row0 + r, node = gr / p.G, hh = gr % p.G;
+            *reinterpret_cast<u32x4 *>(ob + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + 8 * d8) = pk;
+        }
+    } else {
+        const size_t unit = (kv_head * p.n_chunks_max + chunk) * (size_t)p.R + row0;
+        for (int idx = tid; idx < rows_valid * (D / 4); idx += WAVES * 64) {
+            const int r = idx / (D / 4), d4 = idx % (D / 4);
+            float4 v;
+            v.x = s_obuf[(4 * d4 + 0) * OBUF_LD + r];
+            v.y = s_obuf[(4 * d4 + 1) * OBUF_LD + r];
+            v.z = s_obuf[(4 * d4 + 2) * OBUF_LD + r];
+            v.w = s_obuf[(4 * d4 + 3) * OBUF_LD + r];
+            *reinterpret_cast<float4 *>(p.part_o + (unit + r) * D + 4 * d4) = v;
+        }
+        if (tid < rows_valid) {
+            p.part_m[unit + tid] = s_mstar[tid];
+            p.part_l[unit + tid] = s_lstar[tid];
+        }
+    }
+}
+
+// Merges the chunks of one sequence: out = sum_c 2^(m_c - m*) O_c / sum_c 2^(m_c - m*) l_c.
+__global__ __launch_bounds__(256) void tree_attn_combine_kernel(AttnParams p)
+{
+    constexpr int D = 128;
+    const int g = blockIdx.y, b = blockIdx.z;
+    int L = p.prefix_len[b];
+    L = max(0, min(L, p.L_stride));
+    const int total_tiles = (L + KT - 1) / KT + p.tiles_tree;
+    const int n_chunks = (total_tiles + p.chunk_tiles - 1) / p.chunk_tiles;
+    if (n_chunks <= 1) return;      // the attention kernel wrote the output itself
+    const int r = blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int d8 = threadIdx.x & 15;
+    if (r >= p.M) return;
+    const size_t kv_head = (size_t)b * p.H_kv + g;
+    const size_t base = kv_head * p.n_chunks_max * (size_t)p.R + r;
+    float ms = M_INIT;
+    for (int c = 0; c < n_chunks; ++c) ms = fmaxf(ms, p.part_m[base + (size_t)c * p.R]);
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float ls = 0.f;
+    for (int c = 0; c < n_chunks; ++c) {
+        const size_t u = base + (size_t)c * p.R;
+        const float f = exp2f(p.part_m[u] - ms);
+        ls += f * p.part_l[u];
+        const float4 a0 = *reinterpret_cast<const float4 *>(p.part_o + u * D + 8 * d8);
+        const float4 a1 = *reinterpret_cast<const float4 *>(p.part_o + u * D + 8 * d8 + 4);
+        acc[0] += f * a0.x; acc[1] += f * a0.y; acc[2] += f * a0.z; acc[3] += f * a0.w;
+        acc[4] += f * a1.x; acc[5] += f * a1.y; acc[6] += f * a1.z; acc[7] += f * a1.w;
+    }
+    const float inv = 1.0f / ls;
+    u32x4 pk = {pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv),
+                pack_bf16(acc[4] * inv, acc[5] * inv), pack_bf16(acc[6] * inv, acc[7] * inv)};
+    const int node = r / p.G, hh = r % p.G;
+    uint16_t *ob = static_cast<uint16_t *>(p.out);
+    *reinterpret_cast<u32x4 *>(ob + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + 8 * d8) = pk;
+}
+
+// ------------------------------------------------------------------ generic path
+// One 256-thread workgroup per (sequence, node, query head).  Keys are taken 256 at
+// a time: thread t scores key t (dot product over d on the vector ALU), the running
+// max is a wavefront-shuffle + LDS reduction, the weights go to LDS, and thread t
+// (t < d) accumulates output column t over the 256 keys.
+template <typename T>
+__device__ __forceinline__ float load_as_float(const T *p, size_t i);
+template <>
+__device__ __forceinline__ float load_as_float<float>(const float *p, size_t i) { return p[i]; }
+template <>
+__device__ __forceinline__ float load_as_float<uint16_t>(const uint16_t *p, size_t i) { return bf16_bits_to_float(p[i]); }
+
+template <typename T>
+__device__ __forceinline__ void store_from_float(T *p, size_t i, float v);
+template <>
+__device__ __forceinline__ void store_from_float<float>(float *p, size_t i, float v) { p[i] = v; }
+template <>
+__device__ __forceinline__ void store_from_float<uint16_t>(uint16_t *p, size_t i, float v)
+{
+    p[i] = (uint16_t)(pack_bf16(v, 0.f) & 0xffffu);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void tree_attn_generic_kernel(AttnParams p)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int h = blockIdx.x, node = blockIdx.y, b = blockIdx.z;
+    const int g = h / p.G, d = p.d;
+    __shared__ float s_q[MCSD_MAX_HEAD_DIM];
+    __shared__ float s_p[256];
+    __shared__ float s_red[4];
+    __shared__ uint32_t s_anc[MCSD_MAX_NODES][4];
+
+    build_ancestor_masks(p.parent + (p.parent_per_seq ? (size_t)b * p.N : 0), p.N, s_anc);
+    const T *qp = static_cast<const T *>(p.q) + (((size_t)b * p.N + node) * p.H_q + h) * (size_t)d;
+    for (int c = tid; c < d; c += 256) s_q[c] = load_as_float<T>(qp, c);
+    __syncthreads();
+
+    int L = p.prefix_len[b];
+    L = max(0, min(L, p.L_stride));
+    const size_t kv_head = (size_t)b * p.H_kv + g;
+    const T *kpre = static_cast<const T *>(p.k_prefix) + kv_head * (size_t)p.L_stride * d;
+    const T *vpre = static_cast<const T *>(p.v_prefix) + kv_head * (size_t)p.L_stride * d;
+    const T *ktre = static_cast<const T *>(p.k_tree) + kv_head * (size_t)p.N * d;
+    const T *vtre = static_cast<const T *>(p.v_tree) + kv_head * (size_t)p.N * d;
+    const int n_keys = L + p.N;
+
+    float m_run = M_INIT, l_run = 0.f, o_acc = 0.f;      // o_acc: output column tid (tid < d)
+    for (int k0 = 0; k0 < n_keys; k0 += 256) {
+        const int key = k0 + tid;
+        float s = -INFINITY;
+        if (key < n_keys) {
+            bool on = true;
+            const T *kr;
+            if (key < L) kr = kpre + (size_t)key * d;
+            else {
+                const int a = key - L;
+                on = (s_anc[node][a >> 5] >> (a & 31)) & 1u;
+                kr = ktre + (size_t)a * d;
+            }
+            if (on) {
+                float acc = 0.f;
+                for (int c = 0; c < d; ++c) acc += s_q[c] * load_as_float<T>(kr, c);
+                s = acc * p.scale_log2;
+            }
+        }
+        float cm = s;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) cm = fmaxf(cm, __shfl_xor(cm, o));
+        if (lane == 0) s_red[wave] = cm;
+        __syncthreads();
+        cm = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+        const float m_new = fmaxf(m_run, cm);
+        const float alpha = exp2f(m_run - m_new);
+        const float pw = exp2f(s - m_new);          // 0 for masked / out-of-range keys
+        s_p[tid] = pw;
+        __syncthreads();
+        float ps = 0.f;
+        const int cnt = min(256, n_keys - k0);
+        if (tid < d) {
+            float acc = 0.f;
+            for (int j = 0; j < cnt; ++j) {
+                const int kj = k0 + j;
+                const T *vr = (kj < L) ? vpre + (size_t)kj * d : vtre + (size_t)(kj - L) * d;
+                acc += s_p[j] * load_as_float<T>(vr, tid);
+            }
+            o_acc = o_acc * alpha + acc;
+        }
+        for (int j = 0; j < cnt; ++j) ps += s_p[j];
+        l_run = l_run * alpha + ps;
+        m_run = m_new;
+        __syncthreads();
+    }
+    if (tid < d) {
+        T *op = static_cast<T *>(p.out) + (((size_t)b * p.N + node) * p.H_q + h) * (size_t)d;
+        store_from_float<T>(op, tid, o_acc / l_run);
+    }
+}
+
+int env_int(const char *name, int dflt)
+{
+    const char *s = getenv(name);
+    if (!s || !*s) return dflt;
+    int v = atoi(s);
+    return v > 0 ? v : dflt;
+}
+
+}  // namespace
+
+bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
+{
+    AttnPlan pl = {};
+    const int G = d.H_q / d.H_kv;
+    pl.rows_per_kv = d.N * G;
+    pl.use_mfma = (d.dtype == MCSD_DTYPE_BF16 && d.d == 128);
+    if (!pl.use_mfma) {
+        if (d.d > MCSD_MAX_HEAD_DIM) return false;
+        pl.ws_bytes = 0;
+        *plan = pl;
+        return true;
+    }
+    pl.row_tile = pl.rows_per_kv <= 32 ? 32 : 64;
+    pl.n_row_tiles = (pl.rows_per_kv + pl.row_tile - 1) / pl.row_tile;
+    pl.tiles_prefix_max = (d.L_stride + KT - 1) / KT;
+    pl.tiles_tree = (d.N + KT - 1) / KT;
+    const long total_max = pl.tiles_prefix_max + pl.tiles_tree;
+    const long units = (long)d.B * d.H_kv * pl.n_row_tiles;
+    // Chunk length: enough workgroups to cover the 256 CUs several times over, but no
+    // shorter than one tile per wave; long chunks keep the partial-result traffic
+    // (one [rows][d] fp32 block per workgroup) small against the KV bytes streamed.
+    const long target_wgs = env_int("MCSD_ATTN_TARGET_WGS", 2048);
+    long chunk = (total_max * units + target_wgs - 1) / target_wgs;
+    chunk = ((chunk + WAVES - 1) / WAVES) * WAVES;
+    if (chunk < WAVES) chunk = WAVES;
+    const int forced = env_int("MCSD_ATTN_CHUNK_TILES", 0);
+    if (forced > 0) chunk = forced;
+    if (chunk > total_max) chunk = total_max;
+    pl.chunk_tiles = (int)chunk;
+    pl.n_chunks_max = (int)((total_max + chunk - 1) / chunk);
+    pl.partial_stride_rows = (size_t)pl.n_row_tiles * pl.row_tile;
+    if (pl.n_chunks_max > 1) {
+        size_t elems = (size_t)d.B * d.H_kv * pl.n_chunks_max * pl.partial_stride_rows * (size_t)(d.d + 2);
+        pl.ws_bytes = (elems * sizeof(float) + 255) & ~(size_t)255;
+    } else {
+        pl.ws_bytes = 0;
+    }
+    if ((long)pl.n_chunks_max * pl.n_row_tiles > 2147483647L || d.H_kv > 65535 || d.B > 65535) return false;
+    *plan = pl;
+    return true;
+}
+
+int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const AttnPlan &plan,
+                         hipStream_t stream)
+{
+    AttnParams p = {};
+    p.q = b.q; p.k_prefix = b.k_prefix; p.v_prefix = b.v_prefix; p.k_tree = b.k_tree; p.v_tree = b.v_tree;
+    p.prefix_len = b.prefix_len; p.parent = b.parent; p.out = b.out;
+    p.B = d.B; p.N = d.N; p.H_q = d.H_q; p.H_kv = d.H_kv; p.G = d.H_q / d.H_kv; p.d = d.d;
+    p.L_stride = d.L_stride; p.M = plan.rows_per_kv; p.parent_per_seq = d.parent_per_seq; p.dtype = d.dtype;
+    p.scale_log2 = d.scale * LOG2E_F;
+    hipError_t e;
+    if (!plan.use_mfma) {
+        if (d.H_q > 2147483647 || d.N > 65535 || d.B > 65535) { set_error("attn: grid too large"); return MCSD_E_UNSUPPORTED; }
+        dim3 grid(d.H_q, d.N, d.B), block(256);
+        timing_begin(K_ATTN_GENERIC, stream);
+        if (d.dtype == MCSD_DTYPE_FP32)
+            hipLaunchKernelGGL(tree_attn_generic_kernel<float>, grid, block, 0, stream, p);
+        else
+            hipLaunchKernelGGL(tree_attn_generic_kernel<uint16_t>, grid, block, 0, stream, p);
+        timing_end(K_ATTN_GENERIC, stream);
+        e = hipGetLastError();
+        if (e != hipSuccess) { set_error("tree_attn_generic launch failed: %s", hipGetErrorString(e)); return MCSD_E_HIP; }
+        return MCSD_OK;
+    }
+    p.n_row_tiles = plan.n_row_tiles; p.chunk_tiles = plan.chunk_tiles; p.n_chunks_max = plan.n_chunks_max;
+    p.tiles_tree = plan.tiles_tree; p.R = (int)plan.partial_stride_rows;
+    if (plan.ws_bytes > 0) {
+        const size_t rows = (size_t)d.B * d.H_kv * plan.n_chunks_max * plan.partial_stride_rows;
+        float *ws = static_cast<float *>(b.workspace);
+        p.part_o = ws;
+        p.part_m = ws + rows * d.d;
+        p.part_l = p.part_m + rows;
+    }
+    dim3 grid(plan.n_chunks_max * plan.n_row_tiles, d.H_kv, d.B), block(WAVES * 64);
+    timing_begin(K_ATTN_MFMA, stream);
+    if (plan.row_tile == 32)
+        hipLaunchKernelGGL(tree_attn_mfma_kernel<2>, grid, block, 0, stream, p);
+    else
+        hipLaunchKernelGGL(tree_attn_mfma_kernel<4>, grid, block, 0, stream, p);
+    timing_end(K_ATTN_MFMA, stream);
+    e = hipGetLastError();
+    if (e != hipSuccess) { set_error("tree_attn_mfma launch failed: %s", hipGetErrorString(e)); return MCSD_E_HIP; }
+    if (plan.n_chunks_max > 1) {
+        dim3 cgrid((plan.rows_per_kv + 15) / 16, d.H_kv, d.B);
+        timing_begin(K_ATTN_COMBINE, stream);
+        hipLaunchKernelGGL(tree_attn_combine_kernel, cgrid, dim3(256), 0, stream, p);
+        timing_end(K_ATTN_COMBINE, stream);
+        e = hipGetLastError();
+        if (e != hipSuccess) { set_error("tree_attn_combine launch failed: %s", hipGetErrorString(e)); return MCSD_E_HIP; }
+    }
+    return MCSD_OK;
+}
+
+}  // namespace mcsd

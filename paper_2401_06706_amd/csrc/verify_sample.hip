@@ -1,0 +1,555 @@
+// Multi-candidate speculative sampling on gfx950: Algorithm 1 (with replacement),
+// Algorithm 2 (without replacement), the endpoint draws and the root-to-leaf walk.
+//
+// One 1024-thread workgroup owns one row of the tree (the root or a node).  Both
+// logit rows of that node are read from HBM exactly once with 128-bit loads and
+// stay in registers for all k sequential accept/reject rounds; every round is one
+// elementwise pass over the resident data plus one block reduction.
+//
+// Instead of renormalising after each rejection the kernel carries an
+// unnormalised residual a(x) and its sum A (p-hat = a / A), and the unnormalised
+// draft weights e_q(x) with the running mass Z_q of the tokens not yet removed
+// (q-bar = e_q / Z_q).  Algorithm 1/2's update p := max(0, p - q) / sum(...) then
+// reads a := max(0, a - (A / Z_q) e_q), A := sum a, and the normaliser the paper
+// divides by (the probability of the rejection, Appendix A) is A_new / A_old.
+//
+// The handful of numbers that decide an accept test - a(x), e_q(x) at the k
+// candidate tokens - are tracked separately in fp64 by one thread per candidate,
+// so that the comparison u <= min(1, p/q) is taken at far better than the 1e-6
+// near-tie band; vocabulary-wide passes are fp32 with fp64 accumulation.
+#include <math.h>
+
+#include "mcsd_internal.h"
+
+namespace mcsd {
+namespace {
+
+constexpr int VT = 1024;           // threads per workgroup
+constexpr int NWAVES = VT / 64;
+constexpr float LOG2E_F = 1.44269504088896340736f;
+
+struct VerifyParams {
+    int B, N, V, P, variant, gamma_max;
+    float eps;
+    const float *target_logits, *draft_logits;
+    const int32_t *q_row, *parent, *cand_tok;
+    const float *u_accept, *u_endpoint, *temperature;
+    int32_t *n_accepted, *accepted_path, *out_tokens, *acc_child, *endpoint;
+    float *ratio;
+    uint32_t *flags;
+    float *residual_out;
+};
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// Every thread returns the same value (fixed summation order over the waves).
+__device__ __forceinline__ double block_sum(double v, double *s_red)
+{
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double r = 0.0;
+#pragma unroll
+    for (int w = 0; w < NWAVES; ++w) r += s_red[w];
+    __syncthreads();
+    return r;
+}
+
+// Two sums in one pass (same barriers): a -> first, b -> second.
+__device__ __forceinline__ void block_sum2(double &a, double &b, double *s_red, double *s_red2)
+{
+    a = wave_sum(a);
+    b = wave_sum(b);
+    if ((threadIdx.x & 63) == 0) { s_red[threadIdx.x >> 6] = a; s_red2[threadIdx.x >> 6] = b; }
+    __syncthreads();
+    double ra = 0.0, rb = 0.0;
+#pragma unroll
+    for (int w = 0; w < NWAVES; ++w) { ra += s_red[w]; rb += s_red2[w]; }
+    __syncthreads();
+    a = ra;
+    b = rb;
+}
+
+__device__ __forceinline__ float block_max(float v, float *s_red)
+{
+    v = wave_max(v);
+    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = s_red[0];
+#pragma unroll
+    for (int w = 1; w < NWAVES; ++w) r = fmaxf(r, s_red[w]);
+    __syncthreads();
+    return r;
+}
+
+template <int ITEMS, bool ALIGNED>
+__device__ __forceinline__ void load_row(const float *z, int V, float4 (&r)[ITEMS])
+{
+    const float ninf = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        int e = 4 * (threadIdx.x + VT * i);
+        if (ALIGNED) {
+            r[i] = (e < V) ? *reinterpret_cast<const float4 *>(z + e) : make_float4(ninf, ninf, ninf, ninf);
+        } else {
+            r[i].x = (e + 0 < V) ? z[e + 0] : ninf;
+            r[i].y = (e + 1 < V) ? z[e + 1] : ninf;
+            r[i].z = (e + 2 < V) ? z[e + 2] : ninf;
+            r[i].w = (e + 3 < V) ? z[e + 3] : ninf;
+        }
+    }
+}
+
+template <int ITEMS>
+__device__ __forceinline__ float row_max(const float4 (&r)[ITEMS])
+{
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) m = fmaxf(fmaxf(m, fmaxf(r[i].x, r[i].y)), fmaxf(r[i].z, r[i].w));
+    return m;
+}
+
+// r := exp((r - m) / T), returns this thread's partial sum in fp64.
+template <int ITEMS>
+__device__ __forceinline__ double row_exp(float4 (&r)[ITEMS], float m, float c)
+{
+    double s = 0.0;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        r[i].x = exp2f((r[i].x - m) * c);
+        r[i].y = exp2f((r[i].y - m) * c);
+        r[i].z = exp2f((r[i].z - m) * c);
+        r[i].w = exp2f((r[i].w - m) * c);
+        s += ((double)r[i].x + (double)r[i].y) + ((double)r[i].z + (double)r[i].w);
+    }
+    return s;
+}
+
+template <int ITEMS, bool ALIGNED>
+__device__ __forceinline__ void store_row_scaled(float *dst, int V, const float4 (&r)[ITEMS], float s)
+{
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        int e = 4 * (threadIdx.x + VT * i);
+        float4 v = make_float4(r[i].x * s, r[i].y * s, r[i].z * s, r[i].w * s);
+        if (ALIGNED) {
+            if (e < V) *reinterpret_cast<float4 *>(dst + e) = v;
+        } else {
+            if (e + 0 < V) dst[e + 0] = v.x;
+            if (e + 1 < V) dst[e + 1] = v.y;
+            if (e + 2 < V) dst[e + 2] = v.z;
+            if (e + 3 < V) dst[e + 3] = v.w;
+        }
+    }
+}
+
+// Inverse CDF of the unnormalised weights a (sum A) at u: the smallest token id x
+// with sum_{y <= x} a(y) > u * A, found by a two-level search: (1) totals of the
+// ITEMS contiguous 4096-token segments, (2) a block-wide inclusive scan inside
+// the segment that holds the crossing.  fp64 throughout.
+template <int ITEMS>
+__device__ __forceinline__ int inverse_cdf(const float4 (&a)[ITEMS], double A, double u, double eps,
+                                           double *s_red, double *s_seg, int *s_int, uint32_t *flag_bits)
+{
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const double tau = u * A;
+    double seg[ITEMS];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        seg[i] = ((double)a[i].x + (double)a[i].y) + ((double)a[i].z + (double)a[i].w);
+        double w = wave_sum(seg[i]);
+        if (lane == 0) s_seg[wave * ITEMS + i] = w;
+    }
+    if (t == 0) { s_int[0] = 0x7fffffff; s_int[1] = -1; }
+    __syncthreads();
+    int istar = -1;
+    double base = 0.0;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        double tot = 0.0;
+#pragma unroll
+        for (int w = 0; w < NWAVES; ++w) tot += s_seg[w * ITEMS + i];
+        if (istar < 0) {
+            if (base + tot > tau) istar = i;
+            else base += tot;
+        }
+    }
+    if (istar >= 0) {
+        double s = 0.0;
+        float4 mine = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i)
+            if (i == istar) { s = seg[i]; mine = a[i]; }
+        double incl = s;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            double n = __shfl_up(incl, o);
+            if (lane >= o) incl += n;
+        }
+        if (lane == 63) s_red[wave] = incl;
+        __syncthreads();
+        double woff = base;
+        for (int w = 0; w < wave; ++w) woff += s_red[w];
+        __syncthreads();
+        const double cum_hi = woff + incl;              // inclusive running sum up to this thread's 4 tokens
+        if (lane == 63) s_red[wave] = cum_hi;
+        __syncthreads();
+        double cum_lo = __shfl_up(cum_hi, 1);            // the neighbour's inclusive value, bit for bit
+        if (lane == 0) cum_lo = (wave == 0) ? base : s_red[wave - 1];
+        if (cum_hi > tau && !(cum_lo > tau)) {
+            const float v[4] = {mine.x, mine.y, mine.z, mine.w};
+            double cum = cum_lo, lo = cum_lo, hi = cum_hi;
+            int pick = -1, last_pos = -1;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                double nxt = cum + (double)v[e];
+                if (v[e] > 0.f) last_pos = e;
+                if (pick < 0 && nxt > tau) { pick = e; lo = cum; hi = nxt; }
+                cum = nxt;
+            }
+            if (pick < 0) pick = last_pos < 0 ? 3 : last_pos;
+            int token = 4 * (t + VT * istar) + pick;
+            atomicMin(&s_int[0], token);
+            if (fabs(tau - lo) < eps * A || fabs(hi - tau) < eps * A) atomicOr(flag_bits, (uint32_t)MCSD_FLAG_NEAR_TIE_ENDPOINT);
+        }
+    }
+    __syncthreads();
+    int token = s_int[0];
+    if (token == 0x7fffffff) {
+        // rounding left no crossing: the last token that carries mass
+        int best = -1;
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            int e = 4 * (t + VT * i);
+            if (a[i].x > 0.f) best = max(best, e);
+            if (a[i].y > 0.f) best = max(best, e + 1);
+            if (a[i].z > 0.f) best = max(best, e + 2);
+            if (a[i].w > 0.f) best = max(best, e + 3);
+        }
+        if (best >= 0) atomicMax(&s_int[1], best);
+        if (t == 0) atomicOr(flag_bits, (uint32_t)MCSD_FLAG_NEAR_TIE_ENDPOINT);
+        __syncthreads();
+        token = s_int[1];
+    }
+    __syncthreads();
+    return token;
+}
+
+template <int ITEMS, bool ALIGNED>
+__global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
+{
+    const int row = blockIdx.x, b = blockIdx.y;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int N = p.N, V = p.V;
+
+    __shared__ double s_red[NWAVES];
+    __shared__ double s_red2[NWAVES];
+    __shared__ double s_seg[NWAVES * ITEMS];
+    __shared__ float s_redf[NWAVES];
+    __shared__ unsigned long long s_mask[2];
+    __shared__ int s_kids[MCSD_MAX_NODES];
+    __shared__ int s_k;
+    __shared__ int s_int[4];
+    __shared__ uint32_t s_flags;
+    __shared__ int s_accept;       // decision of the current round
+    __shared__ int s_xrem;         // token removed from q after a rejection (-1: none)
+    __shared__ float s_bestv[NWAVES];
+    __shared__ int s_besti[NWAVES];
+
+    // children of this row, ascending node id = sampling order
+    if (t < 128) {
+        bool f = (t < N) && (p.parent[t] == row - 1);
+        unsigned long long m = __ballot(f);
+        if (lane == 0) s_mask[wave] = m;
+    }
+    if (t == 0) s_flags = 0u;
+    __syncthreads();
+    if (t == 0) {
+        int k = 0;
+        for (int w = 0; w < 2; ++w) {
+            unsigned long long m = s_mask[w];
+            while (m) {
+                s_kids[k++] = w * 64 + (__ffsll((long long)m) - 1);
+                m &= m - 1;
+            }
+        }
+        s_k = k;
+    }
+    __syncthreads();
+    int k = s_k;
+    if (k > 0) {
+        // a row with children needs a draft row; a bad map is reported, never dereferenced
+        const int qr = p.q_row[row];
+        if (qr < 0 || qr >= p.P) {
+            k = 0;
+            if (t == 0) atomicOr(&s_flags, (uint32_t)MCSD_FLAG_BAD_TREE);
+        }
+    }
+    const size_t rix = (size_t)b * (1 + N) + row;
+    const float T = p.temperature[b];
+    const float *zp_row = p.target_logits + rix * (size_t)V;
+    const float NaN = __int_as_float(0x7fc00000);
+
+    float4 a[ITEMS];
+    load_row<ITEMS, ALIGNED>(zp_row, V, a);
+
+    if (T == 0.f) {
+        // argmax sampling: lowest id on ties
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            int e = 4 * (t + VT * i);
+            const float v[4] = {a[i].x, a[i].y, a[i].z, a[i].w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (e + c < V && (v[c] > bv || (v[c] == bv && e + c < bi))) { bv = v[c]; bi = e + c; }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            float ov = __shfl_xor(bv, o);
+            int oi = __shfl_xor(bi, o);
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        }
+        if (lane == 0) { s_bestv[wave] = bv; s_besti[wave] = bi; }
+        __syncthreads();
+        bv = s_bestv[0]; bi = s_besti[0];
+        for (int w = 1; w < NWAVES; ++w)
+            if (s_bestv[w] > bv || (s_bestv[w] == bv && s_besti[w] < bi)) { bv = s_bestv[w]; bi = s_besti[w]; }
+        if (bi == 0x7fffffff) bi = 0;
+        if (t == 0) {
+            int acc = -1;
+            for (int i = 0; i < k && acc < 0; ++i)
+                if (p.cand_tok[(size_t)b * N + s_kids[i]] == bi) acc = s_kids[i];
+            p.acc_child[rix] = acc;
+            p.endpoint[rix] = acc < 0 ? bi : -1;
+            p.flags[rix] = s_flags;
+        }
+        if (p.ratio && t < k) p.ratio[(size_t)b * N + s_kids[t]] = NaN;
+        if (p.residual_out) {
+            float *dst = p.residual_out + rix * (size_t)V;
+            for (int e = t; e < V; e += VT) dst[e] = (e == bi) ? 1.f : 0.f;
+        }
+        return;
+    }
+
+    const float invT = 1.0f / T;
+    const float c2 = invT * LOG2E_F;
+    const float mp = block_max(row_max<ITEMS>(a), s_redf);
+    double A = block_sum(row_exp<ITEMS>(a, mp, c2), s_red);       // a = e_p, A = Z_p
+    if (!(A > 0.0) || !isfinite(A)) {
+        if (t == 0) atomicOr(&s_flags, (uint32_t)MCSD_FLAG_NONFINITE);
+    }
+
+    int accepted = -1;
+    if (k > 0) {
+        float4 eq[ITEMS];
+        const float *zq_row = p.draft_logits + ((size_t)b * p.P + p.q_row[row]) * (size_t)V;
+        load_row<ITEMS, ALIGNED>(zq_row, V, eq);
+        const float mq = block_max(row_max<ITEMS>(eq), s_redf);
+        const double Zq0 = block_sum(row_exp<ITEMS>(eq, mq, c2), s_red);
+        if (!(Zq0 > 0.0) || !isfinite(Zq0)) {
+            if (t == 0) atomicOr(&s_flags, (uint32_t)MCSD_FLAG_NONFINITE);
+        }
+        // fp64 track of the candidate tokens: thread c follows candidate c
+        int my_tok = -1;
+        double my_a = 0.0, my_q = 0.0;
+        float my_u = 0.f;
+        if (t < k) {
+            const int node = s_kids[t];
+            my_tok = p.cand_tok[(size_t)b * N + node];
+            my_u = p.u_accept[(size_t)b * N + node];
+            if (my_tok >= 0 && my_tok < V) {
+                my_a = exp(((double)zp_row[my_tok] - (double)mp) * (double)invT);
+                my_q = exp(((double)zq_row[my_tok] - (double)mq) * (double)invT);
+            }
+        }
+        // Z_q: mass of the draft tokens not yet removed.  After a removal it is summed
+        // again over the resident row rather than updated by subtraction, so that it
+        // keeps its relative accuracy when most of the mass has been removed.
+        double Zq = Zq0;
+
+        for (int i = 0; i < k; ++i) {
+            if (t == i) {
+                double ratio;
+                uint32_t fl = 0u;
+                const bool valid = (my_tok >= 0 && my_tok < V);
+                if (!valid) {
+                    ratio = 0.0;
+                    fl |= MCSD_FLAG_BAD_TOKEN;
+                } else if (my_q > 0.0) {
+                    ratio = (my_a * Zq) / (A * my_q);
+                    if (!(ratio < 1.0)) ratio = 1.0;
+                } else {
+                    ratio = my_a > 0.0 ? 1.0 : 0.0;
+                    fl |= MCSD_FLAG_ZERO_DRAFT_PROB;
+                }
+                const double u = (double)my_u;
+                const bool acc = (u <= ratio);
+                if (fabs(u - ratio) < (double)p.eps) fl |= MCSD_FLAG_NEAR_TIE_ACCEPT;
+                if (fl) atomicOr(&s_flags, fl);
+                if (p.ratio) p.ratio[(size_t)b * N + s_kids[i]] = (float)ratio;
+                s_accept = acc ? 1 : 0;
+                const bool remove = (!acc) && valid && (p.variant == MCSD_WITHOUT_REPLACEMENT);
+                s_xrem = remove ? my_tok : -1;
+            }
+            __syncthreads();
+            if (s_accept) {
+                accepted = i;
+                break;
+            }
+            // rejected: a := max(0, a - beta e_q) with beta = A / Z_q in fp64, applied as a
+            // two-term float product so that no common rounding of beta biases the sum
+            const double beta = (Zq > 0.0) ? A / Zq : 0.0;   // nothing left in q: the residual is p itself
+            const int xrem = s_xrem;
+            const float bh = (float)beta;
+            const float bl = (float)(beta - (double)bh);
+            double part = 0.0, partq = 0.0;
+#pragma unroll
+            for (int j = 0; j < ITEMS; ++j) {
+                a[j].x = fmaxf(0.f, fmaf(-bl, eq[j].x, fmaf(-bh, eq[j].x, a[j].x)));
+                a[j].y = fmaxf(0.f, fmaf(-bl, eq[j].y, fmaf(-bh, eq[j].y, a[j].y)));
+                a[j].z = fmaxf(0.f, fmaf(-bl, eq[j].z, fmaf(-bh, eq[j].z, a[j].z)));
+                a[j].w = fmaxf(0.f, fmaf(-bl, eq[j].w, fmaf(-bh, eq[j].w, a[j].w)));
+                part += ((double)a[j].x + (double)a[j].y) + ((double)a[j].z + (double)a[j].w);
+            }
+            if (t < k) {
+                my_a = fmax(0.0, my_a - beta * my_q);
+                if (xrem >= 0 && my_tok == xrem) my_q = 0.0;
+            }
+            if (xrem >= 0) {
+                const int q4 = xrem >> 2;                 // float4 index of the removed token
+                if ((q4 & (VT - 1)) == t) {
+                    const int j = q4 / VT, c = xrem & 3;
+#pragma unroll
+                    for (int jj = 0; jj < ITEMS; ++jj)
+                        if (jj == j) {
+                            if (c == 0) eq[jj].x = 0.f;
+                            if (c == 1) eq[jj].y = 0.f;
+                            if (c == 2) eq[jj].z = 0.f;
+                            if (c == 3) eq[jj].w = 0.f;
+                        }
+                }
+#pragma unroll
+                for (int j = 0; j < ITEMS; ++j)
+                    partq += ((double)eq[j].x + (double)eq[j].y) + ((double)eq[j].z + (double)eq[j].w);
+                block_sum2(part, partq, s_red, s_red2);   // barriers inside also order the reuse of s_accept / s_xrem
+                A = part;
+                Zq = partq;
+            } else {
+                A = block_sum(part, s_red);
+            }
+            if (!(A > 0.0)) {
+                if (t == 0) atomicOr(&s_flags, (uint32_t)MCSD_FLAG_ZERO_RESIDUAL);
+            }
+        }
+        // candidates after the accepted one were never tested
+        if (p.ratio && accepted >= 0 && t > accepted && t < k) p.ratio[(size_t)b * N + s_kids[t]] = NaN;
+    }
+
+    int endpoint = -1;
+    if (accepted < 0) {
+        const double u = (double)p.u_endpoint[rix];
+        endpoint = inverse_cdf<ITEMS>(a, A, u, (double)p.eps, s_red, s_seg, s_int, &s_flags);
+        if (endpoint < 0 || endpoint >= V) endpoint = V - 1;
+    }
+    if (p.residual_out) {
+        const float inv = (A > 0.0) ? (float)(1.0 / A) : 0.f;
+        store_row_scaled<ITEMS, ALIGNED>(p.residual_out + rix * (size_t)V, V, a, inv);
+    }
+    __syncthreads();
+    if (t == 0) {
+        p.acc_child[rix] = accepted >= 0 ? s_kids[accepted] : -1;
+        p.endpoint[rix] = endpoint;
+        p.flags[rix] = s_flags;
+    }
+}
+
+// Sec. 3: walk from the root; an accepted child moves down one level, otherwise
+// (or at a leaf) the row's endpoint closes the block.
+__global__ void walk_kernel(VerifyParams p)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= p.B) return;
+    const int N = p.N, G = p.gamma_max;
+    int32_t *path = p.accepted_path + (size_t)b * G;
+    int32_t *out = p.out_tokens + (size_t)b * (G + 1);
+    for (int i = 0; i < G; ++i) path[i] = -1;
+    for (int i = 0; i <= G; ++i) out[i] = -1;
+    int row = 0, n = 0;
+    for (;;) {
+        const size_t rix = (size_t)b * (1 + N) + row;
+        const int c = p.acc_child[rix];
+        if (c < 0 || c >= N || n >= G) {
+            out[n] = p.endpoint[rix];
+            break;
+        }
+        path[n] = c;
+        out[n] = p.cand_tok[(size_t)b * N + c];
+        ++n;
+        row = 1 + c;
+    }
+    p.n_accepted[b] = n;
+}
+
+template <int ITEMS>
+void launch_rows(const VerifyParams &p, hipStream_t stream)
+{
+    dim3 grid(1 + p.N, p.B), block(VT);
+    if (p.V % 4 == 0)
+        hipLaunchKernelGGL((verify_rows_kernel<ITEMS, true>), grid, block, 0, stream, p);
+    else
+        hipLaunchKernelGGL((verify_rows_kernel<ITEMS, false>), grid, block, 0, stream, p);
+}
+
+}  // namespace
+
+int32_t launch_verify(const mcsd_verify_desc &d, const mcsd_verify_bufs &b, hipStream_t stream)
+{
+    VerifyParams p;
+    p.B = d.B; p.N = d.N; p.V = d.V; p.P = d.P; p.variant = d.variant; p.gamma_max = d.gamma_max;
+    p.eps = d.near_tie_eps;
+    p.target_logits = b.target_logits; p.draft_logits = b.draft_logits;
+    p.q_row = b.q_row; p.parent = b.parent; p.cand_tok = b.cand_tok;
+    p.u_accept = b.u_accept; p.u_endpoint = b.u_endpoint; p.temperature = b.temperature;
+    p.n_accepted = b.n_accepted; p.accepted_path = b.accepted_path; p.out_tokens = b.out_tokens;
+    p.acc_child = b.acc_child; p.endpoint = b.endpoint; p.ratio = b.ratio; p.flags = b.flags;
+    p.residual_out = b.residual_out;
+
+    const int per_item = 4 * VT;
+    const int items = (d.V + per_item - 1) / per_item;
+    timing_begin(K_VERIFY_ROWS, stream);
+    if (items <= 1) launch_rows<1>(p, stream);
+    else if (items <= 2) launch_rows<2>(p, stream);
+    else if (items <= 4) launch_rows<4>(p, stream);
+    else launch_rows<8>(p, stream);
+    timing_end(K_VERIFY_ROWS, stream);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("verify_rows launch failed: %s", hipGetErrorString(e));
+        return MCSD_E_HIP;
+    }
+    timing_begin(K_WALK, stream);
+    hipLaunchKernelGGL(walk_kernel, dim3((d.B + 63) / 64), dim3(64), 0, stream, p);
+    timing_end(K_WALK, stream);
+    e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("walk launch failed: %s", hipGetErrorString(e));
+        return MCSD_E_HIP;
+    }
+    return MCSD_OK;
+}
+
+}  // namespace mcsd

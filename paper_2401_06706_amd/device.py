@@ -1,0 +1,100 @@
+"""Moves a synthetic workload (numpy, from workloads.py) into device tensors and
+builds the argument structs of the C ABI.  Allocation and copies only: torch is
+used for device memory and streams, every computation runs in libmcsd's kernels.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+from . import binding as mcsd
+from .workloads import AttnInputs, VerifyInputs
+
+
+def _to_device(a: np.ndarray, dtype: str, device) -> torch.Tensor:
+    if dtype == "bf16":
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)
+
+
+@dataclass
+class AttnCall:
+    args: mcsd.AttnArgs
+    tensors: Dict[str, torch.Tensor]
+
+    @property
+    def out(self) -> torch.Tensor:
+        return self.tensors["out"]
+
+    def out_numpy(self) -> np.ndarray:
+        """Output as float64 (exact conversion from the storage type)."""
+        return self.out.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def make_attn_call(ai: AttnInputs, device="cuda:0", parent_per_seq: bool = False) -> AttnCall:
+    t = {
+        "q": _to_device(ai.q, ai.dtype, device),
+        "k_prefix": _to_device(ai.k_prefix, ai.dtype, device),
+        "v_prefix": _to_device(ai.v_prefix, ai.dtype, device),
+        "k_tree": _to_device(ai.k_tree, ai.dtype, device),
+        "v_tree": _to_device(ai.v_tree, ai.dtype, device),
+        "prefix_len": torch.from_numpy(ai.prefix_len.astype(np.int32)).to(device),
+    }
+    parent = ai.parent.astype(np.int32)
+    if parent_per_seq:
+        parent = np.ascontiguousarray(np.broadcast_to(parent, (ai.B, ai.N)))
+    t["parent"] = torch.from_numpy(parent).to(device)
+    t["out"] = torch.zeros_like(t["q"])
+    dt = mcsd.DTYPE_FP32 if ai.dtype == "fp32" else mcsd.DTYPE_BF16
+    desc = mcsd.attn_desc(ai.B, ai.N, ai.H_q, ai.H_kv, ai.d, dt, ai.L_stride, ai.scale, parent_per_seq)
+    ws_bytes = mcsd.mcsd_attn_workspace_bytes(desc)
+    t["workspace"] = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=device)
+    args = mcsd.attn_args(t["q"], t["k_prefix"], t["v_prefix"], t["prefix_len"], t["k_tree"], t["v_tree"],
+                          t["parent"], t["out"], ai.scale, t["workspace"])
+    return AttnCall(args, t)
+
+
+@dataclass
+class VerifyCall:
+    args: mcsd.VerifyArgs
+    tensors: Dict[str, torch.Tensor]
+
+    def results(self) -> Dict[str, np.ndarray]:
+        names = ["n_accepted", "accepted_path", "out_tokens", "acc_child", "endpoint", "flags", "ratio",
+                 "residual_out"]
+        return {n: self.tensors[n].detach().cpu().numpy() for n in names if self.tensors.get(n) is not None}
+
+
+def make_verify_call(vi: VerifyInputs, device="cuda:0", want_ratio: bool = True,
+                     want_residual: bool = False, near_tie_eps: float = 1e-6) -> VerifyCall:
+    B, N, V = vi.B, vi.N, vi.V
+    G = vi.tree.gamma
+    i32 = dict(dtype=torch.int32, device=device)
+    t: Dict[str, Optional[torch.Tensor]] = {
+        "target_logits": torch.from_numpy(vi.target_logits).to(device),
+        "draft_logits": torch.from_numpy(vi.draft_logits).to(device),
+        "q_row": torch.from_numpy(vi.tree.q_row.astype(np.int32)).to(device),
+        "parent": torch.from_numpy(vi.tree.parent.astype(np.int32)).to(device),
+        "cand_tok": torch.from_numpy(vi.cand_tok.astype(np.int32)).to(device),
+        "u_accept": torch.from_numpy(vi.u_accept).to(device),
+        "u_endpoint": torch.from_numpy(vi.u_endpoint).to(device),
+        "temperature": torch.from_numpy(vi.temperature).to(device),
+        "n_accepted": torch.full((B,), -7, **i32),
+        "accepted_path": torch.full((B, G), -7, **i32),
+        "out_tokens": torch.full((B, G + 1), -7, **i32),
+        "acc_child": torch.full((B, 1 + N), -7, **i32),
+        "endpoint": torch.full((B, 1 + N), -7, **i32),
+        "flags": torch.full((B, 1 + N), -7, **i32),
+        "ratio": torch.full((B, N), -7.0, dtype=torch.float32, device=device) if want_ratio else None,
+        "residual_out": torch.full((B, 1 + N, V), -7.0, dtype=torch.float32, device=device)
+        if want_residual else None,
+    }
+    args = mcsd.verify_args(t["target_logits"], t["draft_logits"], t["q_row"], t["parent"], t["cand_tok"],
+                            t["u_accept"], t["u_endpoint"], t["temperature"], t["n_accepted"],
+                            t["accepted_path"], t["out_tokens"], t["acc_child"], t["endpoint"], t["flags"],
+                            vi.variant, ratio=t["ratio"], residual_out=t["residual_out"],
+                            near_tie_eps=near_tie_eps)
+    return VerifyCall(args, t)

@@ -1,0 +1,157 @@
+"""The C ABI without a GPU: the library loads, exports every symbol the header
+declares, the ctypes structs match the C layout, and every argument error is
+reported by return code before anything touches the device."""
+import ctypes as C
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+
+from paper_2401_06706_amd import binding as M
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mcsd.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(M.LIB_PATH):
+        from paper_2401_06706_amd.build import build
+        build(verbose=False)
+    return M.lib()
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(mcsd_[a-z_]+)\s*\(", src)))
+
+
+def test_exports_every_declared_symbol(lib):
+    names = declared_functions()
+    assert set(M.EXPORTS) == set(names)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert b"gfx950" in lib.mcsd_version()
+
+
+def test_struct_layout_matches_header(tmp_path):
+    """Compile a C program against the header and compare sizeof/offsetof with ctypes."""
+    fields = {"mcsd_attn_desc": (M.AttnDesc, ["struct_size", "B", "d", "L_stride", "scale", "parent_per_seq"]),
+              "mcsd_attn_bufs": (M.AttnBufs, ["q", "prefix_len", "out", "workspace", "workspace_bytes"]),
+              "mcsd_verify_desc": (M.VerifyDesc, ["V", "P", "variant", "gamma_max", "near_tie_eps"]),
+              "mcsd_verify_bufs": (M.VerifyBufs, ["target_logits", "temperature", "acc_child", "ratio",
+                                                  "flags", "residual_out", "workspace_bytes"])}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "mcsd.h"', "int main(void){"]
+    for cname, (_, fs) in fields.items():
+        lines.append(f'printf("{cname} %zu\\n", sizeof({cname}));')
+        for f in fs:
+            lines.append(f'printf("{cname}.{f} %zu\\n", offsetof({cname}, {f}));')
+    lines.append("return 0;}")
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           str(src), "-o", str(exe)])
+    got = dict(l.split() for l in subprocess.check_output([str(exe)], text=True).splitlines())
+    for cname, (ct, fs) in fields.items():
+        assert int(got[cname]) == C.sizeof(ct)
+        for f in fs:
+            assert int(got[f"{cname}.{f}"]) == getattr(ct, f).offset
+
+
+def test_tree_validate(lib):
+    M.mcsd_tree_validate(np.array([-1, -1, 0, 0, 1, 1], np.int32))
+    for bad in ([0], [-1, 1], [-1, -2], [-1, 0, 5]):
+        with pytest.raises(M.McsdError) as e:
+            M.mcsd_tree_validate(np.array(bad, np.int32))
+        assert e.value.code == -4
+    with pytest.raises(M.McsdError) as e:
+        M.mcsd_tree_validate(np.full(129, -1, np.int32))
+    assert e.value.code == -4
+    assert lib.mcsd_tree_validate(None, 3) == -1
+
+
+def good_attn_desc(**kw):
+    a = dict(B=2, N=6, H_q=4, H_kv=2, d=128, dtype=M.DTYPE_BF16, L_stride=4096, scale=0.088)
+    a.update(kw)
+    return M.attn_desc(**a)
+
+
+def test_attn_workspace_and_descriptor_errors(lib):
+    assert M.mcsd_attn_workspace_bytes(good_attn_desc()) % 256 == 0
+    assert M.mcsd_attn_workspace_bytes(good_attn_desc()) > 0
+    assert M.mcsd_attn_workspace_bytes(good_attn_desc(dtype=M.DTYPE_FP32, d=64)) == 0
+    bufs = M.AttnBufs(C.sizeof(M.AttnBufs), 4096, 4096, 4096, 4096, 4096, 4096, 4096, 4096, 4096, 1 << 40)
+    cases = [(dict(N=0), -4), (dict(N=129), -4), (dict(H_q=5), -2), (dict(B=0), -2), (dict(d=130), -3),
+             (dict(d=512), -3), (dict(dtype=7), -3), (dict(scale=float("nan")), -2), (dict(L_stride=-1), -2)]
+    for kw, code in cases:
+        d = good_attn_desc(**kw)
+        assert M.mcsd_attn_workspace_bytes(d) == 0
+        assert lib.mcsd_tree_attn(C.byref(d), C.byref(bufs), None) == code, kw
+        assert len(lib.mcsd_last_error()) > 0
+    d = good_attn_desc()
+    d.struct_size = 12
+    assert lib.mcsd_tree_attn(C.byref(d), C.byref(bufs), None) == -2
+    d = good_attn_desc()
+    assert lib.mcsd_tree_attn(None, C.byref(bufs), None) == -1
+    assert lib.mcsd_tree_attn(C.byref(d), None, None) == -1
+    # buffer errors: NULL tensor, missing / short / misaligned workspace, misaligned tensor
+    need = M.mcsd_attn_workspace_bytes(d)
+    b = M.AttnBufs(C.sizeof(M.AttnBufs), None, 4096, 4096, 4096, 4096, 4096, 4096, 4096, 4096, need)
+    assert lib.mcsd_tree_attn(C.byref(d), C.byref(b), None) == -1
+    b = M.AttnBufs(C.sizeof(M.AttnBufs), 4096, 4096, 4096, 4096, 4096, 4096, 4096, 4096, None, 0)
+    assert lib.mcsd_tree_attn(C.byref(d), C.byref(b), None) == -5
+    b = M.AttnBufs(C.sizeof(M.AttnBufs), 4096, 4096, 4096, 4096, 4096, 4096, 4096, 4096, 4096, need - 1)
+    assert lib.mcsd_tree_attn(C.byref(d), C.byref(b), None) == -5
+    b = M.AttnBufs(C.sizeof(M.AttnBufs), 4096, 4096, 4096, 4096, 4096, 4096, 4096, 4096, 4096 + 64, need)
+    assert lib.mcsd_tree_attn(C.byref(d), C.byref(b), None) == -5
+    b = M.AttnBufs(C.sizeof(M.AttnBufs), 4096 + 2, 4096, 4096, 4096, 4096, 4096, 4096, 4096, 4096, need)
+    assert lib.mcsd_tree_attn(C.byref(d), C.byref(b), None) == -2
+    b = M.AttnBufs(7, 4096, 4096, 4096, 4096, 4096, 4096, 4096, 4096, 4096, need)
+    assert lib.mcsd_tree_attn(C.byref(d), C.byref(b), None) == -2
+
+
+def good_verify_desc(**kw):
+    a = dict(B=2, N=6, V=64, P=3, variant=0, gamma_max=2, near_tie_eps=1e-6)
+    a.update(kw)
+    return M.VerifyDesc(C.sizeof(M.VerifyDesc), a["B"], a["N"], a["V"], a["P"], a["variant"],
+                        a["gamma_max"], a["near_tie_eps"])
+
+
+def test_verify_descriptor_errors(lib):
+    ptrs = [4096] * 16 + [None]
+    bufs = M.VerifyBufs(C.sizeof(M.VerifyBufs), *ptrs, 0)
+    assert M.mcsd_verify_workspace_bytes(good_verify_desc()) == 0
+    cases = [(dict(N=0), -4), (dict(N=200), -4), (dict(V=0), -2), (dict(V=40000), -3), (dict(P=9), -2),
+             (dict(variant=3), -3), (dict(gamma_max=0), -2), (dict(near_tie_eps=-1.0), -2),
+             (dict(B=70000), -3), (dict(P=0), -2)]
+    for kw, code in cases:
+        d = good_verify_desc(**kw)
+        assert lib.mcsd_verify_sample(C.byref(d), C.byref(bufs), None) == code, kw
+    d = good_verify_desc()
+    assert lib.mcsd_verify_sample(None, C.byref(bufs), None) == -1
+    assert lib.mcsd_verify_sample(C.byref(d), None, None) == -1
+    for i in (0, 3, 7, 8, 11, 14):        # required pointers
+        p2 = list(ptrs); p2[i] = None
+        b = M.VerifyBufs(C.sizeof(M.VerifyBufs), *p2, 0)
+        assert lib.mcsd_verify_sample(C.byref(d), C.byref(b), None) == -1, i
+    p2 = list(ptrs); p2[0] = 4100           # V % 4 == 0 rows are read with 16-byte loads
+    b = M.VerifyBufs(C.sizeof(M.VerifyBufs), *p2, 0)
+    assert lib.mcsd_verify_sample(C.byref(d), C.byref(b), None) == -2
+    # verify_step validates both halves before enqueueing anything
+    ad = good_attn_desc(N=0)
+    ab = M.AttnBufs(C.sizeof(M.AttnBufs), 4096, 4096, 4096, 4096, 4096, 4096, 4096, 4096, 4096, 1 << 40)
+    assert lib.mcsd_verify_step(C.byref(ad), C.byref(ab), C.byref(d), C.byref(bufs), None) == -4
+    ad = good_attn_desc()
+    dv = good_verify_desc(V=0)
+    assert lib.mcsd_verify_step(C.byref(ad), C.byref(ab), C.byref(dv), C.byref(bufs), None) == -2
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(M, "_lib", None)
+    monkeypatch.setattr(M, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(FileNotFoundError):
+        M.lib()

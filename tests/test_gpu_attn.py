@@ -1,0 +1,164 @@
+"""GPU parity of mcsd_tree_attn (through the C ABI) against the CPU oracle.
+
+Tolerances: 2e-2 abs for bf16 storage (inputs are N(0,1); outputs are convex
+combinations of V rows, so |out| <= max|V| ~ 5 and a bf16 output ulp is up to
+1.6e-2), 1e-5 abs for fp32.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mcsd_oracle as O
+from paper_2401_06706_amd import binding as M
+from paper_2401_06706_amd import device as D
+from paper_2401_06706_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"fp32": 1e-5, "bf16": 2e-2}
+
+
+def oracle_rows(ai, sel=None):
+    return O.tree_attn(ai.q, ai.k_prefix, ai.v_prefix, ai.prefix_len, ai.k_tree, ai.v_tree, ai.parent,
+                       ai.scale, O.FP32 if ai.dtype == "fp32" else O.BF16, sel=sel, n_threads=8)
+
+
+def run_gpu(ai, parent_per_seq=False):
+    call = D.make_attn_call(ai, parent_per_seq=parent_per_seq)
+    M.mcsd_tree_attn(call.args)
+    torch.cuda.synchronize()
+    return call.out_numpy()
+
+
+def check_full(ai, label, parent_per_seq=False):
+    print(f"[attn] {label}: B={ai.B} N={ai.N} H={ai.H_q}/{ai.H_kv} d={ai.d} {ai.dtype} L={ai.prefix_len.tolist()[:8]}",
+          flush=True)
+    got = run_gpu(ai, parent_per_seq)
+    ref = oracle_rows(ai)
+    err = np.abs(got - ref)
+    print(f"[attn] {label}: max abs err {err.max():.3e}", flush=True)
+    assert np.isfinite(got).all()
+    assert err.max() <= TOL[ai.dtype], f"{label}: max abs err {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)}"
+    return got, ref
+
+
+def check_sampled(ai, label, n_sel=96, seed=0):
+    print(f"[attn] {label}: B={ai.B} N={ai.N} H={ai.H_q}/{ai.H_kv} d={ai.d} {ai.dtype} sampled {n_sel} rows", flush=True)
+    got = run_gpu(ai)
+    rng = np.random.default_rng(seed)
+    sel = np.stack([rng.integers(0, ai.B, n_sel), rng.integers(0, ai.N, n_sel), rng.integers(0, ai.H_q, n_sel)],
+                   axis=1).astype(np.int32)
+    # always include the first and last row of the first and last sequence / head
+    sel[0] = (0, 0, 0); sel[1] = (ai.B - 1, ai.N - 1, ai.H_q - 1); sel[2] = (0, ai.N - 1, 0)
+    ref = oracle_rows(ai, sel)
+    g = got[sel[:, 0], sel[:, 1], sel[:, 2]]
+    err = np.abs(g - ref)
+    print(f"[attn] {label}: max abs err over sample {err.max():.3e}", flush=True)
+    assert np.isfinite(got).all()
+    assert err.max() <= TOL[ai.dtype], f"{label}: {err.max():.3e}"
+    # property that holds at any size: every output is a convex combination of V rows
+    vmax = max(np.abs(W.bf16_bits_to_f32(ai.v_prefix)).max(), np.abs(W.bf16_bits_to_f32(ai.v_tree)).max()) \
+        if ai.dtype == "bf16" else max(np.abs(ai.v_prefix).max(), np.abs(ai.v_tree).max())
+    assert np.abs(got).max() <= vmax * 1.01
+
+
+def wl(**kw):
+    base = dict(name="t", index=50, B=2, H_q=4, H_kv=4, d=128, dtype="bf16", prefix=(100, 100),
+                kconfig=(4, 2, 2), V=8, sigma_q=1.0, variant=0)
+    base.update(kw)
+    return W.Workload(**base)
+
+
+def test_c1_tiny_fp32():
+    check_full(W.gen_attn_inputs(W.WORKLOADS["c1"]), "c1")
+
+
+def test_c2_full():
+    check_full(W.gen_attn_inputs(W.WORKLOADS["c2"]), "c2")
+
+
+def test_c3_sampled():
+    check_sampled(W.gen_attn_inputs(W.WORKLOADS["c3"]), "c3", n_sel=256)
+
+
+def test_c4_sampled_ragged_batch():
+    check_sampled(W.gen_attn_inputs(W.WORKLOADS["c4"]), "c4", n_sel=192)
+
+
+def test_c5_sampled_gqa_long_prefix():
+    check_sampled(W.gen_attn_inputs(W.WORKLOADS["c5"]), "c5", n_sel=64)
+
+
+@pytest.mark.parametrize("L", [0, 1, 31, 32, 33, 63, 64, 65, 127, 129, 300])
+def test_prefix_lengths_around_tile_edges(L):
+    ai = W.gen_attn_inputs(wl(prefix=(L, L), B=1, H_q=2, H_kv=2), np.random.default_rng(L), L_stride=max(L, 1))
+    check_full(ai, f"L={L}")
+
+
+@pytest.mark.parametrize("kconfig", [(1,), (2,), (1, 1, 1, 1), (33,), (16, 2, 2), (2, 2, 2, 2, 2, 2), (128,)])
+def test_tree_shapes(kconfig):
+    """1 node, chains, a level wider than one key tile, 126- and 128-node trees."""
+    ai = W.gen_attn_inputs(wl(kconfig=kconfig, prefix=(70, 70), B=1, H_q=2, H_kv=2), np.random.default_rng(7))
+    check_full(ai, f"k={kconfig}")
+
+
+@pytest.mark.parametrize("H_q,H_kv,kconfig", [(8, 2, (4, 2)), (8, 1, (4, 2, 2)), (16, 2, (3, 2)), (6, 2, (5, 2, 1))])
+def test_gqa_row_tiles(H_q, H_kv, kconfig):
+    """Rows per KV head of 48, 224 (several row tiles, ragged last tile), 72, 45."""
+    ai = W.gen_attn_inputs(wl(H_q=H_q, H_kv=H_kv, kconfig=kconfig, prefix=(40, 200), B=2), np.random.default_rng(H_q))
+    check_full(ai, f"gqa {H_q}/{H_kv} {kconfig}")
+
+
+def test_ragged_batch_with_padding_rows_poisoned():
+    """Cache rows past prefix_len hold NaN: they must never reach the output."""
+    ai = W.gen_attn_inputs(wl(prefix=(1, 260), B=6, H_q=4, H_kv=2), np.random.default_rng(11), L_stride=300)
+    nan16 = np.uint16(0x7FC0)
+    for b in range(ai.B):
+        ai.k_prefix[b, :, ai.prefix_len[b]:] = nan16
+        ai.v_prefix[b, :, ai.prefix_len[b]:] = nan16
+    check_full(ai, "poisoned padding")
+
+
+def test_split_factors_agree(monkeypatch):
+    """Different chunk lengths (number of workgroups along the keys) give the same result
+    within tolerance; one chunk (direct write) and many chunks (combine kernel)."""
+    ai = W.gen_attn_inputs(wl(prefix=(1000, 1500), B=2, H_q=4, H_kv=4), np.random.default_rng(13), L_stride=1500)
+    ref = oracle_rows(ai)
+    outs = []
+    for chunk in (4, 8, 20, 1000):
+        monkeypatch.setenv("MCSD_ATTN_CHUNK_TILES", str(chunk))
+        got = run_gpu(ai)
+        assert np.abs(got - ref).max() <= TOL["bf16"], chunk
+        outs.append(got)
+    assert np.abs(outs[0] - outs[-1]).max() <= TOL["bf16"]
+
+
+def test_parent_per_sequence_and_determinism():
+    ai = W.gen_attn_inputs(wl(prefix=(50, 90), B=3), np.random.default_rng(17))
+    a, _ = check_full(ai, "shared parent")
+    b, _ = check_full(ai, "per-seq parent", parent_per_seq=True)
+    np.testing.assert_array_equal(a, b)
+    np.testing.assert_array_equal(a, run_gpu(ai))
+
+
+@pytest.mark.parametrize("d,dtype", [(64, "bf16"), (256, "bf16"), (128, "fp32"), (8, "fp32"), (96, "fp32")])
+def test_generic_kernel_shapes(d, dtype):
+    ai = W.gen_attn_inputs(wl(d=d, dtype=dtype, prefix=(5, 300), B=2, H_q=4, H_kv=2, kconfig=(3, 2)),
+                           np.random.default_rng(d))
+    check_full(ai, f"generic d={d} {dtype}")
+
+
+def test_scale_zero_gives_mean_of_visible_values():
+    ai = W.gen_attn_inputs(wl(prefix=(64, 64), B=1, H_q=2, H_kv=2, kconfig=(2, 2)), np.random.default_rng(19))
+    ai.scale = 0.0
+    got, ref = check_full(ai, "scale 0")
+
+
+def test_workspace_too_small_is_an_error():
+    ai = W.gen_attn_inputs(wl(prefix=(2000, 2000), B=1))
+    call = D.make_attn_call(ai)
+    assert call.args.bufs.workspace_bytes > 256
+    call.args.bufs.workspace_bytes = 256
+    with pytest.raises(M.McsdError) as e:
+        M.mcsd_tree_attn(call.args)
+    assert e.value.code == -5

@@ -1,0 +1,143 @@
+"""GPU parity of mcsd_verify_sample (through the C ABI) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2401_06706_amd import binding as M
+from paper_2401_06706_amd import device as D
+from paper_2401_06706_amd import workloads as W
+from tests.parity import compare_verify, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def run_gpu(vi, want_residual=False):
+    call = D.make_verify_call(vi, want_ratio=True, want_residual=want_residual)
+    M.mcsd_verify_sample(call.args)
+    torch.cuda.synchronize()
+    return call.results()
+
+
+def check(vi, label, want_residual=False):
+    print(f"[verify] {label}: B={vi.B} N={vi.N} V={vi.V} variant={vi.variant}", flush=True)
+    gpu = run_gpu(vi, want_residual)
+    orc = run_oracle(vi, want_residual)
+    st = compare_verify(vi, gpu, orc, check_residual=want_residual, label=label)
+    print(f"[verify] {label}: {st}", flush=True)
+    return gpu, orc, st
+
+
+@pytest.mark.parametrize("variant", [W.WITH_REPLACEMENT, W.WITHOUT_REPLACEMENT], ids=["wr", "wor"])
+def test_tiny_config_many_seeds(variant):
+    """C1 (tree 2x2, vocab 64), 10^4 independent draws of logits, candidates and uniforms."""
+    w = W.WORKLOADS["c1"].with_(B=10000, variant=variant)
+    vi = W.gen_verify_inputs(w, np.random.default_rng(w.seed + variant))
+    _, _, st = check(vi, f"c1-{variant}", want_residual=True)
+    assert st["near_tie_mismatch"] <= 2
+
+
+@pytest.mark.parametrize("name", ["c2", "c3", "c5"])
+def test_full_vocab_configs(name):
+    w = W.WORKLOADS[name]
+    vi = W.gen_verify_inputs(w)
+    gpu, orc, _ = check(vi, name, want_residual=True)
+    assert (gpu["n_accepted"] >= 0).all() and (gpu["n_accepted"] <= w.tree.gamma).all()
+
+
+def test_batched_serving_config_greedy_and_sampled():
+    """C4: 8 argmax sequences + 8 sampled ones in one call, both variants."""
+    for variant in (W.WITHOUT_REPLACEMENT, W.WITH_REPLACEMENT):
+        w = W.WORKLOADS["c4"].with_(variant=variant)
+        vi = W.gen_verify_inputs(w)
+        gpu, orc, _ = check(vi, f"c4-{variant}", want_residual=False)
+        # greedy rows never look at uniforms or ratios
+        assert np.isnan(gpu["ratio"][:8]).all()
+
+
+@pytest.mark.parametrize("V", [1, 2, 3, 5, 63, 64, 4095, 4096, 4097, 8190, 16385, 32767, 32768])
+def test_ragged_vocabulary_sizes(V):
+    """Vocabulary sizes around the vector width and the per-thread item boundaries."""
+    w = W.WORKLOADS["c2"].with_(V=V, B=3, kconfig=(3, 2) if V >= 3 else (1, 1), n_greedy=1,
+                                variant=W.WITHOUT_REPLACEMENT if V >= 3 else W.WITH_REPLACEMENT)
+    vi = W.gen_verify_inputs(w, np.random.default_rng(V))
+    check(vi, f"V={V}", want_residual=True)
+
+
+@pytest.mark.parametrize("kconfig", [(1,), (32,), (1, 1, 1, 1, 1, 1), (16, 2), (2, 2, 2, 2, 2, 2)])
+def test_tree_shapes(kconfig):
+    """Chains (ordinary speculative decoding), a single wide level, and a full binary
+    tree of 126 nodes (close to the 128-node limit)."""
+    w = W.WORKLOADS["c2"].with_(V=2048, B=4, kconfig=kconfig, variant=W.WITHOUT_REPLACEMENT)
+    vi = W.gen_verify_inputs(w, np.random.default_rng(len(kconfig)))
+    check(vi, f"k={kconfig}")
+
+
+def test_duplicate_candidates_with_replacement():
+    """Sec. 3.1: a rejected token has residual probability 0, a repeat is never accepted."""
+    w = W.WORKLOADS["c2"].with_(V=512, B=64, kconfig=(6,), variant=W.WITH_REPLACEMENT)
+    vi = W.gen_verify_inputs(w, np.random.default_rng(3))
+    vi.cand_tok[:, 1] = vi.cand_tok[:, 0]
+    vi.cand_tok[:, 4] = vi.cand_tok[:, 2]
+    vi.u_accept[:, :] = np.float32(0.999)          # mostly rejections, so repeats get tested
+    gpu, orc, _ = check(vi, "dups", want_residual=True)
+    tested = ~np.isnan(gpu["ratio"][:, 1])
+    assert tested.any() and (gpu["ratio"][tested, 1] == 0).all()
+
+
+def test_identical_distributions_accept_first_candidate():
+    w = W.WORKLOADS["c2"].with_(V=1000, B=8, kconfig=(4, 2))
+    vi = W.gen_verify_inputs(w, np.random.default_rng(5))
+    for row in range(1 + vi.N):
+        if vi.tree.q_row[row] >= 0:
+            vi.draft_logits[:, vi.tree.q_row[row]] = vi.target_logits[:, row]
+    gpu, orc, _ = check(vi, "p==q")
+    assert (gpu["n_accepted"] == 2).all()
+    assert (gpu["accepted_path"][:, 0] == 0).all() and (gpu["accepted_path"][:, 1] == 4).all()
+
+
+def test_temperatures_other_than_one():
+    w = W.WORKLOADS["c2"].with_(V=4000, B=6, kconfig=(4, 2))
+    vi = W.gen_verify_inputs(w, np.random.default_rng(6), temperature=[0.5, 0.7, 1.0, 1.5, 2.0, 0.0])
+    check(vi, "temps", want_residual=True)
+
+
+def test_bad_tokens_are_flagged_not_dereferenced():
+    w = W.WORKLOADS["c2"].with_(V=256, B=4, kconfig=(3,))
+    vi = W.gen_verify_inputs(w, np.random.default_rng(8))
+    vi.cand_tok[0, 0] = 256
+    vi.cand_tok[1, 1] = -5
+    vi.cand_tok[2, 2] = 1 << 30
+    vi.u_accept[:] = np.float32(0.9999)
+    gpu = run_gpu(vi)
+    assert (gpu["flags"][:3, 0] & M.FLAG_BAD_TOKEN).all() and not (gpu["flags"][3, 0] & M.FLAG_BAD_TOKEN)
+    assert gpu["ratio"][0, 0] == 0 and ((gpu["endpoint"] >= -1) & (gpu["endpoint"] < 256)).all()
+
+
+def test_deterministic_and_stream_ordered():
+    """Same inputs, two calls on a side stream: bitwise identical outputs."""
+    w = W.WORKLOADS["c3"].with_(B=2)
+    vi = W.gen_verify_inputs(w)
+    call = D.make_verify_call(vi, want_residual=True)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    M.mcsd_verify_sample(call.args, stream=s)
+    s.synchronize()
+    first = {k: v.copy() for k, v in call.results().items()}
+    for t in ("acc_child", "endpoint", "out_tokens", "ratio", "residual_out"):
+        call.tensors[t].fill_(-3)
+    s.wait_stream(torch.cuda.current_stream())
+    M.mcsd_verify_sample(call.args, stream=s)
+    s.synchronize()
+    second = call.results()
+    for k in first:
+        np.testing.assert_array_equal(first[k], second[k], err_msg=k)
+
+
+def test_runtime_errors_are_return_codes():
+    w = W.WORKLOADS["c1"]
+    vi = W.gen_verify_inputs(w)
+    call = D.make_verify_call(vi)
+    call.args.desc.V = 40000
+    with pytest.raises(M.McsdError) as e:
+        M.mcsd_verify_sample(call.args)
+    assert e.value.code == -3
