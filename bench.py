@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the MCSD verification step on one MI355X.
+
+One "step" = one mcsd_verify_step call: tree attention of one layer over the
+draft tree (prefix KV cache streamed once) followed by the multi-candidate
+accept/reject pass over the vocabulary and the root-to-leaf walk.  Inputs are
+seeded synthetic tensors resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  Metric: verified draft-tree nodes per second
+(B * N / step time).  `roofline` describes the dominant kernel (tree attention)
+from per-kernel HIP-event durations taken in a second pass over the same work;
+`cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+# HBM traffic per launch of the tree-attention kernel measured with rocprofv3 --pmc
+# (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see the
+# summaries under profiles/.  None = not measured for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--sets", type=int, default=0, help="rotating input copies (0 = enough for >= 1 GiB)")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, ai, vi, target_seconds):
+    """Times the oracle (as it stands) on a sample of the workload: a random subset of
+    attention rows and the verification of a subset of sequences, all host threads."""
+    from oracle import mcsd_oracle as O
+    threads = min(O.max_threads(), os.cpu_count() or 1)
+    dt = O.FP32 if ai.dtype == "fp32" else O.BF16
+    rng = np.random.default_rng(0)
+    total_rows = ai.B * ai.N * ai.H_q
+
+    def attn_time(n):
+        sel = np.stack([rng.integers(0, ai.B, n), rng.integers(0, ai.N, n), rng.integers(0, ai.H_q, n)],
+                       axis=1).astype(np.int32)
+        t0 = time.perf_counter()
+        O.tree_attn(ai.q, ai.k_prefix, ai.v_prefix, ai.prefix_len, ai.k_tree, ai.v_tree, ai.parent, ai.scale,
+                    dt, sel=sel, n_threads=threads)
+        return time.perf_counter() - t0
+
+    pilot_n = 4 * threads
+    per_row = attn_time(pilot_n) / pilot_n
+    n_rows = int(min(total_rows, max(pilot_n, 0.7 * target_seconds / max(per_row, 1e-9))))
+    t_attn = attn_time(n_rows)
+
+    nb = min(vi.B, max(1, vi.B // 4))
+    sl = slice(vi.B - nb, vi.B)          # the last sequences (sampled ones in the mixed batch)
+    t0 = time.perf_counter()
+    O.verify(vi.target_logits[sl], vi.draft_logits[sl], vi.tree.q_row, vi.tree.parent, vi.cand_tok[sl],
+             vi.u_accept[sl], vi.u_endpoint[sl], vi.temperature[sl], vi.variant, gamma_max=vi.tree.gamma,
+             n_threads=threads)
+    t_ver = time.perf_counter() - t0
+    est_step = t_attn * total_rows / n_rows + t_ver * vi.B / nb
+    return {
+        "value": vi.B * vi.N / est_step, "unit": "nodes/s", "cores": threads, "kind": "oracle",
+        "sample": f"{n_rows} of {total_rows} attention rows ({t_attn:.2f} s) + verification of {nb} of "
+                  f"{vi.B} sequences ({t_ver:.2f} s), extrapolated to one full step ({est_step:.1f} s)",
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build measures one GPU only (got --gpus {args.gpus}); the path shards by "
+              "sequence / KV head without any exchange, see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2401_06706_amd import binding as M
+    from paper_2401_06706_amd import device as D
+    from paper_2401_06706_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    M.lib()     # fails loudly if libmcsd.so is not built
+    dev = "cuda:0"
+    w = W.WORKLOADS[args.workload]
+    ai = W.gen_attn_inputs(w)
+    vi = W.gen_verify_inputs(w)
+
+    attn_bytes = ai.algorithmic_bytes()
+    verify_bytes = vi.design_bytes()
+    footprint = attn_bytes + verify_bytes
+    n_sets = args.sets if args.sets > 0 else max(2, int(np.ceil((1 << 30) / footprint)))
+    n_sets = min(n_sets, 128)
+    sets = []
+    for s in range(n_sets):
+        # every set holds the same values at different addresses, so no cache level can
+        # serve one step's reads from the previous step
+        sets.append((D.make_attn_call(ai, dev), D.make_verify_call(vi, dev, want_ratio=False)))
+    torch.cuda.synchronize()
+
+    def run(n_steps, offset=0):
+        for i in range(n_steps):
+            a, v = sets[(offset + i) % n_sets]
+            M.mcsd_verify_step(a.args, v.args)
+
+    run(args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps, args.warmup)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    # second pass, same work, with every kernel launch bracketed by HIP events on its stream
+    M.mcsd_kernel_timing(True)
+    run(args.steps, args.warmup + args.steps)
+    torch.cuda.synchronize()
+    ktimes = M.mcsd_kernel_timing_read()
+    M.mcsd_kernel_timing(False)
+    kernels = {k: {"avg_us": 1e3 * ms / n, "launches": n} for k, (ms, n) in ktimes.items() if n > 0}
+
+    dom = "tree_attn_mfma"
+    dom_us = kernels[dom]["avg_us"]
+    achieved = attn_bytes / (dom_us * 1e-6) / 1e9
+    flops = ai.flops()
+    roofline = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                "algorithmic_bytes": attn_bytes, "avg_kernel_us": dom_us,
+                "mfma_tflops": flops / (dom_us * 1e-6) / 1e12,
+                "mfma_frac": flops / (dom_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+    ver_us = kernels["verify_rows"]["avg_us"]
+    verify_roof = {"kernel": "verify_rows", "bound": "hbm", "achieved": verify_bytes / (ver_us * 1e-6) / 1e9,
+                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": verify_bytes / (ver_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                   "algorithmic_bytes": verify_bytes, "avg_kernel_us": ver_us}
+
+    out = {
+        "metric": "verified draft-tree nodes/sec (tree-attn + MCSD sample); achieved HBM GB/s",
+        "value": w.B * ai.N / (ms_per_step * 1e-3),
+        "unit": "nodes/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.description}", "B": w.B, "tree": "x".join(map(str, w.kconfig)),
+                   "nodes": ai.N, "H_q": w.H_q, "H_kv": w.H_kv, "d": w.d, "V": w.V,
+                   "prefix_tokens_total": int(ai.prefix_len.sum()), "input_sets": n_sets,
+                   "variant": "without_replacement" if vi.variant else "with_replacement"},
+        "step_hbm_gbs": footprint / (ms_per_step * 1e-3) / 1e9,
+        "step_hbm_frac": footprint / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "roofline": roofline,
+        "verify_roofline": verify_roof,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, ai, vi, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -105,12 +105,19 @@ def test_bad_tokens_are_flagged_not_dereferenced():
     w = W.WORKLOADS["c2"].with_(V=256, B=4, kconfig=(3,))
     vi = W.gen_verify_inputs(w, np.random.default_rng(8))
     vi.cand_tok[0, 0] = 256
-    vi.cand_tok[1, 1] = -5
-    vi.cand_tok[2, 2] = 1 << 30
+    vi.cand_tok[1, 0] = -5
+    vi.cand_tok[2, 0] = 1 << 30
     vi.u_accept[:] = np.float32(0.9999)
     gpu = run_gpu(vi)
     assert (gpu["flags"][:3, 0] & M.FLAG_BAD_TOKEN).all() and not (gpu["flags"][3, 0] & M.FLAG_BAD_TOKEN)
-    assert gpu["ratio"][0, 0] == 0 and ((gpu["endpoint"] >= -1) & (gpu["endpoint"] < 256)).all()
+    assert (gpu["ratio"][:3, 0] == 0).all() and ((gpu["endpoint"] >= -1) & (gpu["endpoint"] < 256)).all()
+    # the bad candidate counts as rejected; the remaining ones are verified as usual
+    vi.cand_tok[:3, 0] = vi.cand_tok[:3, 1]
+    vi.u_accept[:, 0] = np.float32(0.99999988)
+    orc = run_oracle(vi)
+    keep = orc.acc_child[:3, 0] != 0          # sequences whose first (replaced) candidate is rejected anyway
+    assert keep.any()
+    np.testing.assert_array_equal(gpu["acc_child"][:3, 0][keep] >= 1, orc.acc_child[:3, 0][keep] >= 1)
 
 
 def test_deterministic_and_stream_ordered():
