@@ -22,6 +22,7 @@ struct AttnPlan {
     bool use_mfma;        // bf16, d == 128: matrix-core kernel; otherwise the generic ALU kernel
     int rows_per_kv;      // M = N * (H_q / H_kv) query rows that share one KV head
     int row_tile;         // query rows per workgroup (32 or 64) for the MFMA kernel
+    int variant;          // which instantiation of the MFMA kernel
     int n_row_tiles;
     int tiles_prefix_max; // 32-key tiles needed for L_stride prefix keys
     int tiles_tree;       // 32-key tiles needed for N tree keys

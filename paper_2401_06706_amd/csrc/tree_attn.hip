@@ -41,8 +41,6 @@ constexpr float LOG2E_F = 1.44269504088896340736f;
 constexpr float M_INIT = -1.0e30f;     // "no key seen yet" running max (finite so that differences stay finite)
 constexpr float RESCALE_GAP = 8.0f;    // running max is only raised when a score exceeds it by 2^8
 constexpr int KT = 32;                 // keys per tile
-constexpr int WAVES = 4;
-constexpr int OBUF_LD = 68;            // leading dimension (rows) of the merge buffer, padded
 
 struct AttnParams {
     const void *q, *k_prefix, *v_prefix, *k_tree, *v_tree;
@@ -84,12 +82,20 @@ __device__ __forceinline__ void build_ancestor_masks(const int32_t *parent, int 
 }
 
 // --------------------------------------------------------------------- MFMA path
-template <int MT>
-__global__ __launch_bounds__(WAVES * 64) void tree_attn_mfma_kernel(AttnParams p)
+// MT = 16-row query tiles per wave, RH = row groups per workgroup, KS = key streams per
+// workgroup.  Wave (rh, ks) owns query rows [16 MT rh, 16 MT (rh+1)) of the workgroup's
+// row tile and the key tiles t_begin + ks, + KS, ...  Waves of one key stream read the
+// same K/V tiles (the second read is served by the L1/L2 caches).
+template <int MT, int RH, int KS>
+__global__ __launch_bounds__(RH * KS * 64) void tree_attn_mfma_kernel(AttnParams p)
 {
-    constexpr int ROWS = 16 * MT;
+    constexpr int NW = RH * KS;
+    constexpr int WROWS = 16 * MT;          // rows per wave
+    constexpr int ROWS = WROWS * RH;        // rows per workgroup
+    constexpr int OLD = ROWS + 4;           // leading dimension of the merge buffer
     constexpr int D = 128;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int rh = wave / KS, ks = wave % KS;
     const int lj = lane >> 4, lc = lane & 15;
     const int rt = blockIdx.x % p.n_row_tiles;
     const int chunk = blockIdx.x / p.n_row_tiles;
@@ -104,39 +110,45 @@ __global__ __launch_bounds__(WAVES * 64) void tree_attn_mfma_kernel(AttnParams p
     const int t_end = min(total_tiles, t_begin + p.chunk_tiles);
     const int n_chunks = (total_tiles + p.chunk_tiles - 1) / p.chunk_tiles;
 
-    __shared__ __attribute__((aligned(16))) uint32_t s_vt[WAVES][64 * 8 * 4];   // V transpose staging, 8 KB per wave
-    __shared__ float s_obuf[D * OBUF_LD];
+    // LDS: V-transpose staging (8 KB per wave) during the main loop; the same memory is the
+    // merge buffer O[d][row] afterwards.  Q operands live in s_q for the whole kernel.
+    constexpr int VT_WORDS = NW * 2048;
+    constexpr int OB_WORDS = D * OLD;
+    __shared__ __attribute__((aligned(16))) uint32_t s_big[VT_WORDS > OB_WORDS ? VT_WORDS : OB_WORDS];
+    __shared__ __attribute__((aligned(16))) uint32_t s_q[RH * MT * 4 * 64 * 4];
     __shared__ uint32_t s_anc[MCSD_MAX_NODES][4];
-    __shared__ float s_m[WAVES][64], s_l[WAVES][64];
-    __shared__ float s_mstar[64], s_lstar[64];
+    __shared__ float s_m[KS][ROWS], s_l[KS][ROWS];
+    __shared__ float s_mstar[ROWS], s_lstar[ROWS];
+    float *s_obuf = reinterpret_cast<float *>(s_big);
 
     const bool has_tree = t_end > tilesP;
-    if (has_tree) {
-        build_ancestor_masks(p.parent + (p.parent_per_seq ? (size_t)b * p.N : 0), p.N, s_anc);
-        __syncthreads();
-    }
+    if (has_tree) build_ancestor_masks(p.parent + (p.parent_per_seq ? (size_t)b * p.N : 0), p.N, s_anc);
 
     const uint16_t *qb = static_cast<const uint16_t *>(p.q);
     const int row0 = rt * ROWS;
 
-    // Q operand: lane (lj, lc) holds Q[row0 + 16 mt + lc][32 kk + 8 lj .. +7]
-    bf16x8 qreg[MT][4];
+    // Q operands, staged once: entry ((rh MT + mt) 4 + kk) 64 + lane holds
+    // Q[row0 + 16 (rh MT + mt) + lc][32 kk + 8 lj .. +7], i.e. exactly what the lane feeds to the MFMA.
     int node_of[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        const int r = row0 + 16 * mt + lc;
+        const int r = row0 + WROWS * rh + 16 * mt + lc;
         const bool ok = r < p.M;
         const int rr = ok ? r : p.M - 1;
         const int node = rr / p.G, hh = rr % p.G;
         node_of[mt] = node;
-        const uint16_t *src = qb + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + 8 * lj;
+        if (ks == 0) {
+            const uint16_t *src = qb + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + 8 * lj;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            u32x4 v = *reinterpret_cast<const u32x4 *>(src + 32 * kk);
-            if (!ok) v = (u32x4){0u, 0u, 0u, 0u};
-            qreg[mt][kk] = __builtin_bit_cast(bf16x8, v);
+            for (int kk = 0; kk < 4; ++kk) {
+                u32x4 v = *reinterpret_cast<const u32x4 *>(src + 32 * kk);
+                if (!ok) v = (u32x4){0u, 0u, 0u, 0u};
+                *reinterpret_cast<u32x4 *>(s_q + ((((rh * MT + mt) * 4 + kk) * 64) + lane) * 4) = v;
+            }
         }
     }
+    __syncthreads();
+    const uint32_t *qw = s_q + (size_t)(rh * MT) * 4 * 64 * 4 + lane * 4;
 
     f32x4 oacc[8][MT];
 #pragma unroll
@@ -180,10 +192,10 @@ __global__ __launch_bounds__(WAVES * 64) void tree_attn_mfma_kernel(AttnParams p
         }
     };
 
-    uint32_t *vt = s_vt[wave];
-    int t = t_begin + wave;
+    uint32_t *vt = s_big + wave * 2048;
+    int t = t_begin + ks;
     if (t < t_end) load_k(t);
-    for (; t < t_end; t += WAVES) {
+    for (; t < t_end; t += KS) {
         // this tile's K operands leave the load registers, which are refilled for the next tile;
         // this tile's V is requested now and consumed after the scores and the softmax
         bf16x8 kop[2][4];
@@ -203,7 +215,7 @@ __global__ __launch_bounds__(WAVES * 64) void tree_attn_mfma_kernel(AttnParams p
                 vcur[s] = *reinterpret_cast<const u32x4 *>(vb + (size_t)row * D + 8 * lc);
             }
         }
-        if (t + WAVES < t_end) load_k(t + WAVES);
+        if (t + KS < t_end) load_k(t + KS);
 
         const bool is_tree = t >= tilesP;
         const int tt = t - tilesP;
@@ -212,16 +224,18 @@ __global__ __launch_bounds__(WAVES * 64) void tree_attn_mfma_kernel(AttnParams p
         // S^T[key][row] = sum_d K[key][d] Q[row][d]
         f32x4 sacc[2][MT];
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
+        for (int mt = 0; mt < MT; ++mt) {
+            f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[sub][kk], qreg[mt][kk], acc, 0, 0, 0);
-                sacc[sub][mt] = acc * p.scale_log2;
+            for (int kk = 0; kk < 4; ++kk) {
+                const bf16x8 qop = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qw + (mt * 4 + kk) * 256));
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[0][kk], qop, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[1][kk], qop, acc1, 0, 0, 0);
             }
-        // lane (lj, lc) now holds, for row 16 mt + lc, keys 16 sub + 4 lj + i
+            sacc[0][mt] = acc0 * p.scale_log2;
+            sacc[1][mt] = acc1 * p.scale_log2;
+        }
+        // lane (lj, lc) now holds, for its row 16 mt + lc, keys 16 sub + 4 lj + i
         if (nvalid < KT || is_tree) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
@@ -308,41 +322,45 @@ __global__ __launch_bounds__(WAVES * 64) void tree_attn_mfma_kernel(AttnParams p
         __builtin_amdgcn_wave_barrier();
     }
 
-    // ---- merge the four waves: (m, l) per row through LDS, O through s_obuf[d][row]
+    // ---- merge the key streams: (m, l) per row through LDS, O through s_obuf[d][row]
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         float lt = l_part[mt];
         lt += __shfl_xor(lt, 16);
         lt += __shfl_xor(lt, 32);
-        if (lj == 0) { s_m[wave][16 * mt + lc] = m_used[mt]; s_l[wave][16 * mt + lc] = lt; }
+        if (lj == 0) { s_m[ks][WROWS * rh + 16 * mt + lc] = m_used[mt]; s_l[ks][WROWS * rh + 16 * mt + lc] = lt; }
     }
-    __syncthreads();
+    __syncthreads();        // also: every wave is done with its V staging area, which becomes s_obuf
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        const int r = 16 * mt + lc;
-        const float ms = fmaxf(fmaxf(s_m[0][r], s_m[1][r]), fmaxf(s_m[2][r], s_m[3][r]));
+        const int r = WROWS * rh + 16 * mt + lc;
+        float ms = s_m[0][r];
+#pragma unroll
+        for (int k2 = 1; k2 < KS; ++k2) ms = fmaxf(ms, s_m[k2][r]);
         const float f = exp2f(m_used[mt] - ms);
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt) oacc[nt][mt] *= f;
     }
     if (tid < ROWS) {
-        const float ms = fmaxf(fmaxf(s_m[0][tid], s_m[1][tid]), fmaxf(s_m[2][tid], s_m[3][tid]));
+        float ms = s_m[0][tid];
+#pragma unroll
+        for (int k2 = 1; k2 < KS; ++k2) ms = fmaxf(ms, s_m[k2][tid]);
         float ls = 0.f;
 #pragma unroll
-        for (int w = 0; w < WAVES; ++w) ls += exp2f(s_m[w][tid] - ms) * s_l[w][tid];
+        for (int k2 = 0; k2 < KS; ++k2) ls += exp2f(s_m[k2][tid] - ms) * s_l[k2][tid];
         s_mstar[tid] = ms;
         s_lstar[tid] = ls;
     }
-    for (int w = 0; w < WAVES; ++w) {
-        if (wave == w) {
+    for (int k2 = 0; k2 < KS; ++k2) {
+        if (ks == k2) {
 #pragma unroll
             for (int nt = 0; nt < 8; ++nt)
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const int idx = (16 * nt + 4 * lj + i) * OBUF_LD + 16 * mt + lc;
-                        if (w == 0) s_obuf[idx] = oacc[nt][mt][i];
+                        const int idx = (16 * nt + 4 * lj + i) * OLD + WROWS * rh + 16 * mt + lc;
+                        if (k2 == 0) s_obuf[idx] = oacc[nt][mt][i];
                         else s_obuf[idx] += oacc[nt][mt][i];
                     }
         }
@@ -353,25 +371,25 @@ __global__ __launch_bounds__(WAVES * 64) void tree_attn_mfma_kernel(AttnParams p
     if (n_chunks == 1) {
         // the only chunk of this sequence: normalise and write the output rows
         uint16_t *ob = static_cast<uint16_t *>(p.out);
-        for (int idx = tid; idx < rows_valid * (D / 8); idx += WAVES * 64) {
+        for (int idx = tid; idx < rows_valid * (D / 8); idx += NW * 64) {
             const int r = idx / (D / 8), d8 = idx % (D / 8);
             const float inv = 1.0f / s_lstar[r];
             float v[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = s_obuf[(8 * d8 + e) * OBUF_LD + r] * inv;
+            for (int e = 0; e < 8; ++e) v[e] = s_obuf[(8 * d8 + e) * OLD + r] * inv;
             u32x4 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
             const int gr = row0 + r, node = gr / p.G, hh = gr % p.G;
             *reinterpret_cast<u32x4 *>(ob + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + 8 * d8) = pk;
         }
     } else {
         const size_t unit = (kv_head * p.n_chunks_max + chunk) * (size_t)p.R + row0;
-        for (int idx = tid; idx < rows_valid * (D / 4); idx += WAVES * 64) {
+        for (int idx = tid; idx < rows_valid * (D / 4); idx += NW * 64) {
             const int r = idx / (D / 4), d4 = idx % (D / 4);
             float4 v;
-            v.x = s_obuf[(4 * d4 + 0) * OBUF_LD + r];
-            v.y = s_obuf[(4 * d4 + 1) * OBUF_LD + r];
-            v.z = s_obuf[(4 * d4 + 2) * OBUF_LD + r];
-            v.w = s_obuf[(4 * d4 + 3) * OBUF_LD + r];
+            v.x = s_obuf[(4 * d4 + 0) * OLD + r];
+            v.y = s_obuf[(4 * d4 + 1) * OLD + r];
+            v.z = s_obuf[(4 * d4 + 2) * OLD + r];
+            v.w = s_obuf[(4 * d4 + 3) * OLD + r];
             *reinterpret_cast<float4 *>(p.part_o + (unit + r) * D + 4 * d4) = v;
         }
         if (tid < rows_valid) {
@@ -538,7 +556,20 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
         *plan = pl;
         return true;
     }
+    // Kernel variant: 0 = 32 rows x 8 key streams, 1 = 2 x 32 rows x 4 key streams (both 8 waves,
+    // two per SIMD: the choice when the KV stream from HBM is the bound), 2 = 64 rows per wave x 4
+    // key streams (half the K/V operand traffic per flop: the choice when many row tiles share a
+    // KV head and the matrix cores are the bound).
     pl.row_tile = pl.rows_per_kv <= 32 ? 32 : 64;
+    pl.variant = pl.rows_per_kv <= 32 ? 0 : (pl.rows_per_kv <= 128 ? 1 : 2);
+    {
+        const int forced_variant = env_int("MCSD_ATTN_VARIANT", 0);     // 1-based; 0 = automatic
+        if (forced_variant >= 1 && forced_variant <= 3) {
+            pl.variant = forced_variant - 1;
+            pl.row_tile = pl.variant == 0 ? 32 : 64;
+        }
+    }
+    const int key_streams = pl.variant == 0 ? 8 : 4;
     pl.n_row_tiles = (pl.rows_per_kv + pl.row_tile - 1) / pl.row_tile;
     pl.tiles_prefix_max = (d.L_stride + KT - 1) / KT;
     pl.tiles_tree = (d.N + KT - 1) / KT;
@@ -549,8 +580,8 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
     // (one [rows][d] fp32 block per workgroup) small against the KV bytes streamed.
     const long target_wgs = env_int("MCSD_ATTN_TARGET_WGS", 2048);
     long chunk = (total_max * units + target_wgs - 1) / target_wgs;
-    chunk = ((chunk + WAVES - 1) / WAVES) * WAVES;
-    if (chunk < WAVES) chunk = WAVES;
+    chunk = ((chunk + key_streams - 1) / key_streams) * key_streams;
+    if (chunk < key_streams) chunk = key_streams;
     const int forced = env_int("MCSD_ATTN_CHUNK_TILES", 0);
     if (forced > 0) chunk = forced;
     if (chunk > total_max) chunk = total_max;
@@ -600,12 +631,14 @@ int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const
         p.part_m = ws + rows * d.d;
         p.part_l = p.part_m + rows;
     }
-    dim3 grid(plan.n_chunks_max * plan.n_row_tiles, d.H_kv, d.B), block(WAVES * 64);
+    dim3 grid(plan.n_chunks_max * plan.n_row_tiles, d.H_kv, d.B);
     timing_begin(K_ATTN_MFMA, stream);
-    if (plan.row_tile == 32)
-        hipLaunchKernelGGL(tree_attn_mfma_kernel<2>, grid, block, 0, stream, p);
+    if (plan.variant == 0)
+        hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 1, 8>), grid, dim3(512), 0, stream, p);
+    else if (plan.variant == 1)
+        hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, 4>), grid, dim3(512), 0, stream, p);
     else
-        hipLaunchKernelGGL(tree_attn_mfma_kernel<4>, grid, block, 0, stream, p);
+        hipLaunchKernelGGL((tree_attn_mfma_kernel<4, 1, 4>), grid, dim3(256), 0, stream, p);
     timing_end(K_ATTN_MFMA, stream);
     e = hipGetLastError();
     if (e != hipSuccess) { set_error("tree_attn_mfma launch failed: %s", hipGetErrorString(e)); return MCSD_E_HIP; }
