@@ -126,7 +126,7 @@ static int32_t check_attn(const mcsd_attn_desc *d, const mcsd_attn_bufs *b, Attn
     if (d->H_q % d->H_kv != 0) { set_error("attn: H_q %d not a multiple of H_kv %d", d->H_q, d->H_kv); return MCSD_E_SHAPE; }
     if (d->dtype != MCSD_DTYPE_FP32 && d->dtype != MCSD_DTYPE_BF16) { set_error("attn: unknown dtype %d", d->dtype); return MCSD_E_UNSUPPORTED; }
     if (d->d > MCSD_MAX_HEAD_DIM || d->d % (d->dtype == MCSD_DTYPE_BF16 ? 8 : 4) != 0) { set_error("attn: head dim %d unsupported", d->d); return MCSD_E_UNSUPPORTED; }
-    if (!(d->scale == d->scale)) { set_error("attn: scale is NaN"); return MCSD_E_SHAPE; }
+    if (!(d->scale >= 0.f) || !(d->scale < 1e30f)) { set_error("attn: scale must be finite and >= 0"); return MCSD_E_SHAPE; }
     if (!make_attn_plan(*d, plan)) { set_error("attn: no kernel for this shape"); return MCSD_E_UNSUPPORTED; }
     if (!b) return MCSD_OK;
     if (b->struct_size != sizeof(mcsd_attn_bufs)) { set_error("attn bufs struct_size %u != %zu", b->struct_size, sizeof(mcsd_attn_bufs)); return MCSD_E_SHAPE; }

@@ -86,15 +86,31 @@ __device__ __forceinline__ void build_ancestor_masks(const int32_t *parent, int 
 // workgroup.  Wave (rh, ks) owns query rows [16 MT rh, 16 MT (rh+1)) of the workgroup's
 // row tile and the key tiles t_begin + ks, + KS, ...  Waves of one key stream read the
 // same K/V tiles (the second read is served by the L1/L2 caches).
+//
+// Data movement per 32-key tile and wave (8 KB of K, 8 KB of V, one 8.5 KB LDS area):
+//   K  global -> registers with fully contiguous 1 KB loads (issued one tile ahead),
+//      registers -> LDS in MFMA-operand order (16-byte granules, XOR-swizzled so that
+//      both the stores and the operand loads are bank-conflict free), LDS -> operand.
+//      Loading K straight into operand registers would make neighbouring lanes read
+//      different cache lines, which stalls the address path of the vector memory unit.
+//   V  global -> registers (a lane reads 8 key rows x 16 contiguous bytes, neighbouring
+//      lanes neighbouring bytes), in-lane 8x8 transpose of the 16-bit elements,
+//      registers -> the same LDS area -> operand (exchange inside each 16-lane group).
 template <int MT, int RH, int KS>
-__global__ __launch_bounds__(RH * KS * 64) void tree_attn_mfma_kernel(AttnParams p)
+__global__ __launch_bounds__(RH * KS * 64) __attribute__((amdgpu_waves_per_eu(MT <= 2 ? 2 : 1, MT <= 2 ? 2 : 1)))
+void tree_attn_mfma_kernel(AttnParams p)
 {
+    constexpr bool QLDS = MT > 2;           // 64 rows per wave: Q operands are re-read from LDS for every tile
     constexpr int NW = RH * KS;
+    constexpr int NT = NW * 64;
     constexpr int WROWS = 16 * MT;          // rows per wave
     constexpr int ROWS = WROWS * RH;        // rows per workgroup
-    constexpr int OLD = ROWS + 4;           // leading dimension of the merge buffer
     constexpr int D = 128;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int TILE_BYTES = KT * D * 2;  // 8192
+    constexpr int AREA_WORDS = WROWS * 68;  // per-wave LDS area: >= 2048 words of staging, WROWS x 68 floats in the epilogue
+    static_assert(AREA_WORDS >= 2048, "staging needs 8 KB per wave");
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps tile indices and pointers scalar
     const int rh = wave / KS, ks = wave % KS;
     const int lj = lane >> 4, lc = lane & 15;
     const int rt = blockIdx.x % p.n_row_tiles;
@@ -110,16 +126,11 @@ __global__ __launch_bounds__(RH * KS * 64) void tree_attn_mfma_kernel(AttnParams
     const int t_end = min(total_tiles, t_begin + p.chunk_tiles);
     const int n_chunks = (total_tiles + p.chunk_tiles - 1) / p.chunk_tiles;
 
-    // LDS: V-transpose staging (8 KB per wave) during the main loop; the same memory is the
-    // merge buffer O[d][row] afterwards.  Q operands live in s_q for the whole kernel.
-    constexpr int VT_WORDS = NW * 2048;
-    constexpr int OB_WORDS = D * OLD;
-    __shared__ __attribute__((aligned(16))) uint32_t s_big[VT_WORDS > OB_WORDS ? VT_WORDS : OB_WORDS];
-    __shared__ __attribute__((aligned(16))) uint32_t s_q[RH * MT * 4 * 64 * 4];
+    __shared__ __attribute__((aligned(16))) uint32_t s_big[NW * AREA_WORDS];
     __shared__ uint32_t s_anc[MCSD_MAX_NODES][4];
     __shared__ float s_m[KS][ROWS], s_l[KS][ROWS];
-    __shared__ float s_mstar[ROWS], s_lstar[ROWS];
-    float *s_obuf = reinterpret_cast<float *>(s_big);
+    __shared__ float s_mstar[ROWS], s_linv[ROWS];
+    __shared__ __attribute__((aligned(16))) uint32_t s_q[QLDS ? RH * MT * 4 * 64 * 4 : 4];
 
     const bool has_tree = t_end > tilesP;
     if (has_tree) build_ancestor_masks(p.parent + (p.parent_per_seq ? (size_t)b * p.N : 0), p.N, s_anc);
@@ -127,8 +138,9 @@ __global__ __launch_bounds__(RH * KS * 64) void tree_attn_mfma_kernel(AttnParams
     const uint16_t *qb = static_cast<const uint16_t *>(p.q);
     const int row0 = rt * ROWS;
 
-    // Q operands, staged once: entry ((rh MT + mt) 4 + kk) 64 + lane holds
-    // Q[row0 + 16 (rh MT + mt) + lc][32 kk + 8 lj .. +7], i.e. exactly what the lane feeds to the MFMA.
+    // Q operand: lane (lj, lc) has Q[row0 + WROWS rh + 16 mt + lc][32 kk + 8 lj .. +7], held in
+    // registers, or (QLDS) parked in LDS in exactly that per-lane order.
+    bf16x8 qreg[QLDS ? 1 : MT][4];
     int node_of[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -137,18 +149,20 @@ __global__ __launch_bounds__(RH * KS * 64) void tree_attn_mfma_kernel(AttnParams
         const int rr = ok ? r : p.M - 1;
         const int node = rr / p.G, hh = rr % p.G;
         node_of[mt] = node;
-        if (ks == 0) {
-            const uint16_t *src = qb + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + 8 * lj;
+        const uint16_t *src = qb + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + 8 * lj;
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                u32x4 v = *reinterpret_cast<const u32x4 *>(src + 32 * kk);
-                if (!ok) v = (u32x4){0u, 0u, 0u, 0u};
-                *reinterpret_cast<u32x4 *>(s_q + ((((rh * MT + mt) * 4 + kk) * 64) + lane) * 4) = v;
+        for (int kk = 0; kk < 4; ++kk) {
+            u32x4 v = *reinterpret_cast<const u32x4 *>(src + 32 * kk);
+            if (!ok) v = (u32x4){0u, 0u, 0u, 0u};
+            if (QLDS) {
+                if (ks == 0) *reinterpret_cast<u32x4 *>(s_q + ((((rh * MT + mt) * 4 + kk) * 64) + lane) * 4) = v;
+            } else {
+                qreg[mt][kk] = __builtin_bit_cast(bf16x8, v);
             }
         }
     }
-    __syncthreads();
-    const uint32_t *qw = s_q + (size_t)(rh * MT) * 4 * 64 * 4 + lane * 4;
+    __syncthreads();        // s_anc and s_q are ready
+    const uint32_t *qw = s_q + (QLDS ? (size_t)(rh * MT) * 4 * 64 * 4 + lane * 4 : 0);
 
     f32x4 oacc[8][MT];
 #pragma unroll
@@ -160,104 +174,132 @@ __global__ __launch_bounds__(RH * KS * 64) void tree_attn_mfma_kernel(AttnParams
     for (int mt = 0; mt < MT; ++mt) { m_used[mt] = M_INIT; l_part[mt] = 0.f; }
 
     const size_t kv_head = (size_t)b * p.H_kv + g;
-    const uint16_t *kpre = static_cast<const uint16_t *>(p.k_prefix) + kv_head * (size_t)p.L_stride * D;
-    const uint16_t *vpre = static_cast<const uint16_t *>(p.v_prefix) + kv_head * (size_t)p.L_stride * D;
-    const uint16_t *ktre = static_cast<const uint16_t *>(p.k_tree) + kv_head * (size_t)p.N * D;
-    const uint16_t *vtre = static_cast<const uint16_t *>(p.v_tree) + kv_head * (size_t)p.N * D;
+    const char *kpre = static_cast<const char *>(p.k_prefix) + kv_head * (size_t)p.L_stride * (D * 2);
+    const char *vpre = static_cast<const char *>(p.v_prefix) + kv_head * (size_t)p.L_stride * (D * 2);
+    const char *ktre = static_cast<const char *>(p.k_tree) + kv_head * (size_t)p.N * (D * 2);
+    const char *vtre = static_cast<const char *>(p.v_tree) + kv_head * (size_t)p.N * (D * 2);
 
-    // Tile addressing.  Rows past the end of a partial tile are clamped to its last valid
-    // row (their scores are masked below), so no load leaves the arrays.
-    auto tile_base = [&](int t, const uint16_t *&kb, const uint16_t *&vb, int &nvalid) {
+    // Per-lane byte offsets inside a full tile (row pitch 256 B).
+    //   K load i (0..7): row 4 i + lj, 16-byte granule lc  ->  i * 1024 + lane * 16
+    //   V load s (0..7): row (s < 4 ? 0 : 16) + 4 lj + (s & 3), granule lc
+    const uint32_t k_lane_off = lane * 16;
+    const uint32_t v_lane_off = lj * 1024 + lc * 16;
+    // LDS positions (in 16-byte granules inside this wave's area).
+    //   K granule (row r, granule c) is the operand of lane (c & 3, r & 15) for (sub = r >> 4, kk = c >> 2):
+    //   position (sub 4 + kk) 64 + (c & 3) 16 + ((r & 15) ^ c)
+    uint32_t *area = s_big + wave * AREA_WORDS;
+    uint32_t kst_pos[4];        // store position of K load i: kst_pos[i & 3] + (i >> 2) * 256
+#pragma unroll
+    for (int j = 0; j < 4; ++j) kst_pos[j] = (lc >> 2) * 64 + (lc & 3) * 16 + ((4 * j + lj) ^ lc);
+    uint32_t kld_pos[4];        // operand position for kk: kld_pos[kk] + sub * 256
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) kld_pos[kk] = kk * 64 + lj * 16 + (lc ^ (4 * kk + lj));
+    //   V: column 8 lc + e of the lane's 8x8 block goes to lane 8 (lc & 1) + e of d-tile lc >> 1
+    const uint32_t vst_base = (lj * 8 + (lc >> 1)) * 16;
+    const uint32_t vst_x = (8 * (lc & 1)) ^ (lc >> 1);      // position = vst_base + (vst_x ^ e)
+    const uint32_t vld_base = lj * 128;                      // position = vld_base + nt * 16 + (lc ^ nt)
+
+    struct TileRef { const char *k, *v; int nvalid; bool tree; int tt; };
+    auto tile_ref = [&](int t) {
+        TileRef r;
         if (t < tilesP) {
-            kb = kpre + (size_t)t * KT * D; vb = vpre + (size_t)t * KT * D;
-            nvalid = min(KT, L - t * KT);
+            r.k = kpre + (size_t)t * TILE_BYTES; r.v = vpre + (size_t)t * TILE_BYTES;
+            r.nvalid = min(KT, L - t * KT); r.tree = false; r.tt = 0;
         } else {
-            const int tt = t - tilesP;
-            kb = ktre + (size_t)tt * KT * D; vb = vtre + (size_t)tt * KT * D;
-            nvalid = min(KT, p.N - tt * KT);
+            r.tt = t - tilesP;
+            r.k = ktre + (size_t)r.tt * TILE_BYTES; r.v = vtre + (size_t)r.tt * TILE_BYTES;
+            r.nvalid = min(KT, p.N - r.tt * KT); r.tree = true;
+        }
+        return r;
+    };
+    // Rows past the end of a partial tile are clamped to its last valid row (their scores are
+    // masked), so no load leaves the arrays.
+    u32x4 kraw[8];
+    auto load_k = [&](const TileRef &r) {
+        if (r.nvalid == KT) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) kraw[i] = *reinterpret_cast<const u32x4 *>(r.k + k_lane_off + i * 1024);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int row = min(4 * i + lj, r.nvalid - 1);
+                kraw[i] = *reinterpret_cast<const u32x4 *>(r.k + row * 256 + lc * 16);
+            }
         }
     };
-    u32x4 kraw[2][4];
-    // K: lane (lj, lc) reads key row 16 sub + lc, 16 bytes at column 32 kk + 8 lj
-    auto load_k = [&](int t) {
-        const uint16_t *kb, *vb;
-        int nvalid;
-        tile_base(t, kb, vb, nvalid);
+    u32x4 vcur[8];
+    auto load_v = [&](const TileRef &r) {
+        if (r.nvalid == KT) {
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            const int row = min(16 * sub + lc, nvalid - 1);
-            const uint16_t *src = kb + (size_t)row * D + 8 * lj;
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) kraw[sub][kk] = *reinterpret_cast<const u32x4 *>(src + 32 * kk);
-        }
-    };
-
-    uint32_t *vt = s_big + wave * 2048;
-    int t = t_begin + ks;
-    if (t < t_end) load_k(t);
-    for (; t < t_end; t += KS) {
-        // this tile's K operands leave the load registers, which are refilled for the next tile;
-        // this tile's V is requested now and consumed after the scores and the softmax
-        bf16x8 kop[2][4];
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) kop[sub][kk] = __builtin_bit_cast(bf16x8, kraw[sub][kk]);
-        u32x4 vcur[8];
-        {
-            // V: lane (lj, lc) reads the 8 key rows of its k-slot group at columns 8 lc .. 8 lc + 7
-            const uint16_t *kb, *vb;
-            int nv;
-            tile_base(t, kb, vb, nv);
+            for (int s = 0; s < 8; ++s)
+                vcur[s] = *reinterpret_cast<const u32x4 *>(r.v + v_lane_off + ((s < 4) ? 0 : 4096) + (s & 3) * 256);
+        } else {
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
-                const int row = min(((s < 4) ? 0 : 16) + 4 * lj + (s & 3), nv - 1);
-                vcur[s] = *reinterpret_cast<const u32x4 *>(vb + (size_t)row * D + 8 * lc);
+                const int row = min(((s < 4) ? 0 : 16) + 4 * lj + (s & 3), r.nvalid - 1);
+                vcur[s] = *reinterpret_cast<const u32x4 *>(r.v + row * 256 + lc * 16);
             }
         }
-        if (t + KS < t_end) load_k(t + KS);
+    };
 
-        const bool is_tree = t >= tilesP;
-        const int tt = t - tilesP;
-        const int nvalid = is_tree ? min(KT, p.N - tt * KT) : min(KT, L - t * KT);
+    const float c2 = p.scale_log2;      // >= 0 (checked by the host)
+    int t = t_begin + ks;
+    if (t < t_end) load_k(tile_ref(t));
+    for (; t < t_end; t += KS) {
+        const TileRef cur = tile_ref(t);
+        // K(t): load registers -> LDS (operand order); V(t) is requested now and consumed after
+        // the scores and the softmax; K(t + KS) is requested as soon as its registers are free.
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            *reinterpret_cast<u32x4 *>(area + 4 * (kst_pos[i & 3] + (i >> 2) * 256)) = kraw[i];
+        load_v(cur);
+        if (t + KS < t_end) load_k(tile_ref(t + KS));
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        // S^T[key][row] = sum_d K[key][d] Q[row][d]
+        // S^T[key][row] = sum_d K[key][d] Q[row][d]   (raw, the softmax scale is applied in the exponent)
         f32x4 sacc[2][MT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+        for (int mt = 0; mt < MT; ++mt) { sacc[0][mt] = (f32x4){0.f, 0.f, 0.f, 0.f}; sacc[1][mt] = (f32x4){0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const bf16x8 qop = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qw + (mt * 4 + kk) * 256));
-                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[0][kk], qop, acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[1][kk], qop, acc1, 0, 0, 0);
-            }
-            sacc[0][mt] = acc0 * p.scale_log2;
-            sacc[1][mt] = acc1 * p.scale_log2;
-        }
-        // lane (lj, lc) now holds, for its row 16 mt + lc, keys 16 sub + 4 lj + i
-        if (nvalid < KT || is_tree) {
+        for (int kk = 0; kk < 4; ++kk) {
+            const bf16x8 k0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(area + 4 * kld_pos[kk]));
+            const bf16x8 k1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(area + 4 * (kld_pos[kk] + 256)));
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                const uint32_t vis = is_tree ? s_anc[node_of[mt]][tt] : 0xffffffffu;
+                bf16x8 qop;
+                if (QLDS) qop = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qw + (mt * 4 + kk) * 256));
+                else qop = qreg[mt][kk];
+                sacc[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qop, sacc[0][mt], 0, 0, 0);
+                sacc[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qop, sacc[1][mt], 0, 0, 0);
+            }
+        }
+        // lane (lj, lc) now holds, for its row 16 mt + lc, keys 16 sub + 4 lj + i
+        const bool masked = cur.nvalid < KT || cur.tree;
+        uint32_t onmask[MT];
+        if (masked) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                uint32_t vis = cur.tree ? s_anc[node_of[mt]][cur.tt] : 0xffffffffu;
+                if (cur.nvalid < KT) vis &= (1u << cur.nvalid) - 1u;
+                onmask[mt] = vis;
 #pragma unroll
                 for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int key = 16 * sub + 4 * lj + i;
-                        const bool on = (key < nvalid) && ((vis >> key) & 1u);
-                        if (!on) sacc[sub][mt][i] = -INFINITY;
-                    }
+                    for (int i = 0; i < 4; ++i)
+                        if (!((vis >> (16 * sub + 4 * lj + i)) & 1u)) sacc[sub][mt][i] = -INFINITY;
             }
         }
-        // online softmax with a lazily raised running max
+        // online softmax with a lazily raised running max (scaled, base-2 domain)
         bool raise = false;
         float lmax[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             float m0 = fmaxf(fmaxf(sacc[0][mt][0], sacc[0][mt][1]), fmaxf(sacc[0][mt][2], sacc[0][mt][3]));
             float m1 = fmaxf(fmaxf(sacc[1][mt][0], sacc[1][mt][1]), fmaxf(sacc[1][mt][2], sacc[1][mt][3]));
-            lmax[mt] = fmaxf(m0, m1);
+            const float mr = fmaxf(m0, m1);
+            lmax[mt] = (mr == -INFINITY) ? -INFINITY : mr * c2;
             raise |= lmax[mt] > m_used[mt] + RESCALE_GAP;
         }
         if (__any(raise)) {
@@ -281,30 +323,34 @@ __global__ __launch_bounds__(RH * KS * 64) void tree_attn_mfma_kernel(AttnParams
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) pv[4 * sub + i] = exp2f(sacc[sub][mt][i] - m_used[mt]);
+                for (int i = 0; i < 4; ++i) pv[4 * sub + i] = exp2f(fmaf(sacc[sub][mt][i], c2, -m_used[mt]));
+            if (masked) {
+                // also covers scale == 0, where a masked score can not be told apart by its value
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (!((onmask[mt] >> (16 * sub + 4 * lj + i)) & 1u)) pv[4 * sub + i] = 0.f;
+            }
             l_part[mt] += ((pv[0] + pv[1]) + (pv[2] + pv[3])) + ((pv[4] + pv[5]) + (pv[6] + pv[7]));
             u32x4 pk = {pack_bf16(pv[0], pv[1]), pack_bf16(pv[2], pv[3]), pack_bf16(pv[4], pv[5]), pack_bf16(pv[6], pv[7])};
             pop[mt] = __builtin_bit_cast(bf16x8, pk);
         }
 
-        // V tile -> V^T operands.  In-lane 8x8 transpose of 16-bit elements: the lane
-        // holds 8 key rows x 8 columns and needs, per column, the 8 keys packed.
-        // Then an exchange inside each 16-lane group through LDS: column 8 lc + e
-        // belongs to lane 8 (lc & 1) + e of the operand for d-tile lc >> 1.
-        {
-            const int nt_w = lc >> 1, cb = 8 * (lc & 1);
+        // V tile -> V^T operands (the K operands in the area are dead by now: LDS ops of one wave
+        // execute in order)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int w = e >> 1;
-                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-                u32x4 o;
-                o[0] = __builtin_amdgcn_perm(vcur[1][w], vcur[0][w], sel);
-                o[1] = __builtin_amdgcn_perm(vcur[3][w], vcur[2][w], sel);
-                o[2] = __builtin_amdgcn_perm(vcur[5][w], vcur[4][w], sel);
-                o[3] = __builtin_amdgcn_perm(vcur[7][w], vcur[6][w], sel);
-                const int slot = (lj * 8 + nt_w) * 16 + ((cb + e) ^ nt_w);
-                *reinterpret_cast<u32x4 *>(vt + 4 * slot) = o;
-            }
+        for (int e = 0; e < 8; ++e) {
+            const int w = e >> 1;
+            const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+            u32x4 o;
+            o[0] = __builtin_amdgcn_perm(vcur[1][w], vcur[0][w], sel);
+            o[1] = __builtin_amdgcn_perm(vcur[3][w], vcur[2][w], sel);
+            o[2] = __builtin_amdgcn_perm(vcur[5][w], vcur[4][w], sel);
+            o[3] = __builtin_amdgcn_perm(vcur[7][w], vcur[6][w], sel);
+            *reinterpret_cast<u32x4 *>(area + 4 * (vst_base + (vst_x ^ e))) = o;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -312,8 +358,7 @@ __global__ __launch_bounds__(RH * KS * 64) void tree_attn_mfma_kernel(AttnParams
         // O^T[d][row] += sum_key V[key][d] P[row][key]
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt) {
-            const int slot = (lj * 8 + nt) * 16 + (lc ^ nt);
-            const bf16x8 vop = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(vt + 4 * slot));
+            const bf16x8 vop = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(area + 4 * (vld_base + nt * 16 + (lc ^ nt))));
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
                 oacc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pop[mt], oacc[nt][mt], 0, 0, 0);
@@ -322,7 +367,9 @@ __global__ __launch_bounds__(RH * KS * 64) void tree_attn_mfma_kernel(AttnParams
         __builtin_amdgcn_wave_barrier();
     }
 
-    // ---- merge the key streams: (m, l) per row through LDS, O through s_obuf[d][row]
+    // ---- epilogue: merge the key streams.  (m, l) per row through LDS; O in two halves of d:
+    // every wave stores its rescaled half as float4 rows [row][68] in its own area, then all
+    // threads add up the KS areas of a row group and write the result.
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         float lt = l_part[mt];
@@ -330,7 +377,7 @@ __global__ __launch_bounds__(RH * KS * 64) void tree_attn_mfma_kernel(AttnParams
         lt += __shfl_xor(lt, 32);
         if (lj == 0) { s_m[ks][WROWS * rh + 16 * mt + lc] = m_used[mt]; s_l[ks][WROWS * rh + 16 * mt + lc] = lt; }
     }
-    __syncthreads();        // also: every wave is done with its V staging area, which becomes s_obuf
+    __syncthreads();
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int r = WROWS * rh + 16 * mt + lc;
@@ -349,53 +396,52 @@ __global__ __launch_bounds__(RH * KS * 64) void tree_attn_mfma_kernel(AttnParams
 #pragma unroll
         for (int k2 = 0; k2 < KS; ++k2) ls += exp2f(s_m[k2][tid] - ms) * s_l[k2][tid];
         s_mstar[tid] = ms;
-        s_lstar[tid] = ls;
+        s_linv[tid] = (n_chunks == 1) ? 1.0f / ls : ls;
     }
-    for (int k2 = 0; k2 < KS; ++k2) {
-        if (ks == k2) {
+    const int rows_valid = min(ROWS, p.M - row0);
+    const size_t unit = (kv_head * p.n_chunks_max + chunk) * (size_t)p.R + row0;
+    float *farea = reinterpret_cast<float *>(area);
 #pragma unroll
-            for (int nt = 0; nt < 8; ++nt)
+    for (int half = 0; half < 2; ++half) {
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
+        for (int n4 = 0; n4 < 4; ++n4)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int idx = (16 * nt + 4 * lj + i) * OLD + WROWS * rh + 16 * mt + lc;
-                        if (k2 == 0) s_obuf[idx] = oacc[nt][mt][i];
-                        else s_obuf[idx] += oacc[nt][mt][i];
-                    }
+            for (int mt = 0; mt < MT; ++mt) {
+                const f32x4 v = oacc[4 * half + n4][mt];       // d = 64 half + 16 n4 + 4 lj + (0..3), row 16 mt + lc
+                *reinterpret_cast<f32x4 *>(farea + (16 * mt + lc) * 68 + 16 * n4 + 4 * lj) = v;
+            }
+        __syncthreads();
+        for (int idx = tid; idx < rows_valid * 8; idx += NT) {
+            const int r = idx >> 3, d8 = idx & 7;
+            const int rg = r / WROWS, rl = r % WROWS;
+            float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int k2 = 0; k2 < KS; ++k2) {
+                const float *src = reinterpret_cast<const float *>(s_big + (rg * KS + k2) * AREA_WORDS) + rl * 68 + 8 * d8;
+                const f32x4 a0 = *reinterpret_cast<const f32x4 *>(src);
+                const f32x4 a1 = *reinterpret_cast<const f32x4 *>(src + 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { acc[e] += a0[e]; acc[4 + e] += a1[e]; }
+            }
+            const int dcol = 64 * half + 8 * d8;
+            if (n_chunks == 1) {
+                const float inv = s_linv[r];
+                u32x4 pk = {pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv),
+                            pack_bf16(acc[4] * inv, acc[5] * inv), pack_bf16(acc[6] * inv, acc[7] * inv)};
+                const int gr = row0 + r, node = gr / p.G, hh = gr % p.G;
+                uint16_t *ob = static_cast<uint16_t *>(p.out);
+                *reinterpret_cast<u32x4 *>(ob + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + dcol) = pk;
+            } else {
+                float *dst = p.part_o + (unit + r) * D + dcol;
+                *reinterpret_cast<f32x4 *>(dst) = (f32x4){acc[0], acc[1], acc[2], acc[3]};
+                *reinterpret_cast<f32x4 *>(dst + 4) = (f32x4){acc[4], acc[5], acc[6], acc[7]};
+            }
         }
         __syncthreads();
     }
-
-    const int rows_valid = min(ROWS, p.M - row0);
-    if (n_chunks == 1) {
-        // the only chunk of this sequence: normalise and write the output rows
-        uint16_t *ob = static_cast<uint16_t *>(p.out);
-        for (int idx = tid; idx < rows_valid * (D / 8); idx += NW * 64) {
-            const int r = idx / (D / 8), d8 = idx % (D / 8);
-            const float inv = 1.0f / s_lstar[r];
-            float v[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = s_obuf[(8 * d8 + e) * OLD + r] * inv;
-            u32x4 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
-            const int gr = row0 + r, node = gr / p.G, hh = gr % p.G;
-            *reinterpret_cast<u32x4 *>(ob + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + 8 * d8) = pk;
-        }
-    } else {
-        const size_t unit = (kv_head * p.n_chunks_max + chunk) * (size_t)p.R + row0;
-        for (int idx = tid; idx < rows_valid * (D / 4); idx += NW * 64) {
-            const int r = idx / (D / 4), d4 = idx % (D / 4);
-            float4 v;
-            v.x = s_obuf[(4 * d4 + 0) * OLD + r];
-            v.y = s_obuf[(4 * d4 + 1) * OLD + r];
-            v.z = s_obuf[(4 * d4 + 2) * OLD + r];
-            v.w = s_obuf[(4 * d4 + 3) * OLD + r];
-            *reinterpret_cast<float4 *>(p.part_o + (unit + r) * D + 4 * d4) = v;
-        }
-        if (tid < rows_valid) {
-            p.part_m[unit + tid] = s_mstar[tid];
-            p.part_l[unit + tid] = s_lstar[tid];
-        }
+    if (n_chunks > 1 && tid < rows_valid) {
+        p.part_m[unit + tid] = s_mstar[tid];
+        p.part_l[unit + tid] = s_linv[tid];
     }
 }
 
@@ -556,10 +602,10 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
         *plan = pl;
         return true;
     }
-    // Kernel variant: 0 = 32 rows x 8 key streams, 1 = 2 x 32 rows x 4 key streams (both 8 waves,
-    // two per SIMD: the choice when the KV stream from HBM is the bound), 2 = 64 rows per wave x 4
-    // key streams (half the K/V operand traffic per flop: the choice when many row tiles share a
-    // KV head and the matrix cores are the bound).
+    // Kernel variant (all 4 waves): 0 = 32 rows x 4 key streams, 1 = 2 x 32 rows x 2 key streams
+    // (two workgroups per CU, two waves per SIMD: the choice when the KV stream from HBM is the
+    // bound), 2 = 64 rows per wave x 4 key streams (half the K/V operand traffic per flop: the
+    // choice when many row tiles share a KV head and the matrix cores are the bound).
     pl.row_tile = pl.rows_per_kv <= 32 ? 32 : 64;
     pl.variant = pl.rows_per_kv <= 32 ? 0 : (pl.rows_per_kv <= 128 ? 1 : 2);
     {
@@ -569,7 +615,7 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
             pl.row_tile = pl.variant == 0 ? 32 : 64;
         }
     }
-    const int key_streams = pl.variant == 0 ? 8 : 4;
+    const int key_streams = pl.variant == 1 ? 2 : 4;
     pl.n_row_tiles = (pl.rows_per_kv + pl.row_tile - 1) / pl.row_tile;
     pl.tiles_prefix_max = (d.L_stride + KT - 1) / KT;
     pl.tiles_tree = (d.N + KT - 1) / KT;
@@ -634,9 +680,9 @@ int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const
     dim3 grid(plan.n_chunks_max * plan.n_row_tiles, d.H_kv, d.B);
     timing_begin(K_ATTN_MFMA, stream);
     if (plan.variant == 0)
-        hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 1, 8>), grid, dim3(512), 0, stream, p);
+        hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 1, 4>), grid, dim3(256), 0, stream, p);
     else if (plan.variant == 1)
-        hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, 4>), grid, dim3(512), 0, stream, p);
+        hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, 2>), grid, dim3(256), 0, stream, p);
     else
         hipLaunchKernelGGL((tree_attn_mfma_kernel<4, 1, 4>), grid, dim3(256), 0, stream, p);
     timing_end(K_ATTN_MFMA, stream);
