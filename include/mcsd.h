@@ -101,7 +101,7 @@ typedef struct {
     int32_t H_q, H_kv;      /* query / KV heads, H_q % H_kv == 0 */
     int32_t d;              /* head dim: multiple of 4 (fp32) or 8 (bf16), <= MCSD_MAX_HEAD_DIM */
     int32_t dtype;          /* MCSD_DTYPE_* of q, k_*, v_*, out */
-    int32_t L_stride;       /* rows allocated per (sequence, KV head) in the prefix cache; prefix_len[b] <= L_stride */
+    int32_t L_stride;       /* rows allocated per (sequence, KV head) in the prefix cache; prefix_len[b] <= L_stride <= 2^22 */
     float scale;            /* softmax scale, finite and >= 0, normally 1/sqrt(d) */
     int32_t parent_per_seq; /* 0: one parent[N] shared by the batch; 1: parent[B][N] */
 } mcsd_attn_desc;

@@ -122,6 +122,7 @@ static int32_t check_attn(const mcsd_attn_desc *d, const mcsd_attn_bufs *b, Attn
     if (!d) { set_error("attn desc is NULL"); return MCSD_E_NULL; }
     if (d->struct_size != sizeof(mcsd_attn_desc)) { set_error("attn desc struct_size %u != %zu", d->struct_size, sizeof(mcsd_attn_desc)); return MCSD_E_SHAPE; }
     if (d->B < 1 || d->H_q < 1 || d->H_kv < 1 || d->d < 1 || d->L_stride < 0) { set_error("attn: non-positive size"); return MCSD_E_SHAPE; }
+    if (d->L_stride > (1 << 22)) { set_error("attn: L_stride %d > %d", d->L_stride, 1 << 22); return MCSD_E_UNSUPPORTED; }
     if (d->N < 1 || d->N > MCSD_MAX_NODES) { set_error("attn: N %d outside 1..%d", d->N, MCSD_MAX_NODES); return MCSD_E_TREE; }
     if (d->H_q % d->H_kv != 0) { set_error("attn: H_q %d not a multiple of H_kv %d", d->H_q, d->H_kv); return MCSD_E_SHAPE; }
     if (d->dtype != MCSD_DTYPE_FP32 && d->dtype != MCSD_DTYPE_BF16) { set_error("attn: unknown dtype %d", d->dtype); return MCSD_E_UNSUPPORTED; }

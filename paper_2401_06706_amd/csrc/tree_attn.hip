@@ -59,6 +59,17 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
     return __builtin_bit_cast(uint32_t, v);
 }
 
+// Raw buffer resource over [ptr, ptr + bytes): reads past the end return zero.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *ptr, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(ptr), 0, bytes, 0x00020000);
+}
+
+__device__ __forceinline__ float fast_exp2(float x)
+{
+    return __builtin_amdgcn_exp2f(x);      // v_exp_f32; results below the normal range flush to 0
+}
+
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16)
 {
     return __uint_as_float(bits16 << 16);
@@ -113,9 +124,12 @@ void tree_attn_mfma_kernel(AttnParams p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps tile indices and pointers scalar
     const int rh = wave / KS, ks = wave % KS;
     const int lj = lane >> 4, lc = lane & 15;
-    const int rt = blockIdx.x % p.n_row_tiles;
-    const int chunk = blockIdx.x / p.n_row_tiles;
-    const int g = blockIdx.y, b = blockIdx.z;
+    // Workgroup ids are handed to the 8 XCDs round-robin, so the KV head is the fastest grid
+    // index: every XCD gets the same mix of long and short chunks, and the row tiles that share
+    // a KV head and chunk (grouped-query attention) run on one XCD and share its L2.
+    const int g = blockIdx.x, b = blockIdx.z;
+    const int rt = blockIdx.y % p.n_row_tiles;
+    const int chunk = blockIdx.y / p.n_row_tiles;
 
     int L = p.prefix_len[b];
     L = max(0, min(L, p.L_stride));
@@ -174,12 +188,16 @@ void tree_attn_mfma_kernel(AttnParams p)
     for (int mt = 0; mt < MT; ++mt) { m_used[mt] = M_INIT; l_part[mt] = 0.f; }
 
     const size_t kv_head = (size_t)b * p.H_kv + g;
-    const char *kpre = static_cast<const char *>(p.k_prefix) + kv_head * (size_t)p.L_stride * (D * 2);
-    const char *vpre = static_cast<const char *>(p.v_prefix) + kv_head * (size_t)p.L_stride * (D * 2);
-    const char *ktre = static_cast<const char *>(p.k_tree) + kv_head * (size_t)p.N * (D * 2);
-    const char *vtre = static_cast<const char *>(p.v_tree) + kv_head * (size_t)p.N * (D * 2);
+    // K and V of this (sequence, KV head) are read through buffer resources whose extent is
+    // exactly the valid rows (prefix_len rows of the cache slab, N rows of the tree block):
+    // the tile base is a scalar offset, the lane offset a constant, and rows past the end of
+    // a partial tile read as zero instead of leaving the array (their scores are masked).
+    const __amdgpu_buffer_rsrc_t rs_kpre = make_rsrc(static_cast<const char *>(p.k_prefix) + kv_head * (size_t)p.L_stride * (D * 2), (uint32_t)L * (D * 2));
+    const __amdgpu_buffer_rsrc_t rs_vpre = make_rsrc(static_cast<const char *>(p.v_prefix) + kv_head * (size_t)p.L_stride * (D * 2), (uint32_t)L * (D * 2));
+    const __amdgpu_buffer_rsrc_t rs_ktre = make_rsrc(static_cast<const char *>(p.k_tree) + kv_head * (size_t)p.N * (D * 2), (uint32_t)p.N * (D * 2));
+    const __amdgpu_buffer_rsrc_t rs_vtre = make_rsrc(static_cast<const char *>(p.v_tree) + kv_head * (size_t)p.N * (D * 2), (uint32_t)p.N * (D * 2));
 
-    // Per-lane byte offsets inside a full tile (row pitch 256 B).
+    // Per-lane byte offsets inside a tile (row pitch 256 B).
     //   K load i (0..7): row 4 i + lj, 16-byte granule lc  ->  i * 1024 + lane * 16
     //   V load s (0..7): row (s < 4 ? 0 : 16) + 4 lj + (s & 3), granule lc
     const uint32_t k_lane_off = lane * 16;
@@ -199,47 +217,29 @@ void tree_attn_mfma_kernel(AttnParams p)
     const uint32_t vst_x = (8 * (lc & 1)) ^ (lc >> 1);      // position = vst_base + (vst_x ^ e)
     const uint32_t vld_base = lj * 128;                      // position = vld_base + nt * 16 + (lc ^ nt)
 
-    struct TileRef { const char *k, *v; int nvalid; bool tree; int tt; };
+    struct TileRef { int off; int nvalid; bool tree; int tt; };
     auto tile_ref = [&](int t) {
         TileRef r;
         if (t < tilesP) {
-            r.k = kpre + (size_t)t * TILE_BYTES; r.v = vpre + (size_t)t * TILE_BYTES;
-            r.nvalid = min(KT, L - t * KT); r.tree = false; r.tt = 0;
+            r.off = t * TILE_BYTES; r.nvalid = min(KT, L - t * KT); r.tree = false; r.tt = 0;
         } else {
             r.tt = t - tilesP;
-            r.k = ktre + (size_t)r.tt * TILE_BYTES; r.v = vtre + (size_t)r.tt * TILE_BYTES;
-            r.nvalid = min(KT, p.N - r.tt * KT); r.tree = true;
+            r.off = r.tt * TILE_BYTES; r.nvalid = min(KT, p.N - r.tt * KT); r.tree = true;
         }
         return r;
     };
-    // Rows past the end of a partial tile are clamped to its last valid row (their scores are
-    // masked), so no load leaves the arrays.
     u32x4 kraw[8];
     auto load_k = [&](const TileRef &r) {
-        if (r.nvalid == KT) {
+        const __amdgpu_buffer_rsrc_t rs = r.tree ? rs_ktre : rs_kpre;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) kraw[i] = *reinterpret_cast<const u32x4 *>(r.k + k_lane_off + i * 1024);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int row = min(4 * i + lj, r.nvalid - 1);
-                kraw[i] = *reinterpret_cast<const u32x4 *>(r.k + row * 256 + lc * 16);
-            }
-        }
+        for (int i = 0; i < 8; ++i) kraw[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off + i * 1024, r.off, 0);
     };
     u32x4 vcur[8];
     auto load_v = [&](const TileRef &r) {
-        if (r.nvalid == KT) {
+        const __amdgpu_buffer_rsrc_t rs = r.tree ? rs_vtre : rs_vpre;
 #pragma unroll
-            for (int s = 0; s < 8; ++s)
-                vcur[s] = *reinterpret_cast<const u32x4 *>(r.v + v_lane_off + ((s < 4) ? 0 : 4096) + (s & 3) * 256);
-        } else {
-#pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                const int row = min(((s < 4) ? 0 : 16) + 4 * lj + (s & 3), r.nvalid - 1);
-                vcur[s] = *reinterpret_cast<const u32x4 *>(r.v + row * 256 + lc * 16);
-            }
-        }
+        for (int s = 0; s < 8; ++s)
+            vcur[s] = __builtin_amdgcn_raw_buffer_load_b128(rs, v_lane_off + ((s < 4) ? 0 : 4096) + (s & 3) * 256, r.off, 0);
     };
 
     const float c2 = p.scale_log2;      // >= 0 (checked by the host)
@@ -309,7 +309,7 @@ void tree_attn_mfma_kernel(AttnParams p)
                 rm = fmaxf(rm, __shfl_xor(rm, 16));
                 rm = fmaxf(rm, __shfl_xor(rm, 32));
                 const float m_new = fmaxf(m_used[mt], rm);
-                const float alpha = exp2f(m_used[mt] - m_new);
+                const float alpha = fast_exp2(m_used[mt] - m_new);
                 m_used[mt] = m_new;
                 l_part[mt] *= alpha;
 #pragma unroll
@@ -323,7 +323,7 @@ void tree_attn_mfma_kernel(AttnParams p)
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) pv[4 * sub + i] = exp2f(fmaf(sacc[sub][mt][i], c2, -m_used[mt]));
+                for (int i = 0; i < 4; ++i) pv[4 * sub + i] = fast_exp2(fmaf(sacc[sub][mt][i], c2, -m_used[mt]));
             if (masked) {
                 // also covers scale == 0, where a masked score can not be told apart by its value
 #pragma unroll
@@ -640,7 +640,7 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
     } else {
         pl.ws_bytes = 0;
     }
-    if ((long)pl.n_chunks_max * pl.n_row_tiles > 2147483647L || d.H_kv > 65535 || d.B > 65535) return false;
+    if ((long)pl.n_chunks_max * pl.n_row_tiles > 65535L || d.B > 65535) return false;
     *plan = pl;
     return true;
 }
@@ -677,7 +677,7 @@ int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const
         p.part_m = ws + rows * d.d;
         p.part_l = p.part_m + rows;
     }
-    dim3 grid(plan.n_chunks_max * plan.n_row_tiles, d.H_kv, d.B);
+    dim3 grid(d.H_kv, plan.n_chunks_max * plan.n_row_tiles, d.B);
     timing_begin(K_ATTN_MFMA, stream);
     if (plan.variant == 0)
         hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 1, 4>), grid, dim3(256), 0, stream, p);
