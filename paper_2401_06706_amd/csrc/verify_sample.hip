@@ -18,14 +18,13 @@
 // so that the comparison u <= min(1, p/q) is taken at far better than the 1e-6
 // near-tie band; vocabulary-wide passes are fp32 with fp64 accumulation.
 #include <math.h>
+#include <stdlib.h>
 
 #include "mcsd_internal.h"
 
 namespace mcsd {
 namespace {
 
-constexpr int VT = 1024;           // threads per workgroup
-constexpr int NWAVES = VT / 64;
 constexpr float LOG2E_F = 1.44269504088896340736f;
 
 struct VerifyParams {
@@ -55,6 +54,7 @@ __device__ __forceinline__ double wave_sum(double v)
 }
 
 // Every thread returns the same value (fixed summation order over the waves).
+template <int NWAVES>
 __device__ __forceinline__ double block_sum(double v, double *s_red)
 {
     v = wave_sum(v);
@@ -68,6 +68,7 @@ __device__ __forceinline__ double block_sum(double v, double *s_red)
 }
 
 // Two sums in one pass (same barriers): a -> first, b -> second.
+template <int NWAVES>
 __device__ __forceinline__ void block_sum2(double &a, double &b, double *s_red, double *s_red2)
 {
     a = wave_sum(a);
@@ -82,6 +83,7 @@ __device__ __forceinline__ void block_sum2(double &a, double &b, double *s_red, 
     b = rb;
 }
 
+template <int NWAVES>
 __device__ __forceinline__ float block_max(float v, float *s_red)
 {
     v = wave_max(v);
@@ -94,7 +96,30 @@ __device__ __forceinline__ float block_max(float v, float *s_red)
     return r;
 }
 
-template <int ITEMS, bool ALIGNED>
+// Two maxima in one pass.
+template <int NWAVES>
+__device__ __forceinline__ void block_max2(float &a, float &b, float *s_red, float *s_red2)
+{
+    a = wave_max(a);
+    b = wave_max(b);
+    if ((threadIdx.x & 63) == 0) { s_red[threadIdx.x >> 6] = a; s_red2[threadIdx.x >> 6] = b; }
+    __syncthreads();
+    float ra = s_red[0], rb = s_red2[0];
+#pragma unroll
+    for (int w = 1; w < NWAVES; ++w) { ra = fmaxf(ra, s_red[w]); rb = fmaxf(rb, s_red2[w]); }
+    __syncthreads();
+    a = ra;
+    b = rb;
+}
+
+// Sum of the four lanes of a float4, exact in fp64: the normalisers A and Z_q enter the accept
+// ratios divided by the rejection probabilities, so their rounding must stay far below 1e-6.
+__device__ __forceinline__ double sum4(const float4 &v)
+{
+    return ((double)v.x + (double)v.y) + ((double)v.z + (double)v.w);
+}
+
+template <int ITEMS, int VT, bool ALIGNED>
 __device__ __forceinline__ void load_row(const float *z, int V, float4 (&r)[ITEMS])
 {
     const float ninf = -INFINITY;
@@ -121,23 +146,28 @@ __device__ __forceinline__ float row_max(const float4 (&r)[ITEMS])
     return m;
 }
 
-// r := exp((r - m) / T), returns this thread's partial sum in fp64.
+// r := 2^((r - m) c) with c = log2(e) / T, i.e. exp((r - m) / T); returns this thread's partial
+// sum in fp64.  The subtraction comes first on purpose: the row maximum maps to exactly 1, so
+// when one token dominates both distributions (p ~ q, small rejection probability) the residual
+// max(0, p - q) does not inherit a rounding error from its largest, cancelling term.
 template <int ITEMS>
 __device__ __forceinline__ double row_exp(float4 (&r)[ITEMS], float m, float c)
 {
     double s = 0.0;
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
-        r[i].x = exp2f((r[i].x - m) * c);
-        r[i].y = exp2f((r[i].y - m) * c);
-        r[i].z = exp2f((r[i].z - m) * c);
-        r[i].w = exp2f((r[i].w - m) * c);
-        s += ((double)r[i].x + (double)r[i].y) + ((double)r[i].z + (double)r[i].w);
+        // v_exp_f32 directly: results below the normal range flush to zero, which is what
+        // a probability of 2^-126 relative to the mode should become anyway
+        r[i].x = __builtin_amdgcn_exp2f((r[i].x - m) * c);
+        r[i].y = __builtin_amdgcn_exp2f((r[i].y - m) * c);
+        r[i].z = __builtin_amdgcn_exp2f((r[i].z - m) * c);
+        r[i].w = __builtin_amdgcn_exp2f((r[i].w - m) * c);
+        s += sum4(r[i]);
     }
     return s;
 }
 
-template <int ITEMS, bool ALIGNED>
+template <int ITEMS, int VT, bool ALIGNED>
 __device__ __forceinline__ void store_row_scaled(float *dst, int V, const float4 (&r)[ITEMS], float s)
 {
 #pragma unroll
@@ -159,16 +189,17 @@ __device__ __forceinline__ void store_row_scaled(float *dst, int V, const float4
 // with sum_{y <= x} a(y) > u * A, found by a two-level search: (1) totals of the
 // ITEMS contiguous 4096-token segments, (2) a block-wide inclusive scan inside
 // the segment that holds the crossing.  fp64 throughout.
-template <int ITEMS>
+template <int ITEMS, int VT>
 __device__ __forceinline__ int inverse_cdf(const float4 (&a)[ITEMS], double A, double u, double eps,
                                            double *s_red, double *s_seg, int *s_int, uint32_t *flag_bits)
 {
+    constexpr int NWAVES = VT / 64;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const double tau = u * A;
     double seg[ITEMS];
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
-        seg[i] = ((double)a[i].x + (double)a[i].y) + ((double)a[i].z + (double)a[i].w);
+        seg[i] = sum4(a[i]);
         double w = wave_sum(seg[i]);
         if (lane == 0) s_seg[wave * ITEMS + i] = w;
     }
@@ -247,9 +278,10 @@ __device__ __forceinline__ int inverse_cdf(const float4 (&a)[ITEMS], double A, d
     return token;
 }
 
-template <int ITEMS, bool ALIGNED>
+template <int ITEMS, int VT, bool ALIGNED>
 __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
 {
+    constexpr int NWAVES = VT / 64;
     const int row = blockIdx.x, b = blockIdx.y;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int N = p.N, V = p.V;
@@ -258,6 +290,7 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     __shared__ double s_red2[NWAVES];
     __shared__ double s_seg[NWAVES * ITEMS];
     __shared__ float s_redf[NWAVES];
+    __shared__ float s_redf2[NWAVES];
     __shared__ unsigned long long s_mask[2];
     __shared__ int s_kids[MCSD_MAX_NODES];
     __shared__ int s_k;
@@ -303,7 +336,7 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     const float NaN = __int_as_float(0x7fc00000);
 
     float4 a[ITEMS];
-    load_row<ITEMS, ALIGNED>(zp_row, V, a);
+    load_row<ITEMS, VT, ALIGNED>(zp_row, V, a);
 
     if (T == 0.f) {
         // argmax sampling: lowest id on ties
@@ -347,22 +380,27 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
 
     const float invT = 1.0f / T;
     const float c2 = invT * LOG2E_F;
-    const float mp = block_max(row_max<ITEMS>(a), s_redf);
-    double A = block_sum(row_exp<ITEMS>(a, mp, c2), s_red);       // a = e_p, A = Z_p
-    if (!(A > 0.0) || !isfinite(A)) {
+    // both rows are requested before anything waits on them
+    float4 eq[ITEMS];
+    const float *zq_row = zp_row;
+    if (k > 0) {
+        zq_row = p.draft_logits + ((size_t)b * p.P + p.q_row[row]) * (size_t)V;
+        load_row<ITEMS, VT, ALIGNED>(zq_row, V, eq);
+    } else {
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) eq[i] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    }
+    float mp = row_max<ITEMS>(a), mq = row_max<ITEMS>(eq);
+    block_max2<NWAVES>(mp, mq, s_redf, s_redf2);
+    double A = row_exp<ITEMS>(a, mp, c2);                 // a = e_p, A = Z_p
+    double Zq0 = (k > 0) ? row_exp<ITEMS>(eq, mq, c2) : 0.0;
+    block_sum2<NWAVES>(A, Zq0, s_red, s_red2);
+    if (!(A > 0.0) || !isfinite(A) || (k > 0 && (!(Zq0 > 0.0) || !isfinite(Zq0)))) {
         if (t == 0) atomicOr(&s_flags, (uint32_t)MCSD_FLAG_NONFINITE);
     }
 
     int accepted = -1;
     if (k > 0) {
-        float4 eq[ITEMS];
-        const float *zq_row = p.draft_logits + ((size_t)b * p.P + p.q_row[row]) * (size_t)V;
-        load_row<ITEMS, ALIGNED>(zq_row, V, eq);
-        const float mq = block_max(row_max<ITEMS>(eq), s_redf);
-        const double Zq0 = block_sum(row_exp<ITEMS>(eq, mq, c2), s_red);
-        if (!(Zq0 > 0.0) || !isfinite(Zq0)) {
-            if (t == 0) atomicOr(&s_flags, (uint32_t)MCSD_FLAG_NONFINITE);
-        }
         // fp64 track of the candidate tokens: thread c follows candidate c
         int my_tok = -1;
         double my_a = 0.0, my_q = 0.0;
@@ -372,8 +410,9 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
             my_tok = p.cand_tok[(size_t)b * N + node];
             my_u = p.u_accept[(size_t)b * N + node];
             if (my_tok >= 0 && my_tok < V) {
-                my_a = exp(((double)zp_row[my_tok] - (double)mp) * (double)invT);
-                my_q = exp(((double)zq_row[my_tok] - (double)mq) * (double)invT);
+                // same constants as the vector pass (float c2), evaluated exactly
+                my_a = exp2(((double)zp_row[my_tok] - (double)mp) * (double)c2);
+                my_q = exp2(((double)zq_row[my_tok] - (double)mq) * (double)c2);
             }
         }
         // Z_q: mass of the draft tokens not yet removed.  After a removal it is summed
@@ -423,7 +462,7 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
                 a[j].y = fmaxf(0.f, fmaf(-bl, eq[j].y, fmaf(-bh, eq[j].y, a[j].y)));
                 a[j].z = fmaxf(0.f, fmaf(-bl, eq[j].z, fmaf(-bh, eq[j].z, a[j].z)));
                 a[j].w = fmaxf(0.f, fmaf(-bl, eq[j].w, fmaf(-bh, eq[j].w, a[j].w)));
-                part += ((double)a[j].x + (double)a[j].y) + ((double)a[j].z + (double)a[j].w);
+                part += sum4(a[j]);
             }
             if (t < k) {
                 my_a = fmax(0.0, my_a - beta * my_q);
@@ -444,12 +483,12 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
                 }
 #pragma unroll
                 for (int j = 0; j < ITEMS; ++j)
-                    partq += ((double)eq[j].x + (double)eq[j].y) + ((double)eq[j].z + (double)eq[j].w);
-                block_sum2(part, partq, s_red, s_red2);   // barriers inside also order the reuse of s_accept / s_xrem
+                    partq += sum4(eq[j]);
+                block_sum2<NWAVES>(part, partq, s_red, s_red2);   // barriers inside also order the reuse of s_accept / s_xrem
                 A = part;
                 Zq = partq;
             } else {
-                A = block_sum(part, s_red);
+                A = block_sum<NWAVES>(part, s_red);
             }
             if (!(A > 0.0)) {
                 if (t == 0) atomicOr(&s_flags, (uint32_t)MCSD_FLAG_ZERO_RESIDUAL);
@@ -462,12 +501,12 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     int endpoint = -1;
     if (accepted < 0) {
         const double u = (double)p.u_endpoint[rix];
-        endpoint = inverse_cdf<ITEMS>(a, A, u, (double)p.eps, s_red, s_seg, s_int, &s_flags);
+        endpoint = inverse_cdf<ITEMS, VT>(a, A, u, (double)p.eps, s_red, s_seg, s_int, &s_flags);
         if (endpoint < 0 || endpoint >= V) endpoint = V - 1;
     }
     if (p.residual_out) {
         const float inv = (A > 0.0) ? (float)(1.0 / A) : 0.f;
-        store_row_scaled<ITEMS, ALIGNED>(p.residual_out + rix * (size_t)V, V, a, inv);
+        store_row_scaled<ITEMS, VT, ALIGNED>(p.residual_out + rix * (size_t)V, V, a, inv);
     }
     __syncthreads();
     if (t == 0) {
@@ -504,14 +543,20 @@ __global__ void walk_kernel(VerifyParams p)
     p.n_accepted[b] = n;
 }
 
-template <int ITEMS>
+template <int ITEMS, int VT>
 void launch_rows(const VerifyParams &p, hipStream_t stream)
 {
     dim3 grid(1 + p.N, p.B), block(VT);
     if (p.V % 4 == 0)
-        hipLaunchKernelGGL((verify_rows_kernel<ITEMS, true>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((verify_rows_kernel<ITEMS, VT, true>), grid, block, 0, stream, p);
     else
-        hipLaunchKernelGGL((verify_rows_kernel<ITEMS, false>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((verify_rows_kernel<ITEMS, VT, false>), grid, block, 0, stream, p);
+}
+
+int env_choice(const char *name, int dflt)
+{
+    const char *s = getenv(name);
+    return (s && *s) ? atoi(s) : dflt;
 }
 
 }  // namespace
@@ -528,13 +573,17 @@ int32_t launch_verify(const mcsd_verify_desc &d, const mcsd_verify_bufs &b, hipS
     p.acc_child = b.acc_child; p.endpoint = b.endpoint; p.ratio = b.ratio; p.flags = b.flags;
     p.residual_out = b.residual_out;
 
-    const int per_item = 4 * VT;
-    const int items = (d.V + per_item - 1) / per_item;
+    // Up to 16384 tokens a 1024-thread workgroup holds both rows in 2 x 16 registers per
+    // thread; beyond that 512 threads with twice the registers each (the 128-register
+    // ceiling of a 1024-thread workgroup would spill).
+    const int items1024 = (d.V + 4095) / 4096;
+    const bool wide = env_choice("MCSD_VERIFY_1024", 0) != 0;
     timing_begin(K_VERIFY_ROWS, stream);
-    if (items <= 1) launch_rows<1>(p, stream);
-    else if (items <= 2) launch_rows<2>(p, stream);
-    else if (items <= 4) launch_rows<4>(p, stream);
-    else launch_rows<8>(p, stream);
+    if (items1024 <= 1) launch_rows<1, 1024>(p, stream);
+    else if (items1024 <= 2) launch_rows<2, 1024>(p, stream);
+    else if (items1024 <= 4) launch_rows<4, 1024>(p, stream);
+    else if (wide) launch_rows<8, 1024>(p, stream);
+    else launch_rows<16, 512>(p, stream);
     timing_end(K_VERIFY_ROWS, stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
