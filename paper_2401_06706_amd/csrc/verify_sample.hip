@@ -39,18 +39,72 @@ struct VerifyParams {
     float *residual_out;
 };
 
-__device__ __forceinline__ float wave_max(float v)
+// Wavefront reductions on the DPP cross-lane paths (no LDS round trip).  The result is
+// complete in lane 63 only: quad swaps, half-row and row mirrors give every lane its row's
+// total, then row_bcast15 / row_bcast31 fold the four rows of 16 lanes into the last one.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_f(float old, float v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_d(double old, double v)
+{
+    const long long o = __double_as_longlong(old), x = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_update_dpp((int)o, (int)x, CTRL, ROW_MASK, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp((int)(o >> 32), (int)(x >> 32), CTRL, ROW_MASK, 0xf, false);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+
+constexpr int DPP_QUAD_1032 = 0xB1, DPP_QUAD_2301 = 0x4E, DPP_ROW_HALF_MIRROR = 0x141, DPP_ROW_MIRROR = 0x140,
+              DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143;
+
+__device__ __forceinline__ float wave_max(float v)      // valid in lane 63
+{
+    v = fmaxf(v, dpp_f<DPP_QUAD_1032, 0xf>(v, v));
+    v = fmaxf(v, dpp_f<DPP_QUAD_2301, 0xf>(v, v));
+    v = fmaxf(v, dpp_f<DPP_ROW_HALF_MIRROR, 0xf>(v, v));
+    v = fmaxf(v, dpp_f<DPP_ROW_MIRROR, 0xf>(v, v));
+    v = fmaxf(v, dpp_f<DPP_ROW_BCAST15, 0xa>(v, v));
+    v = fmaxf(v, dpp_f<DPP_ROW_BCAST31, 0xc>(v, v));
     return v;
 }
 
-__device__ __forceinline__ double wave_sum(double v)
+__device__ __forceinline__ double wave_sum(double v)    // valid in lane 63
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    v += dpp_d<DPP_QUAD_1032, 0xf>(0.0, v);
+    v += dpp_d<DPP_QUAD_2301, 0xf>(0.0, v);
+    v += dpp_d<DPP_ROW_HALF_MIRROR, 0xf>(0.0, v);
+    v += dpp_d<DPP_ROW_MIRROR, 0xf>(0.0, v);
+    v += dpp_d<DPP_ROW_BCAST15, 0xa>(0.0, v);
+    v += dpp_d<DPP_ROW_BCAST31, 0xc>(0.0, v);
     return v;
+}
+
+// 2^x in fp64 for x <= 0 (one thread per candidate token evaluates two of these): x = n + f with
+// |f| <= 1/2, 2^f = exp(f ln 2) by its Taylor series to degree 13 (|f ln 2| <= 0.35: truncation
+// below 1e-17), scaled by 2^n.  Arguments below -1000 return 0.
+__device__ __forceinline__ double exp2_neg(double x)
+{
+    if (!(x > -1000.0)) return 0.0;
+    const double n = rint(x);
+    const double y = (x - n) * 0.69314718055994530942;
+    double r = 1.0 / 6227020800.0;
+    r = fma(r, y, 1.0 / 479001600.0);
+    r = fma(r, y, 1.0 / 39916800.0);
+    r = fma(r, y, 1.0 / 3628800.0);
+    r = fma(r, y, 1.0 / 362880.0);
+    r = fma(r, y, 1.0 / 40320.0);
+    r = fma(r, y, 1.0 / 5040.0);
+    r = fma(r, y, 1.0 / 720.0);
+    r = fma(r, y, 1.0 / 120.0);
+    r = fma(r, y, 1.0 / 24.0);
+    r = fma(r, y, 1.0 / 6.0);
+    r = fma(r, y, 0.5);
+    r = fma(r, y, 1.0);
+    r = fma(r, y, 1.0);
+    return ldexp(r, (int)n);
 }
 
 // Every thread returns the same value (fixed summation order over the waves).
@@ -58,7 +112,7 @@ template <int NWAVES>
 __device__ __forceinline__ double block_sum(double v, double *s_red)
 {
     v = wave_sum(v);
-    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = v;
+    if ((threadIdx.x & 63) == 63) s_red[threadIdx.x >> 6] = v;
     __syncthreads();
     double r = 0.0;
 #pragma unroll
@@ -73,7 +127,7 @@ __device__ __forceinline__ void block_sum2(double &a, double &b, double *s_red, 
 {
     a = wave_sum(a);
     b = wave_sum(b);
-    if ((threadIdx.x & 63) == 0) { s_red[threadIdx.x >> 6] = a; s_red2[threadIdx.x >> 6] = b; }
+    if ((threadIdx.x & 63) == 63) { s_red[threadIdx.x >> 6] = a; s_red2[threadIdx.x >> 6] = b; }
     __syncthreads();
     double ra = 0.0, rb = 0.0;
 #pragma unroll
@@ -87,7 +141,7 @@ template <int NWAVES>
 __device__ __forceinline__ float block_max(float v, float *s_red)
 {
     v = wave_max(v);
-    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = v;
+    if ((threadIdx.x & 63) == 63) s_red[threadIdx.x >> 6] = v;
     __syncthreads();
     float r = s_red[0];
 #pragma unroll
@@ -102,7 +156,7 @@ __device__ __forceinline__ void block_max2(float &a, float &b, float *s_red, flo
 {
     a = wave_max(a);
     b = wave_max(b);
-    if ((threadIdx.x & 63) == 0) { s_red[threadIdx.x >> 6] = a; s_red2[threadIdx.x >> 6] = b; }
+    if ((threadIdx.x & 63) == 63) { s_red[threadIdx.x >> 6] = a; s_red2[threadIdx.x >> 6] = b; }
     __syncthreads();
     float ra = s_red[0], rb = s_red2[0];
 #pragma unroll
@@ -201,7 +255,7 @@ __device__ __forceinline__ int inverse_cdf(const float4 (&a)[ITEMS], double A, d
     for (int i = 0; i < ITEMS; ++i) {
         seg[i] = sum4(a[i]);
         double w = wave_sum(seg[i]);
-        if (lane == 0) s_seg[wave * ITEMS + i] = w;
+        if (lane == 63) s_seg[wave * ITEMS + i] = w;
     }
     if (t == 0) { s_int[0] = 0x7fffffff; s_int[1] = -1; }
     __syncthreads();
@@ -301,6 +355,27 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     __shared__ float s_bestv[NWAVES];
     __shared__ int s_besti[NWAVES];
 
+    // The two logit rows are requested first; the bookkeeping below (children list, flags)
+    // runs while they are in flight.  A row has a draft row iff q_row says so; whether it
+    // also has children is checked afterwards (a mismatch is flagged, the row then counts
+    // as a leaf and the extra row that was fetched is ignored).
+    const size_t rix = (size_t)b * (1 + N) + row;
+    const float T = p.temperature[b];
+    const float *zp_row = p.target_logits + rix * (size_t)V;
+    const float NaN = __int_as_float(0x7fc00000);
+    float4 a[ITEMS];
+    load_row<ITEMS, VT, ALIGNED>(zp_row, V, a);
+    const int qr = p.q_row[row];
+    const bool have_q = (qr >= 0 && qr < p.P) && (T != 0.f);
+    const float *zq_row = have_q ? p.draft_logits + ((size_t)b * p.P + qr) * (size_t)V : zp_row;
+    float4 eq[ITEMS];
+    if (have_q) {
+        load_row<ITEMS, VT, ALIGNED>(zq_row, V, eq);
+    } else {
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) eq[i] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    }
+
     // children of this row, ascending node id = sampling order
     if (t < 128) {
         bool f = (t < N) && (p.parent[t] == row - 1);
@@ -322,21 +397,11 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     }
     __syncthreads();
     int k = s_k;
-    if (k > 0) {
+    if (k > 0 && (qr < 0 || qr >= p.P)) {
         // a row with children needs a draft row; a bad map is reported, never dereferenced
-        const int qr = p.q_row[row];
-        if (qr < 0 || qr >= p.P) {
-            k = 0;
-            if (t == 0) atomicOr(&s_flags, (uint32_t)MCSD_FLAG_BAD_TREE);
-        }
+        k = 0;
+        if (t == 0) atomicOr(&s_flags, (uint32_t)MCSD_FLAG_BAD_TREE);
     }
-    const size_t rix = (size_t)b * (1 + N) + row;
-    const float T = p.temperature[b];
-    const float *zp_row = p.target_logits + rix * (size_t)V;
-    const float NaN = __int_as_float(0x7fc00000);
-
-    float4 a[ITEMS];
-    load_row<ITEMS, VT, ALIGNED>(zp_row, V, a);
 
     if (T == 0.f) {
         // argmax sampling: lowest id on ties
@@ -380,16 +445,6 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
 
     const float invT = 1.0f / T;
     const float c2 = invT * LOG2E_F;
-    // both rows are requested before anything waits on them
-    float4 eq[ITEMS];
-    const float *zq_row = zp_row;
-    if (k > 0) {
-        zq_row = p.draft_logits + ((size_t)b * p.P + p.q_row[row]) * (size_t)V;
-        load_row<ITEMS, VT, ALIGNED>(zq_row, V, eq);
-    } else {
-#pragma unroll
-        for (int i = 0; i < ITEMS; ++i) eq[i] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-    }
     float mp = row_max<ITEMS>(a), mq = row_max<ITEMS>(eq);
     block_max2<NWAVES>(mp, mq, s_redf, s_redf2);
     double A = row_exp<ITEMS>(a, mp, c2);                 // a = e_p, A = Z_p
@@ -411,8 +466,8 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
             my_u = p.u_accept[(size_t)b * N + node];
             if (my_tok >= 0 && my_tok < V) {
                 // same constants as the vector pass (float c2), evaluated exactly
-                my_a = exp2(((double)zp_row[my_tok] - (double)mp) * (double)c2);
-                my_q = exp2(((double)zq_row[my_tok] - (double)mq) * (double)c2);
+                my_a = exp2_neg(((double)zp_row[my_tok] - (double)mp) * (double)c2);
+                my_q = exp2_neg(((double)zq_row[my_tok] - (double)mq) * (double)c2);
             }
         }
         // Z_q: mass of the draft tokens not yet removed.  After a removal it is summed
