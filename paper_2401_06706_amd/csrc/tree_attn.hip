@@ -244,15 +244,15 @@ void tree_attn_mfma_kernel(AttnParams p)
 
     const float c2 = p.scale_log2;      // >= 0 (checked by the host)
     int t = t_begin + ks;
-    if (t < t_end) load_k(tile_ref(t));
+    if (t < t_end) { load_k(tile_ref(t)); load_v(tile_ref(t)); }
     for (; t < t_end; t += KS) {
         const TileRef cur = tile_ref(t);
-        // K(t): load registers -> LDS (operand order); V(t) is requested now and consumed after
-        // the scores and the softmax; K(t + KS) is requested as soon as its registers are free.
+        // Both K and V run one tile ahead of their use: K(t) goes from its load registers to LDS
+        // (operand order) and K(t + KS) is requested into the same registers; V(t + KS) is
+        // requested further down, as soon as V(t) has left its registers.
 #pragma unroll
         for (int i = 0; i < 8; ++i)
             *reinterpret_cast<u32x4 *>(area + 4 * (kst_pos[i & 3] + (i >> 2) * 256)) = kraw[i];
-        load_v(cur);
         if (t + KS < t_end) load_k(tile_ref(t + KS));
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -352,6 +352,7 @@ void tree_attn_mfma_kernel(AttnParams p)
             o[3] = __builtin_amdgcn_perm(vcur[7][w], vcur[6][w], sel);
             *reinterpret_cast<u32x4 *>(area + 4 * (vst_base + (vst_x ^ e))) = o;
         }
+        if (t + KS < t_end) load_v(tile_ref(t + KS));
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -602,14 +603,15 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
         *plan = pl;
         return true;
     }
-    // Kernel variant (all 4 waves): 0 = 32 rows x 4 key streams, 1 = 2 x 32 rows x 2 key streams
-    // (two workgroups per CU, two waves per SIMD: the choice when the KV stream from HBM is the
-    // bound), 2 = 64 rows per wave x 4 key streams (half the K/V operand traffic per flop: the
-    // choice when many row tiles share a KV head and the matrix cores are the bound).
+    // Kernel variant (all 4 waves, two workgroups per CU): 0 = 32 rows x 4 key streams for
+    // rows_per_kv <= 32, 1 = 2 x 32 rows x 2 key streams otherwise (row tiles of 64).  Variant 2
+    // (64 rows per wave, one wave per SIMD, Q operands in LDS) halves the K/V operand traffic
+    // per flop but measured slower on every workload tried; it stays selectable for experiments
+    // through MCSD_ATTN_VARIANT=3 (the variable is 1-based, 0 or unset = automatic).
     pl.row_tile = pl.rows_per_kv <= 32 ? 32 : 64;
-    pl.variant = pl.rows_per_kv <= 32 ? 0 : (pl.rows_per_kv <= 128 ? 1 : 2);
+    pl.variant = pl.rows_per_kv <= 32 ? 0 : 1;
     {
-        const int forced_variant = env_int("MCSD_ATTN_VARIANT", 0);     // 1-based; 0 = automatic
+        const int forced_variant = env_int("MCSD_ATTN_VARIANT", 0);
         if (forced_variant >= 1 && forced_variant <= 3) {
             pl.variant = forced_variant - 1;
             pl.row_tile = pl.variant == 0 ? 32 : 64;
@@ -621,13 +623,14 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
     pl.tiles_tree = (d.N + KT - 1) / KT;
     const long total_max = pl.tiles_prefix_max + pl.tiles_tree;
     const long units = (long)d.B * d.H_kv * pl.n_row_tiles;
-    // Chunk length: enough workgroups to cover the 256 CUs several times over, but no
-    // shorter than one tile per wave; long chunks keep the partial-result traffic
-    // (one [rows][d] fp32 block per workgroup) small against the KV bytes streamed.
+    // Chunk length: enough workgroups to cover the 256 CUs (two resident workgroups each) several
+    // times over, but at least 6 tiles per key stream: every workgroup pays a fixed prologue
+    // (Q, first tiles) and epilogue (merge, one [rows][d] fp32 partial written and read back by
+    // the combine kernel), which short chunks do not amortise.
     const long target_wgs = env_int("MCSD_ATTN_TARGET_WGS", 2048);
     long chunk = (total_max * units + target_wgs - 1) / target_wgs;
     chunk = ((chunk + key_streams - 1) / key_streams) * key_streams;
-    if (chunk < key_streams) chunk = key_streams;
+    if (chunk < 6 * key_streams) chunk = 6 * key_streams;
     const int forced = env_int("MCSD_ATTN_CHUNK_TILES", 0);
     if (forced > 0) chunk = forced;
     if (chunk > total_max) chunk = total_max;
