@@ -31,7 +31,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 # HBM traffic per launch of the tree-attention kernel measured with rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see the
 # summaries under profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"c4": 652656485}     # profiles/step_c4.md
 
 
 def parse_args():
@@ -43,6 +43,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--sets", type=int, default=0, help="rotating input copies (0 = enough for >= 1 GiB)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a few device-to-device copies of 1 GiB (a plain copy kernel of known "
+                         "size) for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters, then exit")
     return ap.parse_args()
 
 
@@ -100,6 +103,14 @@ def main():
         sys.exit(2)
     M.lib()     # fails loudly if libmcsd.so is not built
     dev = "cuda:0"
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": src.numel() * 4, "copies": 4}))
+        return
     w = W.WORKLOADS[args.workload]
     ai = W.gen_attn_inputs(w)
     vi = W.gen_verify_inputs(w)
