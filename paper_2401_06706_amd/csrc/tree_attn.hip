@@ -9,18 +9,15 @@
 //
 // Work decomposition (bf16, d = 128: tree_attn_mfma_kernel)
 //   keys of a sequence = ceil(L/32) prefix tiles followed by ceil(N/32) tree tiles
-//   workgroup (4 waves) = (sequence b, KV head g, tile of 32/64 query rows, chunk of
-//                          `chunk_tiles` consecutive key tiles)
-//   wave w takes key tiles t_begin + w, + 4, ... : every wave runs an independent
-//   online softmax over its tiles with no workgroup barrier in the main loop.
-//   S^T = K Q^T  : v_mfma_f32_16x16x32_bf16, A = K tile straight from global memory
-//                  (a lane's operand is 16 contiguous bytes of one key row),
-//                  B = Q held in registers for the whole kernel.
-//   O^T += V^T P^T: A = V tile transposed through a wave-private LDS buffer,
-//                  B = P taken from the S^T accumulators without leaving the lane.
-//   The waves' (max, sum, O) are merged through LDS; if the sequence has more than
-//   one chunk the partial goes to the workspace and tree_attn_combine_kernel merges
-//   the chunks by log-sum-exp, otherwise the output row is written directly.
+//   unit      = (sequence b, KV head g, tile of 32/64 query rows)
+//   segment   = one chunk of a unit, processed by one workgroup
+//               (4 waves): wave (rh, ks) owns 32 rows and every KS-th tile of the run and
+//               runs an independent online softmax with no workgroup barrier in the loop.
+//   The keys of a unit are cut into chunks of `chunk_tiles` tiles: grid (KV head, chunk x row
+//   tile, sequence).  The (sequence, chunk) pairs are handed out longest first.
+//   A segment that covers its whole unit writes the output rows itself; otherwise its
+//   (max, sum, O) partial goes to the workspace and tree_attn_combine_kernel merges the
+//   partials of a unit by log-sum-exp.
 //
 // Everything else (fp32 storage, other head dims) runs tree_attn_generic_kernel on
 // the vector ALUs.
@@ -52,6 +49,7 @@ struct AttnParams {
     int R;                // rows per (b, g) in the partial buffers
     float scale_log2;     // scale * log2(e)
 };
+
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 {
@@ -93,10 +91,10 @@ __device__ __forceinline__ void build_ancestor_masks(const int32_t *parent, int 
 }
 
 // --------------------------------------------------------------------- MFMA path
-// MT = 16-row query tiles per wave, RH = row groups per workgroup, KS = key streams per
-// workgroup.  Wave (rh, ks) owns query rows [16 MT rh, 16 MT (rh+1)) of the workgroup's
-// row tile and the key tiles t_begin + ks, + KS, ...  Waves of one key stream read the
-// same K/V tiles (the second read is served by the L1/L2 caches).
+// RH = row groups per workgroup, KS = key streams per workgroup.  Wave (rh, ks) owns query rows
+// [32 rh, 32 (rh+1)) of the workgroup's row tile and the key tiles t_begin + ks, + KS, ... of the
+// segment.  Waves of one key stream read the same K/V tiles (the second read is served by the
+// L1/L2 caches).
 //
 // Data movement per 32-key tile and wave (8 KB of K, 8 KB of V, one 8.5 KB LDS area):
 //   K  global -> registers with fully contiguous 1 KB loads (issued one tile ahead),
@@ -105,13 +103,13 @@ __device__ __forceinline__ void build_ancestor_masks(const int32_t *parent, int 
 //      Loading K straight into operand registers would make neighbouring lanes read
 //      different cache lines, which stalls the address path of the vector memory unit.
 //   V  global -> registers (a lane reads 8 key rows x 16 contiguous bytes, neighbouring
-//      lanes neighbouring bytes), in-lane 8x8 transpose of the 16-bit elements,
-//      registers -> the same LDS area -> operand (exchange inside each 16-lane group).
-template <int MT, int RH, int KS>
-__global__ __launch_bounds__(RH * KS * 64) __attribute__((amdgpu_waves_per_eu(MT <= 2 ? 2 : 1, MT <= 2 ? 2 : 1)))
+//      lanes neighbouring bytes; one tile ahead), in-lane 8x8 transpose of the 16-bit
+//      elements, registers -> the same LDS area -> operand (exchange inside 16-lane groups).
+template <int RH, int KS>
+__global__ __launch_bounds__(RH * KS * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void tree_attn_mfma_kernel(AttnParams p)
 {
-    constexpr bool QLDS = MT > 2;           // 64 rows per wave: Q operands are re-read from LDS for every tile
+    constexpr int MT = 2;                   // 16-row MFMA tiles per wave
     constexpr int NW = RH * KS;
     constexpr int NT = NW * 64;
     constexpr int WROWS = 16 * MT;          // rows per wave
@@ -124,84 +122,13 @@ void tree_attn_mfma_kernel(AttnParams p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps tile indices and pointers scalar
     const int rh = wave / KS, ks = wave % KS;
     const int lj = lane >> 4, lc = lane & 15;
-    // Workgroup ids are handed to the 8 XCDs round-robin, so the KV head is the fastest grid
-    // index: every XCD gets the same mix of long and short chunks, and the row tiles that share
-    // a KV head and chunk (grouped-query attention) run on one XCD and share its L2.
-    const int g = blockIdx.x, b = blockIdx.z;
-    const int rt = blockIdx.y % p.n_row_tiles;
-    const int chunk = blockIdx.y / p.n_row_tiles;
-
-    int L = p.prefix_len[b];
-    L = max(0, min(L, p.L_stride));
-    const int tilesP = (L + KT - 1) / KT;
-    const int total_tiles = tilesP + p.tiles_tree;
-    const int t_begin = chunk * p.chunk_tiles;
-    if (t_begin >= total_tiles) return;
-    const int t_end = min(total_tiles, t_begin + p.chunk_tiles);
-    const int n_chunks = (total_tiles + p.chunk_tiles - 1) / p.chunk_tiles;
 
     __shared__ __attribute__((aligned(16))) uint32_t s_big[NW * AREA_WORDS];
     __shared__ uint32_t s_anc[MCSD_MAX_NODES][4];
     __shared__ float s_m[KS][ROWS], s_l[KS][ROWS];
     __shared__ float s_mstar[ROWS], s_linv[ROWS];
-    __shared__ __attribute__((aligned(16))) uint32_t s_q[QLDS ? RH * MT * 4 * 64 * 4 : 4];
+    __shared__ int s_pair_len[NT], s_pair_of_rank[NT];
 
-    const bool has_tree = t_end > tilesP;
-    if (has_tree) build_ancestor_masks(p.parent + (p.parent_per_seq ? (size_t)b * p.N : 0), p.N, s_anc);
-
-    const uint16_t *qb = static_cast<const uint16_t *>(p.q);
-    const int row0 = rt * ROWS;
-
-    // Q operand: lane (lj, lc) has Q[row0 + WROWS rh + 16 mt + lc][32 kk + 8 lj .. +7], held in
-    // registers, or (QLDS) parked in LDS in exactly that per-lane order.
-    bf16x8 qreg[QLDS ? 1 : MT][4];
-    int node_of[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int r = row0 + WROWS * rh + 16 * mt + lc;
-        const bool ok = r < p.M;
-        const int rr = ok ? r : p.M - 1;
-        const int node = rr / p.G, hh = rr % p.G;
-        node_of[mt] = node;
-        const uint16_t *src = qb + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + 8 * lj;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            u32x4 v = *reinterpret_cast<const u32x4 *>(src + 32 * kk);
-            if (!ok) v = (u32x4){0u, 0u, 0u, 0u};
-            if (QLDS) {
-                if (ks == 0) *reinterpret_cast<u32x4 *>(s_q + ((((rh * MT + mt) * 4 + kk) * 64) + lane) * 4) = v;
-            } else {
-                qreg[mt][kk] = __builtin_bit_cast(bf16x8, v);
-            }
-        }
-    }
-    __syncthreads();        // s_anc and s_q are ready
-    const uint32_t *qw = s_q + (QLDS ? (size_t)(rh * MT) * 4 * 64 * 4 + lane * 4 : 0);
-
-    f32x4 oacc[8][MT];
-#pragma unroll
-    for (int nt = 0; nt < 8; ++nt)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) oacc[nt][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    float m_used[MT], l_part[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) { m_used[mt] = M_INIT; l_part[mt] = 0.f; }
-
-    const size_t kv_head = (size_t)b * p.H_kv + g;
-    // K and V of this (sequence, KV head) are read through buffer resources whose extent is
-    // exactly the valid rows (prefix_len rows of the cache slab, N rows of the tree block):
-    // the tile base is a scalar offset, the lane offset a constant, and rows past the end of
-    // a partial tile read as zero instead of leaving the array (their scores are masked).
-    const __amdgpu_buffer_rsrc_t rs_kpre = make_rsrc(static_cast<const char *>(p.k_prefix) + kv_head * (size_t)p.L_stride * (D * 2), (uint32_t)L * (D * 2));
-    const __amdgpu_buffer_rsrc_t rs_vpre = make_rsrc(static_cast<const char *>(p.v_prefix) + kv_head * (size_t)p.L_stride * (D * 2), (uint32_t)L * (D * 2));
-    const __amdgpu_buffer_rsrc_t rs_ktre = make_rsrc(static_cast<const char *>(p.k_tree) + kv_head * (size_t)p.N * (D * 2), (uint32_t)p.N * (D * 2));
-    const __amdgpu_buffer_rsrc_t rs_vtre = make_rsrc(static_cast<const char *>(p.v_tree) + kv_head * (size_t)p.N * (D * 2), (uint32_t)p.N * (D * 2));
-
-    // Per-lane byte offsets inside a tile (row pitch 256 B).
-    //   K load i (0..7): row 4 i + lj, 16-byte granule lc  ->  i * 1024 + lane * 16
-    //   V load s (0..7): row (s < 4 ? 0 : 16) + 4 lj + (s & 3), granule lc
-    const uint32_t k_lane_off = lane * 16;
-    const uint32_t v_lane_off = lj * 1024 + lc * 16;
     // LDS positions (in 16-byte granules inside this wave's area).
     //   K granule (row r, granule c) is the operand of lane (c & 3, r & 15) for (sub = r >> 4, kk = c >> 2):
     //   position (sub 4 + kk) 64 + (c & 3) 16 + ((r & 15) ^ c)
@@ -216,237 +143,362 @@ void tree_attn_mfma_kernel(AttnParams p)
     const uint32_t vst_base = (lj * 8 + (lc >> 1)) * 16;
     const uint32_t vst_x = (8 * (lc & 1)) ^ (lc >> 1);      // position = vst_base + (vst_x ^ e)
     const uint32_t vld_base = lj * 128;                      // position = vld_base + nt * 16 + (lc ^ nt)
-
-    struct TileRef { int off; int nvalid; bool tree; int tt; };
-    auto tile_ref = [&](int t) {
-        TileRef r;
-        if (t < tilesP) {
-            r.off = t * TILE_BYTES; r.nvalid = min(KT, L - t * KT); r.tree = false; r.tt = 0;
-        } else {
-            r.tt = t - tilesP;
-            r.off = r.tt * TILE_BYTES; r.nvalid = min(KT, p.N - r.tt * KT); r.tree = true;
-        }
-        return r;
-    };
-    u32x4 kraw[8];
-    auto load_k = [&](const TileRef &r) {
-        const __amdgpu_buffer_rsrc_t rs = r.tree ? rs_ktre : rs_kpre;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) kraw[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off + i * 1024, r.off, 0);
-    };
-    u32x4 vcur[8];
-    auto load_v = [&](const TileRef &r) {
-        const __amdgpu_buffer_rsrc_t rs = r.tree ? rs_vtre : rs_vpre;
-#pragma unroll
-        for (int s = 0; s < 8; ++s)
-            vcur[s] = __builtin_amdgcn_raw_buffer_load_b128(rs, v_lane_off + ((s < 4) ? 0 : 4096) + (s & 3) * 256, r.off, 0);
-    };
-
+    // Per-lane byte offsets inside a tile (row pitch 256 B).
+    //   K load i (0..7): row 4 i + lj, 16-byte granule lc  ->  i * 1024 + lane * 16
+    //   V load s (0..7): row (s < 4 ? 0 : 16) + 4 lj + (s & 3), granule lc
+    const uint32_t k_lane_off = lane * 16;
+    const uint32_t v_lane_off = lj * 1024 + lc * 16;
     const float c2 = p.scale_log2;      // >= 0 (checked by the host)
-    int t = t_begin + ks;
-    if (t < t_end) { load_k(tile_ref(t)); load_v(tile_ref(t)); }
-    for (; t < t_end; t += KS) {
-        const TileRef cur = tile_ref(t);
-        // Both K and V run one tile ahead of their use: K(t) goes from its load registers to LDS
-        // (operand order) and K(t + KS) is requested into the same registers; V(t + KS) is
-        // requested further down, as soon as V(t) has left its registers.
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            *reinterpret_cast<u32x4 *>(area + 4 * (kst_pos[i & 3] + (i >> 2) * 256)) = kraw[i];
-        if (t + KS < t_end) load_k(tile_ref(t + KS));
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const uint16_t *qb = static_cast<const uint16_t *>(p.q);
 
-        // S^T[key][row] = sum_d K[key][d] Q[row][d]   (raw, the softmax scale is applied in the exponent)
-        f32x4 sacc[2][MT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) { sacc[0][mt] = (f32x4){0.f, 0.f, 0.f, 0.f}; sacc[1][mt] = (f32x4){0.f, 0.f, 0.f, 0.f}; }
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const bf16x8 k0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(area + 4 * kld_pos[kk]));
-            const bf16x8 k1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(area + 4 * (kld_pos[kk] + 256)));
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                bf16x8 qop;
-                if (QLDS) qop = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qw + (mt * 4 + kk) * 256));
-                else qop = qreg[mt][kk];
-                sacc[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qop, sacc[0][mt], 0, 0, 0);
-                sacc[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qop, sacc[1][mt], 0, 0, 0);
+    // ---- this workgroup's segment: unit (b, g, rt), tiles [t_begin, t_end) of total_tiles
+    int b, g, rt, t_begin, t_end, total_tiles, L;
+    bool direct;
+    size_t part_row;                    // first row of this segment's partial in the workspace
+    {
+        // Workgroups start in the order z, y, x.  The (sequence, chunk) pairs are handed out
+        // longest first (the short last chunks of the sequences fill the end of the launch
+        // instead of a mostly idle last wave of workgroups): pair number r in dispatch order
+        // takes the pair of rank r by length.  Done when the pairs fit one workgroup's threads.
+        g = blockIdx.x; b = blockIdx.z;
+        rt = blockIdx.y % p.n_row_tiles;
+        int chunk = blockIdx.y / p.n_row_tiles;
+        const int n_pairs = p.B * p.n_chunks_max;
+        if (n_pairs <= NT && p.n_chunks_max > 1) {
+            int my_len = 0;
+            if (tid < n_pairs) {
+                int Lb = p.prefix_len[tid / p.n_chunks_max];
+                Lb = max(0, min(Lb, p.L_stride));
+                const int Tb = (Lb + KT - 1) / KT + p.tiles_tree;
+                my_len = max(0, min(p.chunk_tiles, Tb - (tid % p.n_chunks_max) * p.chunk_tiles));
+                s_pair_len[tid] = my_len;
             }
-        }
-        // lane (lj, lc) now holds, for its row 16 mt + lc, keys 16 sub + 4 lj + i
-        const bool masked = cur.nvalid < KT || cur.tree;
-        uint32_t onmask[MT];
-        if (masked) {
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                uint32_t vis = cur.tree ? s_anc[node_of[mt]][cur.tt] : 0xffffffffu;
-                if (cur.nvalid < KT) vis &= (1u << cur.nvalid) - 1u;
-                onmask[mt] = vis;
-#pragma unroll
-                for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (!((vis >> (16 * sub + 4 * lj + i)) & 1u)) sacc[sub][mt][i] = -INFINITY;
+            __syncthreads();
+            if (tid < n_pairs) {
+                int rank = 0;
+                for (int j = 0; j < n_pairs; ++j) {
+                    const int lj2 = s_pair_len[j];
+                    rank += (lj2 > my_len || (lj2 == my_len && j < tid)) ? 1 : 0;
+                }
+                s_pair_of_rank[rank] = tid;
             }
+            __syncthreads();
+            const int pair = s_pair_of_rank[blockIdx.z * p.n_chunks_max + chunk];
+            b = pair / p.n_chunks_max;
+            chunk = pair % p.n_chunks_max;
         }
-        // online softmax with a lazily raised running max (scaled, base-2 domain)
-        bool raise = false;
-        float lmax[MT];
+        L = p.prefix_len[b];
+        L = max(0, min(L, p.L_stride));
+        total_tiles = (L + KT - 1) / KT + p.tiles_tree;
+        t_begin = chunk * p.chunk_tiles;
+        if (t_begin >= total_tiles) return;
+        t_end = min(total_tiles, t_begin + p.chunk_tiles);
+        direct = (total_tiles <= p.chunk_tiles);
+        part_row = (((size_t)b * p.H_kv + g) * p.n_chunks_max + chunk) * (size_t)p.R + (size_t)rt * ROWS;
+    }
+    {
+        const int tilesP = (L + KT - 1) / KT;
+        const int row0 = rt * ROWS;
+
+        if (t_end > tilesP) {
+            build_ancestor_masks(p.parent + (p.parent_per_seq ? (size_t)b * p.N : 0), p.N, s_anc);
+            __syncthreads();
+        }
+
+        // Q operand, held in registers: lane (lj, lc) has Q[row0 + WROWS rh + 16 mt + lc][32 kk + 8 lj .. +7]
+        bf16x8 qreg[MT][4];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            float m0 = fmaxf(fmaxf(sacc[0][mt][0], sacc[0][mt][1]), fmaxf(sacc[0][mt][2], sacc[0][mt][3]));
-            float m1 = fmaxf(fmaxf(sacc[1][mt][0], sacc[1][mt][1]), fmaxf(sacc[1][mt][2], sacc[1][mt][3]));
-            const float mr = fmaxf(m0, m1);
-            lmax[mt] = (mr == -INFINITY) ? -INFINITY : mr * c2;
-            raise |= lmax[mt] > m_used[mt] + RESCALE_GAP;
-        }
-        if (__any(raise)) {
+            const int r = row0 + WROWS * rh + 16 * mt + lc;
+            const bool ok = r < p.M;
+            const int rr = ok ? r : p.M - 1;
+            const int node = rr / p.G, hh = rr % p.G;
+            const uint16_t *src = qb + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + 8 * lj;
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                float rm = lmax[mt];
-                rm = fmaxf(rm, __shfl_xor(rm, 16));
-                rm = fmaxf(rm, __shfl_xor(rm, 32));
-                const float m_new = fmaxf(m_used[mt], rm);
-                const float alpha = fast_exp2(m_used[mt] - m_new);
-                m_used[mt] = m_new;
-                l_part[mt] *= alpha;
-#pragma unroll
-                for (int nt = 0; nt < 8; ++nt) oacc[nt][mt] *= alpha;
+            for (int kk = 0; kk < 4; ++kk) {
+                u32x4 v = *reinterpret_cast<const u32x4 *>(src + 32 * kk);
+                if (!ok) v = (u32x4){0u, 0u, 0u, 0u};
+                qreg[mt][kk] = __builtin_bit_cast(bf16x8, v);
             }
-        }
-        bf16x8 pop[MT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            float pv[8];
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) pv[4 * sub + i] = fast_exp2(fmaf(sacc[sub][mt][i], c2, -m_used[mt]));
-            if (masked) {
-                // also covers scale == 0, where a masked score can not be told apart by its value
-#pragma unroll
-                for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (!((onmask[mt] >> (16 * sub + 4 * lj + i)) & 1u)) pv[4 * sub + i] = 0.f;
-            }
-            l_part[mt] += ((pv[0] + pv[1]) + (pv[2] + pv[3])) + ((pv[4] + pv[5]) + (pv[6] + pv[7]));
-            u32x4 pk = {pack_bf16(pv[0], pv[1]), pack_bf16(pv[2], pv[3]), pack_bf16(pv[4], pv[5]), pack_bf16(pv[6], pv[7])};
-            pop[mt] = __builtin_bit_cast(bf16x8, pk);
         }
 
-        // V tile -> V^T operands (the K operands in the area are dead by now: LDS ops of one wave
-        // execute in order)
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+        f32x4 oacc[8][MT];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int w = e >> 1;
-            const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-            u32x4 o;
-            o[0] = __builtin_amdgcn_perm(vcur[1][w], vcur[0][w], sel);
-            o[1] = __builtin_amdgcn_perm(vcur[3][w], vcur[2][w], sel);
-            o[2] = __builtin_amdgcn_perm(vcur[5][w], vcur[4][w], sel);
-            o[3] = __builtin_amdgcn_perm(vcur[7][w], vcur[6][w], sel);
-            *reinterpret_cast<u32x4 *>(area + 4 * (vst_base + (vst_x ^ e))) = o;
-        }
-        if (t + KS < t_end) load_v(tile_ref(t + KS));
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        // O^T[d][row] += sum_key V[key][d] P[row][key]
+        for (int nt = 0; nt < 8; ++nt)
 #pragma unroll
-        for (int nt = 0; nt < 8; ++nt) {
-            const bf16x8 vop = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(area + 4 * (vld_base + nt * 16 + (lc ^ nt))));
+            for (int mt = 0; mt < MT; ++mt) oacc[nt][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        float m_used[MT], l_part[MT];
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-                oacc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pop[mt], oacc[nt][mt], 0, 0, 0);
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-    }
+        for (int mt = 0; mt < MT; ++mt) { m_used[mt] = M_INIT; l_part[mt] = 0.f; }
 
-    // ---- epilogue: merge the key streams.  (m, l) per row through LDS; O in two halves of d:
-    // every wave stores its rescaled half as float4 rows [row][68] in its own area, then all
-    // threads add up the KS areas of a row group and write the result.
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        float lt = l_part[mt];
-        lt += __shfl_xor(lt, 16);
-        lt += __shfl_xor(lt, 32);
-        if (lj == 0) { s_m[ks][WROWS * rh + 16 * mt + lc] = m_used[mt]; s_l[ks][WROWS * rh + 16 * mt + lc] = lt; }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int r = WROWS * rh + 16 * mt + lc;
-        float ms = s_m[0][r];
-#pragma unroll
-        for (int k2 = 1; k2 < KS; ++k2) ms = fmaxf(ms, s_m[k2][r]);
-        const float f = exp2f(m_used[mt] - ms);
-#pragma unroll
-        for (int nt = 0; nt < 8; ++nt) oacc[nt][mt] *= f;
-    }
-    if (tid < ROWS) {
-        float ms = s_m[0][tid];
-#pragma unroll
-        for (int k2 = 1; k2 < KS; ++k2) ms = fmaxf(ms, s_m[k2][tid]);
-        float ls = 0.f;
-#pragma unroll
-        for (int k2 = 0; k2 < KS; ++k2) ls += exp2f(s_m[k2][tid] - ms) * s_l[k2][tid];
-        s_mstar[tid] = ms;
-        s_linv[tid] = (n_chunks == 1) ? 1.0f / ls : ls;
-    }
-    const int rows_valid = min(ROWS, p.M - row0);
-    const size_t unit = (kv_head * p.n_chunks_max + chunk) * (size_t)p.R + row0;
-    float *farea = reinterpret_cast<float *>(area);
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-#pragma unroll
-        for (int n4 = 0; n4 < 4; ++n4)
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const f32x4 v = oacc[4 * half + n4][mt];       // d = 64 half + 16 n4 + 4 lj + (0..3), row 16 mt + lc
-                *reinterpret_cast<f32x4 *>(farea + (16 * mt + lc) * 68 + 16 * n4 + 4 * lj) = v;
-            }
-        __syncthreads();
-        for (int idx = tid; idx < rows_valid * 8; idx += NT) {
-            const int r = idx >> 3, d8 = idx & 7;
-            const int rg = r / WROWS, rl = r % WROWS;
-            float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int k2 = 0; k2 < KS; ++k2) {
-                const float *src = reinterpret_cast<const float *>(s_big + (rg * KS + k2) * AREA_WORDS) + rl * 68 + 8 * d8;
-                const f32x4 a0 = *reinterpret_cast<const f32x4 *>(src);
-                const f32x4 a1 = *reinterpret_cast<const f32x4 *>(src + 4);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) { acc[e] += a0[e]; acc[4 + e] += a1[e]; }
-            }
-            const int dcol = 64 * half + 8 * d8;
-            if (n_chunks == 1) {
-                const float inv = s_linv[r];
-                u32x4 pk = {pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv),
-                            pack_bf16(acc[4] * inv, acc[5] * inv), pack_bf16(acc[6] * inv, acc[7] * inv)};
-                const int gr = row0 + r, node = gr / p.G, hh = gr % p.G;
-                uint16_t *ob = static_cast<uint16_t *>(p.out);
-                *reinterpret_cast<u32x4 *>(ob + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + dcol) = pk;
+        const size_t kv_head = (size_t)b * p.H_kv + g;
+        // K and V of this (sequence, KV head) are read through buffer resources whose extent is
+        // exactly the valid rows (prefix_len rows of the cache slab, N rows of the tree block):
+        // the tile base is a scalar offset, the lane offset a constant, and rows past the end of
+        // a partial tile read as zero instead of leaving the array (their scores are masked).
+        const __amdgpu_buffer_rsrc_t rs_kpre = make_rsrc(static_cast<const char *>(p.k_prefix) + kv_head * (size_t)p.L_stride * (D * 2), (uint32_t)L * (D * 2));
+        const __amdgpu_buffer_rsrc_t rs_vpre = make_rsrc(static_cast<const char *>(p.v_prefix) + kv_head * (size_t)p.L_stride * (D * 2), (uint32_t)L * (D * 2));
+        const __amdgpu_buffer_rsrc_t rs_ktre = make_rsrc(static_cast<const char *>(p.k_tree) + kv_head * (size_t)p.N * (D * 2), (uint32_t)p.N * (D * 2));
+        const __amdgpu_buffer_rsrc_t rs_vtre = make_rsrc(static_cast<const char *>(p.v_tree) + kv_head * (size_t)p.N * (D * 2), (uint32_t)p.N * (D * 2));
+
+        struct TileRef { int off; int nvalid; bool tree; int tt; };
+        // Tiles at or past t_end are requested at an offset beyond every buffer's extent: the
+        // hardware returns zeros without touching memory.  This keeps the prefetch of the next
+        // tile unconditional, so the wait for one tile's data never has to cover the loads issued
+        // after it (a load under a branch makes the compiler wait for everything outstanding).
+        constexpr int OFF_NOWHERE = 0x7fff0000;
+        auto tile_ref = [&](int t) {
+            TileRef r;
+            if (t >= t_end) {
+                r.off = OFF_NOWHERE; r.nvalid = KT; r.tree = false; r.tt = 0;
+            } else if (t < tilesP) {
+                r.off = t * TILE_BYTES; r.nvalid = min(KT, L - t * KT); r.tree = false; r.tt = 0;
             } else {
-                float *dst = p.part_o + (unit + r) * D + dcol;
-                *reinterpret_cast<f32x4 *>(dst) = (f32x4){acc[0], acc[1], acc[2], acc[3]};
-                *reinterpret_cast<f32x4 *>(dst + 4) = (f32x4){acc[4], acc[5], acc[6], acc[7]};
+                r.tt = t - tilesP;
+                r.off = r.tt * TILE_BYTES; r.nvalid = min(KT, p.N - r.tt * KT); r.tree = true;
             }
+            return r;
+        };
+        u32x4 kraw[8];
+        auto load_k = [&](const TileRef &r) {
+            const __amdgpu_buffer_rsrc_t rs = r.tree ? rs_ktre : rs_kpre;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) kraw[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off + i * 1024, r.off, 0);
+        };
+        u32x4 vcur[8];
+        auto load_v = [&](const TileRef &r) {
+            const __amdgpu_buffer_rsrc_t rs = r.tree ? rs_vtre : rs_vpre;
+#pragma unroll
+            for (int s = 0; s < 8; ++s)
+                vcur[s] = __builtin_amdgcn_raw_buffer_load_b128(rs, v_lane_off + ((s < 4) ? 0 : 4096) + (s & 3) * 256, r.off, 0);
+        };
+
+        int t = t_begin + ks;
+        load_k(tile_ref(t));
+        load_v(tile_ref(t));
+        for (; t < t_end; t += KS) {
+            const TileRef cur = tile_ref(t);
+            // Both K and V run one tile ahead of their use: K(t) goes from its load registers to LDS
+            // (operand order) and K(t + KS) is requested into the same registers; V(t + KS) is
+            // requested further down, as soon as V(t) has left its registers.
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                *reinterpret_cast<u32x4 *>(area + 4 * (kst_pos[i & 3] + (i >> 2) * 256)) = kraw[i];
+            load_k(tile_ref(t + KS));
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+            // S^T[key][row] = sum_d K[key][d] Q[row][d]   (raw, the softmax scale is applied in the exponent)
+            f32x4 sacc[2][MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) { sacc[0][mt] = (f32x4){0.f, 0.f, 0.f, 0.f}; sacc[1][mt] = (f32x4){0.f, 0.f, 0.f, 0.f}; }
+            // operands are fetched from LDS four at a time ahead of the eight MFMAs that use them, so
+            // that one LDS latency is exposed per group instead of one per operand
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh) {
+                bf16x8 kop[2][2];
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2) {
+                    const int kk = 2 * kh + k2;
+                    kop[k2][0] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(area + 4 * kld_pos[kk]));
+                    kop[k2][1] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(area + 4 * (kld_pos[kk] + 256)));
+                }
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        sacc[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[k2][0], qreg[mt][2 * kh + k2], sacc[0][mt], 0, 0, 0);
+                        sacc[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[k2][1], qreg[mt][2 * kh + k2], sacc[1][mt], 0, 0, 0);
+                    }
+            }
+            // lane (lj, lc) now holds, for its row 16 mt + lc, keys 16 sub + 4 lj + i
+            const bool masked = cur.nvalid < KT || cur.tree;
+            uint32_t onmask[MT];
+            if (masked) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    // the node of this lane's row is recomputed here (tree tiles are rare) rather than
+                    // kept in a register across the whole loop
+                    const int node_m = min(row0 + WROWS * rh + 16 * mt + lc, p.M - 1) / p.G;
+                    uint32_t vis = cur.tree ? s_anc[node_m][cur.tt] : 0xffffffffu;
+                    if (cur.nvalid < KT) vis &= (1u << cur.nvalid) - 1u;
+                    onmask[mt] = vis;
+#pragma unroll
+                    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (!((vis >> (16 * sub + 4 * lj + i)) & 1u)) sacc[sub][mt][i] = -INFINITY;
+                }
+            }
+            // online softmax with a lazily raised running max (scaled, base-2 domain)
+            bool raise = false;
+            float lmax[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                float m0 = fmaxf(fmaxf(sacc[0][mt][0], sacc[0][mt][1]), fmaxf(sacc[0][mt][2], sacc[0][mt][3]));
+                float m1 = fmaxf(fmaxf(sacc[1][mt][0], sacc[1][mt][1]), fmaxf(sacc[1][mt][2], sacc[1][mt][3]));
+                const float mr = fmaxf(m0, m1);
+                lmax[mt] = (mr == -INFINITY) ? -INFINITY : mr * c2;
+                raise |= lmax[mt] > m_used[mt] + RESCALE_GAP;
+            }
+            if (__any(raise)) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    float rm = lmax[mt];
+                    rm = fmaxf(rm, __shfl_xor(rm, 16));
+                    rm = fmaxf(rm, __shfl_xor(rm, 32));
+                    const float m_new = fmaxf(m_used[mt], rm);
+                    const float alpha = fast_exp2(m_used[mt] - m_new);
+                    m_used[mt] = m_new;
+                    l_part[mt] *= alpha;
+#pragma unroll
+                    for (int nt = 0; nt < 8; ++nt) oacc[nt][mt] *= alpha;
+                }
+            }
+            bf16x8 pop[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                float pv[8];
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) pv[4 * sub + i] = fast_exp2(fmaf(sacc[sub][mt][i], c2, -m_used[mt]));
+                if (masked) {
+                    // also covers scale == 0, where a masked score can not be told apart by its value
+#pragma unroll
+                    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (!((onmask[mt] >> (16 * sub + 4 * lj + i)) & 1u)) pv[4 * sub + i] = 0.f;
+                }
+                l_part[mt] += ((pv[0] + pv[1]) + (pv[2] + pv[3])) + ((pv[4] + pv[5]) + (pv[6] + pv[7]));
+                u32x4 pk = {pack_bf16(pv[0], pv[1]), pack_bf16(pv[2], pv[3]), pack_bf16(pv[4], pv[5]), pack_bf16(pv[6], pv[7])};
+                pop[mt] = __builtin_bit_cast(bf16x8, pk);
+            }
+
+            // V tile -> V^T operands (the K operands in the area are dead by now: LDS ops of one wave
+            // execute in order)
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int w = e >> 1;
+                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+                u32x4 o;
+                o[0] = __builtin_amdgcn_perm(vcur[1][w], vcur[0][w], sel);
+                o[1] = __builtin_amdgcn_perm(vcur[3][w], vcur[2][w], sel);
+                o[2] = __builtin_amdgcn_perm(vcur[5][w], vcur[4][w], sel);
+                o[3] = __builtin_amdgcn_perm(vcur[7][w], vcur[6][w], sel);
+                *reinterpret_cast<u32x4 *>(area + 4 * (vst_base + (vst_x ^ e))) = o;
+            }
+            load_v(tile_ref(t + KS));
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            // O^T[d][row] += sum_key V[key][d] P[row][key]
+#pragma unroll
+            for (int nh = 0; nh < 2; ++nh) {
+                bf16x8 vop[4];
+#pragma unroll
+                for (int n4 = 0; n4 < 4; ++n4) {
+                    const int nt = 4 * nh + n4;
+                    vop[n4] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(area + 4 * (vld_base + nt * 16 + (lc ^ nt))));
+                }
+#pragma unroll
+                for (int n4 = 0; n4 < 4; ++n4)
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        oacc[4 * nh + n4][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[n4], pop[mt], oacc[4 * nh + n4][mt], 0, 0, 0);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+
+        // ---- epilogue: merge the key streams.  (m, l) per row through LDS; O in two halves of d:
+        // every wave stores its rescaled half as float4 rows [row][68] in its own area, then all
+        // threads add up the KS areas of a row group and write the result.
+        // The lane indices are re-derived from an opaque copy so that the epilogue's address
+        // arithmetic is not hoisted above the tile loop, where it would cost registers (and spill).
+        int tid_e = tid;
+        asm volatile("" : "+v"(tid_e));
+        const int lj_e = (tid_e & 63) >> 4, lc_e = tid_e & 15;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            float lt = l_part[mt];
+            lt += __shfl_xor(lt, 16);
+            lt += __shfl_xor(lt, 32);
+            if (lj_e == 0) { s_m[ks][WROWS * rh + 16 * mt + lc_e] = m_used[mt]; s_l[ks][WROWS * rh + 16 * mt + lc_e] = lt; }
         }
         __syncthreads();
-    }
-    if (n_chunks > 1 && tid < rows_valid) {
-        p.part_m[unit + tid] = s_mstar[tid];
-        p.part_l[unit + tid] = s_linv[tid];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const int r = WROWS * rh + 16 * mt + lc_e;
+            float ms = s_m[0][r];
+#pragma unroll
+            for (int k2 = 1; k2 < KS; ++k2) ms = fmaxf(ms, s_m[k2][r]);
+            const float fsc = exp2f(m_used[mt] - ms);
+#pragma unroll
+            for (int nt = 0; nt < 8; ++nt) oacc[nt][mt] *= fsc;
+        }
+        if (tid_e < ROWS) {
+            float ms = s_m[0][tid_e];
+#pragma unroll
+            for (int k2 = 1; k2 < KS; ++k2) ms = fmaxf(ms, s_m[k2][tid_e]);
+            float ls = 0.f;
+#pragma unroll
+            for (int k2 = 0; k2 < KS; ++k2) ls += exp2f(s_m[k2][tid_e] - ms) * s_l[k2][tid_e];
+            s_mstar[tid_e] = ms;
+            s_linv[tid_e] = direct ? 1.0f / ls : ls;
+        }
+        const int rows_valid = min(ROWS, p.M - row0);
+        float *farea = reinterpret_cast<float *>(area);
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+#pragma unroll
+            for (int n4 = 0; n4 < 4; ++n4)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const f32x4 v = oacc[4 * half + n4][mt];       // d = 64 half + 16 n4 + 4 lj + (0..3), row 16 mt + lc
+                    *reinterpret_cast<f32x4 *>(farea + (16 * mt + lc_e) * 68 + 16 * n4 + 4 * lj_e) = v;
+                }
+            __syncthreads();
+            for (int idx = tid_e; idx < rows_valid * 8; idx += NT) {
+                const int r = idx >> 3, d8 = idx & 7;
+                const int rg = r / WROWS, rl = r % WROWS;
+                float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int k2 = 0; k2 < KS; ++k2) {
+                    const float *src = reinterpret_cast<const float *>(s_big + (rg * KS + k2) * AREA_WORDS) + rl * 68 + 8 * d8;
+                    const f32x4 a0 = *reinterpret_cast<const f32x4 *>(src);
+                    const f32x4 a1 = *reinterpret_cast<const f32x4 *>(src + 4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { acc[e] += a0[e]; acc[4 + e] += a1[e]; }
+                }
+                const int dcol = 64 * half + 8 * d8;
+                if (direct) {
+                    const float inv = s_linv[r];
+                    u32x4 pk = {pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv),
+                                pack_bf16(acc[4] * inv, acc[5] * inv), pack_bf16(acc[6] * inv, acc[7] * inv)};
+                    const int gr = row0 + r, node = gr / p.G, hh = gr % p.G;
+                    uint16_t *ob = static_cast<uint16_t *>(p.out);
+                    *reinterpret_cast<u32x4 *>(ob + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + dcol) = pk;
+                } else {
+                    float *dst = p.part_o + (part_row + r) * D + dcol;
+                    *reinterpret_cast<f32x4 *>(dst) = (f32x4){acc[0], acc[1], acc[2], acc[3]};
+                    *reinterpret_cast<f32x4 *>(dst + 4) = (f32x4){acc[4], acc[5], acc[6], acc[7]};
+                }
+            }
+            __syncthreads();
+        }
+        if (!direct && tid_e < rows_valid) {
+            p.part_m[part_row + tid_e] = s_mstar[tid_e];
+            p.part_l[part_row + tid_e] = s_linv[tid_e];
+        }
     }
 }
 
-// Merges the chunks of one sequence: out = sum_c 2^(m_c - m*) O_c / sum_c 2^(m_c - m*) l_c.
+// Merges the chunks of one unit: out = sum_c 2^(m_c - m*) O_c / sum_c 2^(m_c - m*) l_c.
 __global__ __launch_bounds__(256) void tree_attn_combine_kernel(AttnParams p)
 {
     constexpr int D = 128;
@@ -459,20 +511,19 @@ __global__ __launch_bounds__(256) void tree_attn_combine_kernel(AttnParams p)
     const int r = blockIdx.x * 16 + (threadIdx.x >> 4);
     const int d8 = threadIdx.x & 15;
     if (r >= p.M) return;
-    const size_t kv_head = (size_t)b * p.H_kv + g;
-    const size_t base = kv_head * p.n_chunks_max * (size_t)p.R + r;
+    const size_t base = (((size_t)b * p.H_kv + g) * p.n_chunks_max) * (size_t)p.R + r;
     float ms = M_INIT;
     for (int c = 0; c < n_chunks; ++c) ms = fmaxf(ms, p.part_m[base + (size_t)c * p.R]);
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     float ls = 0.f;
     for (int c = 0; c < n_chunks; ++c) {
         const size_t u = base + (size_t)c * p.R;
-        const float f = exp2f(p.part_m[u] - ms);
-        ls += f * p.part_l[u];
+        const float fsc = exp2f(p.part_m[u] - ms);
+        ls += fsc * p.part_l[u];
         const float4 a0 = *reinterpret_cast<const float4 *>(p.part_o + u * D + 8 * d8);
         const float4 a1 = *reinterpret_cast<const float4 *>(p.part_o + u * D + 8 * d8 + 4);
-        acc[0] += f * a0.x; acc[1] += f * a0.y; acc[2] += f * a0.z; acc[3] += f * a0.w;
-        acc[4] += f * a1.x; acc[5] += f * a1.y; acc[6] += f * a1.z; acc[7] += f * a1.w;
+        acc[0] += fsc * a0.x; acc[1] += fsc * a0.y; acc[2] += fsc * a0.z; acc[3] += fsc * a0.w;
+        acc[4] += fsc * a1.x; acc[5] += fsc * a1.y; acc[6] += fsc * a1.z; acc[7] += fsc * a1.w;
     }
     const float inv = 1.0f / ls;
     u32x4 pk = {pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv),
@@ -603,16 +654,13 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
         *plan = pl;
         return true;
     }
-    // Kernel variant (all 4 waves, two workgroups per CU): 0 = 32 rows x 4 key streams for
-    // rows_per_kv <= 32, 1 = 2 x 32 rows x 2 key streams otherwise (row tiles of 64).  Variant 2
-    // (64 rows per wave, one wave per SIMD, Q operands in LDS) halves the K/V operand traffic
-    // per flop but measured slower on every workload tried; it stays selectable for experiments
-    // through MCSD_ATTN_VARIANT=3 (the variable is 1-based, 0 or unset = automatic).
+    // Kernel variant (4 waves, two workgroups per CU): 0 = 32 rows x 4 key streams for
+    // rows_per_kv <= 32, 1 = 2 x 32 rows x 2 key streams otherwise (row tiles of 64).
     pl.row_tile = pl.rows_per_kv <= 32 ? 32 : 64;
     pl.variant = pl.rows_per_kv <= 32 ? 0 : 1;
     {
-        const int forced_variant = env_int("MCSD_ATTN_VARIANT", 0);
-        if (forced_variant >= 1 && forced_variant <= 3) {
+        const int forced_variant = env_int("MCSD_ATTN_VARIANT", 0);     // 1-based, 0 / unset = automatic
+        if (forced_variant >= 1 && forced_variant <= 2) {
             pl.variant = forced_variant - 1;
             pl.row_tile = pl.variant == 0 ? 32 : 64;
         }
@@ -623,14 +671,16 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
     pl.tiles_tree = (d.N + KT - 1) / KT;
     const long total_max = pl.tiles_prefix_max + pl.tiles_tree;
     const long units = (long)d.B * d.H_kv * pl.n_row_tiles;
-    // Chunk length: enough workgroups to cover the 256 CUs (two resident workgroups each) several
-    // times over, but at least 6 tiles per key stream: every workgroup pays a fixed prologue
-    // (Q, first tiles) and epilogue (merge, one [rows][d] fp32 partial written and read back by
-    // the combine kernel), which short chunks do not amortise.
+    // Every segment pays a fixed prologue (Q, first tiles) and epilogue (merge, possibly one
+    // [rows][d] fp32 partial written and read back by the combine kernel), which runs shorter
+    // than 6 tiles per key stream do not amortise (measured).
+    const long min_run = 6 * key_streams;
+
+    // Enough workgroups to cover the CUs (two resident workgroups each) several times over.
     const long target_wgs = env_int("MCSD_ATTN_TARGET_WGS", 2048);
     long chunk = (total_max * units + target_wgs - 1) / target_wgs;
     chunk = ((chunk + key_streams - 1) / key_streams) * key_streams;
-    if (chunk < 6 * key_streams) chunk = 6 * key_streams;
+    if (chunk < min_run) chunk = min_run;
     const int forced = env_int("MCSD_ATTN_CHUNK_TILES", 0);
     if (forced > 0) chunk = forced;
     if (chunk > total_max) chunk = total_max;
@@ -680,14 +730,10 @@ int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const
         p.part_m = ws + rows * d.d;
         p.part_l = p.part_m + rows;
     }
-    dim3 grid(d.H_kv, plan.n_chunks_max * plan.n_row_tiles, d.B);
+    const dim3 grid(d.H_kv, plan.n_chunks_max * plan.n_row_tiles, d.B);
     timing_begin(K_ATTN_MFMA, stream);
-    if (plan.variant == 0)
-        hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 1, 4>), grid, dim3(256), 0, stream, p);
-    else if (plan.variant == 1)
-        hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, 2>), grid, dim3(256), 0, stream, p);
-    else
-        hipLaunchKernelGGL((tree_attn_mfma_kernel<4, 1, 4>), grid, dim3(256), 0, stream, p);
+    if (plan.variant == 0) hipLaunchKernelGGL((tree_attn_mfma_kernel<1, 4>), grid, dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2>), grid, dim3(256), 0, stream, p);
     timing_end(K_ATTN_MFMA, stream);
     e = hipGetLastError();
     if (e != hipSuccess) { set_error("tree_attn_mfma launch failed: %s", hipGetErrorString(e)); return MCSD_E_HIP; }
