@@ -336,7 +336,8 @@ template <int ITEMS, int VT, bool ALIGNED>
 __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
 {
     constexpr int NWAVES = VT / 64;
-    const int row = blockIdx.x, b = blockIdx.y;
+    const int row = blockIdx.x;
+    int b = blockIdx.y;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int N = p.N, V = p.V;
 
@@ -354,6 +355,31 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     __shared__ int s_xrem;         // token removed from q after a rejection (-1: none)
     __shared__ float s_bestv[NWAVES];
     __shared__ int s_besti[NWAVES];
+
+    // Workgroups start in the order y, x.  A sampled sequence costs a workgroup about three
+    // times what an argmax sequence costs (two rows, exponentials, k dependent rounds against
+    // one row and an argmax), so the sampled sequences are handed out first and the cheap ones
+    // fill the end of the launch: sequence number y in dispatch order is the y-th sampled
+    // sequence, then the argmax ones in their own order.  Done when B fits the workgroup.
+    __shared__ int s_cnt[NWAVES];
+    __shared__ int s_seq_of_rank[VT];
+    if (p.B > 1 && p.B <= VT) {
+        const bool sampled = (t < p.B) && (p.temperature[t] != 0.f);
+        const unsigned long long m = __ballot(sampled);
+        if (lane == 0) s_cnt[wave] = __popcll(m);
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < NWAVES; ++w) {
+            const int c = s_cnt[w];
+            before += (w < wave) ? c : 0;
+            total += c;
+        }
+        const int idx_s = before + __popcll(m & ((1ull << lane) - 1ull));   // sampled sequences before this one
+        if (t < p.B) s_seq_of_rank[sampled ? idx_s : total + (t - idx_s)] = t;
+        __syncthreads();
+        b = s_seq_of_rank[blockIdx.y];
+    }
 
     // The two logit rows are requested first; the bookkeeping below (children list, flags)
     // runs while they are in flight.  A row has a draft row iff q_row says so; whether it

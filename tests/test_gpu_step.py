@@ -1,0 +1,75 @@
+"""mcsd_verify_step (attention + verification on one stream) and the profiling aid."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mcsd_oracle as O
+from paper_2401_06706_amd import binding as M
+from paper_2401_06706_amd import device as D
+from paper_2401_06706_amd import workloads as W
+from tests.parity import compare_verify, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def test_verify_step_matches_separate_calls_and_oracle():
+    w = W.WORKLOADS["c4"].with_(B=4, H_q=8, H_kv=8, prefix=(100, 700), V=8192, n_greedy=2)
+    ai, vi = W.gen_attn_inputs(w), W.gen_verify_inputs(w)
+    a1, v1 = D.make_attn_call(ai), D.make_verify_call(vi, want_residual=True)
+    M.mcsd_verify_step(a1.args, v1.args)
+    torch.cuda.synchronize()
+    a2, v2 = D.make_attn_call(ai), D.make_verify_call(vi, want_residual=True)
+    M.mcsd_tree_attn(a2.args)
+    M.mcsd_verify_sample(v2.args)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(a1.out_numpy(), a2.out_numpy())
+    r1, r2 = v1.results(), v2.results()
+    for k in r1:
+        np.testing.assert_array_equal(r1[k], r2[k], err_msg=k)
+    ref = O.tree_attn(ai.q, ai.k_prefix, ai.v_prefix, ai.prefix_len, ai.k_tree, ai.v_tree, ai.parent, ai.scale,
+                      O.BF16, n_threads=8)
+    assert np.abs(a1.out_numpy() - ref).max() <= 2e-2
+    compare_verify(vi, r1, run_oracle(vi, want_residual=True), check_residual=True, label="step")
+
+
+def test_verify_step_rejects_bad_half_without_running_the_other():
+    w = W.WORKLOADS["c1"]
+    ai, vi = W.gen_attn_inputs(w), W.gen_verify_inputs(w)
+    a, v = D.make_attn_call(ai), D.make_verify_call(vi)
+    a.out.fill_(7.0)
+    v.args.desc.variant = 9
+    with pytest.raises(M.McsdError) as e:
+        M.mcsd_verify_step(a.args, v.args)
+    assert e.value.code == -3
+    torch.cuda.synchronize()
+    assert (a.out == 7.0).all()           # nothing was enqueued
+
+
+def test_kernel_timing_counts_launches():
+    w = W.WORKLOADS["c2"].with_(prefix=(2048, 2048))
+    ai, vi = W.gen_attn_inputs(w), W.gen_verify_inputs(w)
+    a, v = D.make_attn_call(ai), D.make_verify_call(vi)
+    M.mcsd_kernel_timing(True)
+    for _ in range(3):
+        M.mcsd_verify_step(a.args, v.args)
+    t = M.mcsd_kernel_timing_read()
+    M.mcsd_kernel_timing(False)
+    assert t["tree_attn_mfma"][1] == 3 and t["verify_rows"][1] == 3 and t["walk"][1] == 3
+    assert t["tree_attn_combine"][1] == 3          # 65 tiles per head: more than one chunk
+    assert all(ms > 0 for ms, n in t.values() if n)
+    M.mcsd_verify_step(a.args, v.args)             # timing off again: nothing recorded
+    assert M.mcsd_kernel_timing_read()["verify_rows"][1] == 3
+
+
+def test_long_prefix_sampled_against_oracle():
+    """32768-token prefix (more than any bench workload), GQA 16/2: sampled rows."""
+    w = W.WORKLOADS["c5"].with_(B=1, H_q=16, H_kv=2, prefix=(32768, 32768), kconfig=(4, 2))
+    ai = W.gen_attn_inputs(w)
+    call = D.make_attn_call(ai)
+    M.mcsd_tree_attn(call.args)
+    torch.cuda.synchronize()
+    got = call.out_numpy()
+    sel = np.array([[0, 0, 0], [0, 11, 15], [0, 5, 7], [0, 3, 8]], np.int32)
+    ref = O.tree_attn(ai.q, ai.k_prefix, ai.v_prefix, ai.prefix_len, ai.k_tree, ai.v_tree, ai.parent, ai.scale,
+                      O.BF16, sel=sel, n_threads=4)
+    assert np.abs(got[sel[:, 0], sel[:, 1], sel[:, 2]] - ref).max() <= 2e-2
