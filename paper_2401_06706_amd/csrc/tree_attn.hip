@@ -47,6 +47,7 @@ struct AttnParams {
     int B, N, H_q, H_kv, G, d, L_stride, M;
     int n_row_tiles, chunk_tiles, n_chunks_max, tiles_tree, parent_per_seq, dtype;
     int R;                // rows per (b, g) in the partial buffers
+    int split_bias;       // see split_tiles
     float scale_log2;     // scale * log2(e)
 };
 
@@ -71,6 +72,17 @@ __device__ __forceinline__ float fast_exp2(float x)
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16)
 {
     return __uint_as_float(bits16 << 16);
+}
+
+// The T key tiles of a sequence are cut into n segments of seg tiles (the last one possibly
+// shorter): n = (T + bias) / chunk_tiles, at least 1.  With bias = chunk_tiles / 2 that is
+// T / chunk_tiles rounded to nearest, so a sequence a little longer than a multiple of
+// chunk_tiles does not pay a partial for a sliver; seg < 1.5 chunk_tiles.
+__device__ __forceinline__ void split_tiles(int T, int chunk_tiles, int bias, int *n, int *seg)
+{
+    const int nn = max(1, (T + bias) / chunk_tiles);
+    *n = nn;
+    *seg = (T + nn - 1) / nn;
 }
 
 // anc[i] = {i} U anc[parent[i]]: one 128-bit mask per node, built by walking up.
@@ -170,7 +182,9 @@ void tree_attn_mfma_kernel(AttnParams p)
                 int Lb = p.prefix_len[tid / p.n_chunks_max];
                 Lb = max(0, min(Lb, p.L_stride));
                 const int Tb = (Lb + KT - 1) / KT + p.tiles_tree;
-                my_len = max(0, min(p.chunk_tiles, Tb - (tid % p.n_chunks_max) * p.chunk_tiles));
+                int nb, segb;
+                split_tiles(Tb, p.chunk_tiles, p.split_bias, &nb, &segb);
+                my_len = max(0, min(segb, Tb - (tid % p.n_chunks_max) * segb));
                 s_pair_len[tid] = my_len;
             }
             __syncthreads();
@@ -190,10 +204,12 @@ void tree_attn_mfma_kernel(AttnParams p)
         L = p.prefix_len[b];
         L = max(0, min(L, p.L_stride));
         total_tiles = (L + KT - 1) / KT + p.tiles_tree;
-        t_begin = chunk * p.chunk_tiles;
+        int n_seg, seg;
+        split_tiles(total_tiles, p.chunk_tiles, p.split_bias, &n_seg, &seg);
+        t_begin = chunk * seg;
         if (t_begin >= total_tiles) return;
-        t_end = min(total_tiles, t_begin + p.chunk_tiles);
-        direct = (total_tiles <= p.chunk_tiles);
+        t_end = min(total_tiles, t_begin + seg);
+        direct = (n_seg == 1);
         part_row = (((size_t)b * p.H_kv + g) * p.n_chunks_max + chunk) * (size_t)p.R + (size_t)rt * ROWS;
     }
     {
@@ -463,30 +479,24 @@ void tree_attn_mfma_kernel(AttnParams p)
                     *reinterpret_cast<f32x4 *>(farea + (16 * mt + lc_e) * 68 + 16 * n4 + 4 * lj_e) = v;
                 }
             __syncthreads();
-            for (int idx = tid_e; idx < rows_valid * 8; idx += NT) {
-                const int r = idx >> 3, d8 = idx & 7;
+            // one 16-byte piece per lane, neighbouring lanes neighbouring pieces: every store
+            // instruction of the partial covers whole 256-byte runs
+            for (int idx = tid_e; idx < rows_valid * 16; idx += NT) {
+                const int r = idx >> 4, d4 = idx & 15;
                 const int rg = r / WROWS, rl = r % WROWS;
-                float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int k2 = 0; k2 < KS; ++k2) {
-                    const float *src = reinterpret_cast<const float *>(s_big + (rg * KS + k2) * AREA_WORDS) + rl * 68 + 8 * d8;
-                    const f32x4 a0 = *reinterpret_cast<const f32x4 *>(src);
-                    const f32x4 a1 = *reinterpret_cast<const f32x4 *>(src + 4);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) { acc[e] += a0[e]; acc[4 + e] += a1[e]; }
-                }
-                const int dcol = 64 * half + 8 * d8;
+                for (int k2 = 0; k2 < KS; ++k2)
+                    acc += *reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(s_big + (rg * KS + k2) * AREA_WORDS) + rl * 68 + 4 * d4);
+                const int dcol = 64 * half + 4 * d4;
                 if (direct) {
                     const float inv = s_linv[r];
-                    u32x4 pk = {pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv),
-                                pack_bf16(acc[4] * inv, acc[5] * inv), pack_bf16(acc[6] * inv, acc[7] * inv)};
+                    const uint2 pk = {pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv)};
                     const int gr = row0 + r, node = gr / p.G, hh = gr % p.G;
                     uint16_t *ob = static_cast<uint16_t *>(p.out);
-                    *reinterpret_cast<u32x4 *>(ob + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + dcol) = pk;
+                    *reinterpret_cast<uint2 *>(ob + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + dcol) = pk;
                 } else {
-                    float *dst = p.part_o + (part_row + r) * D + dcol;
-                    *reinterpret_cast<f32x4 *>(dst) = (f32x4){acc[0], acc[1], acc[2], acc[3]};
-                    *reinterpret_cast<f32x4 *>(dst + 4) = (f32x4){acc[4], acc[5], acc[6], acc[7]};
+                    *reinterpret_cast<f32x4 *>(p.part_o + (part_row + r) * D + dcol) = acc;
                 }
             }
             __syncthreads();
@@ -506,31 +516,50 @@ __global__ __launch_bounds__(256) void tree_attn_combine_kernel(AttnParams p)
     int L = p.prefix_len[b];
     L = max(0, min(L, p.L_stride));
     const int total_tiles = (L + KT - 1) / KT + p.tiles_tree;
-    const int n_chunks = (total_tiles + p.chunk_tiles - 1) / p.chunk_tiles;
+    int n_chunks, seg;
+    split_tiles(total_tiles, p.chunk_tiles, p.split_bias, &n_chunks, &seg);
+    n_chunks = (total_tiles + seg - 1) / seg;      // segments that are not empty
     if (n_chunks <= 1) return;      // the attention kernel wrote the output itself
-    const int r = blockIdx.x * 16 + (threadIdx.x >> 4);
-    const int d8 = threadIdx.x & 15;
+    const int r = blockIdx.x * 8 + (threadIdx.x >> 5);
+    const int d4 = threadIdx.x & 31;        // 16-byte piece of the row
     if (r >= p.M) return;
     const size_t base = (((size_t)b * p.H_kv + g) * p.n_chunks_max) * (size_t)p.R + r;
-    float ms = M_INIT;
-    for (int c = 0; c < n_chunks; ++c) ms = fmaxf(ms, p.part_m[base + (size_t)c * p.R]);
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     float ls = 0.f;
-    for (int c = 0; c < n_chunks; ++c) {
-        const size_t u = base + (size_t)c * p.R;
-        const float fsc = exp2f(p.part_m[u] - ms);
-        ls += fsc * p.part_l[u];
-        const float4 a0 = *reinterpret_cast<const float4 *>(p.part_o + u * D + 8 * d8);
-        const float4 a1 = *reinterpret_cast<const float4 *>(p.part_o + u * D + 8 * d8 + 4);
-        acc[0] += fsc * a0.x; acc[1] += fsc * a0.y; acc[2] += fsc * a0.z; acc[3] += fsc * a0.w;
-        acc[4] += fsc * a1.x; acc[5] += fsc * a1.y; acc[6] += fsc * a1.z; acc[7] += fsc * a1.w;
+    if (n_chunks <= 4) {
+        // the usual case: every load is issued before the first use, one memory round trip
+        float mc[4], lc[4];
+        f32x4 oc[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const bool on = c < n_chunks;
+            const size_t u = base + (size_t)(on ? c : 0) * p.R;
+            mc[c] = on ? p.part_m[u] : M_INIT;
+            lc[c] = on ? p.part_l[u] : 0.f;
+            oc[c] = *reinterpret_cast<const f32x4 *>(p.part_o + u * D + 4 * d4);
+        }
+        const float ms = fmaxf(fmaxf(mc[0], mc[1]), fmaxf(mc[2], mc[3]));
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float fsc = (c < n_chunks) ? exp2f(mc[c] - ms) : 0.f;
+            ls += fsc * lc[c];
+            acc += fsc * oc[c];
+        }
+    } else {
+        float ms = M_INIT;
+        for (int c = 0; c < n_chunks; ++c) ms = fmaxf(ms, p.part_m[base + (size_t)c * p.R]);
+        for (int c = 0; c < n_chunks; ++c) {
+            const size_t u = base + (size_t)c * p.R;
+            const float fsc = exp2f(p.part_m[u] - ms);
+            ls += fsc * p.part_l[u];
+            acc += fsc * *reinterpret_cast<const f32x4 *>(p.part_o + u * D + 4 * d4);
+        }
     }
     const float inv = 1.0f / ls;
-    u32x4 pk = {pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv),
-                pack_bf16(acc[4] * inv, acc[5] * inv), pack_bf16(acc[6] * inv, acc[7] * inv)};
+    const uint2 pk = {pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv)};
     const int node = r / p.G, hh = r % p.G;
     uint16_t *ob = static_cast<uint16_t *>(p.out);
-    *reinterpret_cast<u32x4 *>(ob + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + 8 * d8) = pk;
+    *reinterpret_cast<uint2 *>(ob + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + 4 * d4) = pk;
 }
 
 // ------------------------------------------------------------------ generic path
@@ -676,8 +705,13 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
     // than 6 tiles per key stream do not amortise (measured).
     const long min_run = 6 * key_streams;
 
-    // Enough workgroups to cover the CUs (two resident workgroups each) several times over.
-    const long target_wgs = env_int("MCSD_ATTN_TARGET_WGS", 2048);
+    // Workgroups per launch if every sequence had the maximum length (the CUs hold 512 at a time).
+    // More, shorter segments balance the end of the launch better but every segment of a split
+    // unit costs one fp32 partial written and read back.  Where the kernel is HBM-bound (one row
+    // tile per KV head) that traffic competes with the cache stream and 1024 measured best; where
+    // the matrix cores are the limit (several row tiles share each key stream) the partials are
+    // free and 2048 measured best.
+    const long target_wgs = env_int("MCSD_ATTN_TARGET_WGS", pl.n_row_tiles == 1 ? 1024 : 2048);
     long chunk = (total_max * units + target_wgs - 1) / target_wgs;
     chunk = ((chunk + key_streams - 1) / key_streams) * key_streams;
     if (chunk < min_run) chunk = min_run;
@@ -723,6 +757,7 @@ int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const
     }
     p.n_row_tiles = plan.n_row_tiles; p.chunk_tiles = plan.chunk_tiles; p.n_chunks_max = plan.n_chunks_max;
     p.tiles_tree = plan.tiles_tree; p.R = (int)plan.partial_stride_rows;
+    p.split_bias = plan.chunk_tiles / 2;
     if (plan.ws_bytes > 0) {
         const size_t rows = (size_t)d.B * d.H_kv * plan.n_chunks_max * plan.partial_stride_rows;
         float *ws = static_cast<float *>(b.workspace);
@@ -738,7 +773,7 @@ int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const
     e = hipGetLastError();
     if (e != hipSuccess) { set_error("tree_attn_mfma launch failed: %s", hipGetErrorString(e)); return MCSD_E_HIP; }
     if (plan.n_chunks_max > 1) {
-        dim3 cgrid((plan.rows_per_kv + 15) / 16, d.H_kv, d.B);
+        dim3 cgrid((plan.rows_per_kv + 7) / 8, d.H_kv, d.B);
         timing_begin(K_ATTN_COMBINE, stream);
         hipLaunchKernelGGL(tree_attn_combine_kernel, cgrid, dim3(256), 0, stream, p);
         timing_end(K_ATTN_COMBINE, stream);
