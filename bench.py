@@ -31,7 +31,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 # HBM traffic per launch of the tree-attention kernel measured with rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see the
 # summaries under profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {"c4": 652656485}     # profiles/step_c4.md
+MEASURED_TRAFFIC_BYTES = {"c4": 658811306, "c5": 411658860, "c3": 50831869, "c2": 9552891}   # profiles/step_<workload>.md
 
 
 def parse_args():
@@ -80,7 +80,19 @@ def cpu_baseline(w, ai, vi, target_seconds):
              vi.u_endpoint, vi.temperature, vi.variant, gamma_max=vi.tree.gamma, n_threads=threads)
     t_ver = time.perf_counter() - t0
     est_step = t_attn * total_rows / n_rows + t_ver
+    # one thread, on a fifth of the budget: attention rows only (the verification of all rows
+    # on one thread would not fit the budget for the large workloads; it scales the same way)
+    n1 = max(4, int(0.2 * target_seconds / max(per_row * threads, 1e-9)))
+    n1 = min(n1, total_rows)
+    sel1 = np.stack([rng.integers(0, ai.B, n1), rng.integers(0, ai.N, n1), rng.integers(0, ai.H_q, n1)],
+                    axis=1).astype(np.int32)
+    t0 = time.perf_counter()
+    O.tree_attn(ai.q, ai.k_prefix, ai.v_prefix, ai.prefix_len, ai.k_tree, ai.v_tree, ai.parent, ai.scale,
+                dt, sel=sel1, n_threads=1)
+    t1_row = (time.perf_counter() - t0) / n1
     return {
+        "single_thread_attention_rows_per_s": 1.0 / t1_row,
+        "all_threads_attention_rows_per_s": n_rows / t_attn,
         "value": vi.B * vi.N / est_step, "unit": "nodes/s", "cores": threads, "kind": "oracle",
         "sample": f"{n_rows} of {total_rows} attention rows in {t_attn:.3f} s + verification of all "
                   f"{vi.B} sequences in {t_ver:.3f} s; one full step extrapolates to {est_step:.3f} s",
@@ -148,6 +160,22 @@ def main():
     M.mcsd_kernel_timing(False)
     kernels = {k: {"avg_us": 1e3 * ms / n, "launches": n} for k, (ms, n) in ktimes.items() if n > 0}
 
+    # third pass: one event pair per step for the spread, then the same step on ONE input set
+    # (the 256 MB memory-side cache then serves part of the reads): labelled, never the headline
+    def per_step_times(n_steps, offset, one_set=False):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_steps)]
+        for i, (e0, e1) in enumerate(evs):
+            a, v = sets[0 if one_set else (offset + i) % n_sets]
+            e0.record()
+            M.mcsd_verify_step(a.args, v.args)
+            e1.record()
+        torch.cuda.synchronize()
+        return np.array([e0.elapsed_time(e1) for e0, e1 in evs])
+
+    n_spread = min(args.steps, 100)
+    spread = per_step_times(n_spread, 0)
+    hot = per_step_times(n_spread, 0, one_set=True)
+
     dom = "tree_attn_mfma"
     dom_us = kernels[dom]["avg_us"]
     achieved = attn_bytes / (dom_us * 1e-6) / 1e9
@@ -173,6 +201,8 @@ def main():
                    "nodes": ai.N, "H_q": w.H_q, "H_kv": w.H_kv, "d": w.d, "V": w.V,
                    "prefix_tokens_total": int(ai.prefix_len.sum()), "input_sets": n_sets,
                    "variant": "without_replacement" if vi.variant else "with_replacement"},
+        "step_ms_event_p10_p50_p90": [float(x) for x in np.percentile(spread, [10, 50, 90])],
+        "hot_cache_ms_per_step": float(np.median(hot)),
         "step_hbm_gbs": footprint / (ms_per_step * 1e-3) / 1e9,
         "step_hbm_frac": footprint / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "roofline": roofline,
