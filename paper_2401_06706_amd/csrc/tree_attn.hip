@@ -151,10 +151,14 @@ void tree_attn_mfma_kernel(AttnParams p)
     uint32_t kld_pos[4];        // operand position for kk: kld_pos[kk] + sub * 256
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) kld_pos[kk] = kk * 64 + lj * 16 + (lc ^ (4 * kk + lj));
-    //   V: column 8 lc + e of the lane's 8x8 block goes to lane 8 (lc & 1) + e of d-tile lc >> 1
-    const uint32_t vst_base = (lj * 8 + (lc >> 1)) * 16;
-    const uint32_t vst_x = (8 * (lc & 1)) ^ (lc >> 1);      // position = vst_base + (vst_x ^ e)
-    const uint32_t vld_base = lj * 128;                      // position = vld_base + nt * 16 + (lc ^ nt)
+    //   V: column 8 lc + e of the lane's 8x8 block is the operand of lane 8 (lc & 1) + e for d-tile
+    //   lc >> 1.  Position of (d-tile nt, lane hi 8 + lo) in the k-group's 128 granules:
+    //   nt 16 + hi 8 + (lo ^ ((2 nt + hi) & 7)): eight neighbouring lanes cover all banks in the
+    //   stores (fixed e: 2 nt + hi = lc runs through eight values) and in the loads (fixed nt: lo does).
+    const uint32_t vst_base = lj * 128 + lc * 8;            // store position = vst_base + (e ^ vst_x)
+    const uint32_t vst_x = lc & 7;
+    const uint32_t vld_base = lj * 128 + (lc >> 3) * 8;     // load position = vld_base + nt 16 + (vld_x ^ ((2 nt) & 7))
+    const uint32_t vld_x = (lc & 7) ^ (lc >> 3);
     // Per-lane byte offsets inside a tile (row pitch 256 B).
     //   K load i (0..7): row 4 i + lj, 16-byte granule lc  ->  i * 1024 + lane * 16
     //   V load s (0..7): row (s < 4 ? 0 : 16) + 4 lj + (s & 3), granule lc
@@ -419,7 +423,7 @@ void tree_attn_mfma_kernel(AttnParams p)
 #pragma unroll
                 for (int n4 = 0; n4 < 4; ++n4) {
                     const int nt = 4 * nh + n4;
-                    vop[n4] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(area + 4 * (vld_base + nt * 16 + (lc ^ nt))));
+                    vop[n4] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(area + 4 * (vld_base + nt * 16 + (vld_x ^ ((2 * nt) & 7)))));
                 }
 #pragma unroll
                 for (int n4 = 0; n4 < 4; ++n4)
