@@ -23,12 +23,21 @@
  *   mcsd_oracle_verify         Sec. 3, the paragraph describing verification as
  *                              a walk from the root of the candidate tree to a
  *                              leaf, with the endpoint rules of Sec. 2.
+ *   mcsd_oracle_draft_parent / mcsd_oracle_draft_sample
+ *                              Sec. 3.1, the k candidates sampled from the draft
+ *                              distribution at each step: independent draws
+ *                              (input of Algorithm 1) or sequential draws without
+ *                              replacement from q-bar of Eq. (1) (input of
+ *                              Algorithm 2).
  *
  * Pins (tests/test_oracle_*.py): exact enumeration of the output distribution
  * against the theorems of Appendix A and B, the per-round accept / reject
  * masses of Appendix A, hand-derived rational examples, the k=1 textbook rule,
  * the Appendix C inequality, the argmax behaviour stated in Sec. 4.4, and
- * brute-force per-path causal attention.  No function here is unpinned.
+ * brute-force per-path causal attention; for the draft sampler the measure of
+ * the uniforms mapped to each candidate tuple against q and Eq. (1), numpy's
+ * cumulative-sum search, and the end-to-end law (sampler + Algorithm 1 / 2
+ * returns the target distribution).  No function here is unpinned.
  *
  * Readings taken where the paper is silent (listed in full in the design notes
  * of this repository): self is attendable; the root is the last context token
@@ -390,4 +399,102 @@ int mcsd_oracle_verify(int B, int N, int V, int P, int variant, const float *tar
         n_accepted[b] = n;
     }
     return 0;
+}
+
+/* ------------------------------------------------------- draft-side candidates
+ *
+ * The k candidates of one parent, drawn from the draft distribution
+ * q = softmax(z_q / T) (Sec. 3.1: the batch of candidates sampled at each step).
+ *   variant 0 (Algorithm 1's input): k independent draws from q;
+ *   variant 1 (Algorithm 2's input): sequentially without replacement, draw i
+ *     from q-bar of Eq. (1): q with the earlier draws zeroed, renormalised;
+ *   T == 0: the k largest logits in descending order, lowest id on ties (k
+ *     distinct candidates of a draft model that samples by arg max).
+ * Draw i uses the supplied uniform u[i] by inverse CDF in token-id order (the
+ * same convention as the endpoint draw above).  margin[i] = distance from u[i]
+ * to the nearer edge of the chosen token's CDF interval (infinity for T == 0).
+ */
+int mcsd_oracle_draft_parent(int V, int k, int variant, double T, const float *z_q,
+                             const float *u, int32_t *tok, double *margin)
+{
+    if (V <= 0 || k < 0 || k > V) return -1;
+    if (T == 0.0) {
+        char *taken = (char *)calloc((size_t)V, 1);
+        if (!taken) return -3;
+        for (int i = 0; i < k; ++i) {
+            int best = -1;
+            for (int x = 0; x < V; ++x)
+                if (!taken[x] && (best < 0 || z_q[x] > z_q[best])) best = x;
+            taken[best] = 1;
+            tok[i] = best;
+            margin[i] = INFINITY;
+        }
+        free(taken);
+        return 0;
+    }
+    double *q = (double *)malloc(sizeof(double) * (size_t)V);
+    if (!q) return -3;
+    softmax_T(z_q, V, T, q);
+    for (int i = 0; i < k; ++i) {
+        tok[i] = inverse_cdf(q, V, (double)u[i], &margin[i]);
+        if (variant == VARIANT_WITHOUT_REPLACEMENT) {
+            q[tok[i]] = 0.0;
+            double s = 0.0;
+            for (int x = 0; x < V; ++x) s += q[x];
+            if (s > 0.0)
+                for (int x = 0; x < V; ++x) q[x] /= s;
+        }
+    }
+    free(q);
+    return 0;
+}
+
+/*
+ * Candidates of a whole tree: for every row that has children (root row 0, node i
+ * -> row 1+i) the children, in ascending node id, receive the draws of
+ * mcsd_oracle_draft_parent from draft row q_row[row].
+ *   draft_logits [B][P][V], q_row [1+N], parent [N], u_draw [B][N], temperature [B]
+ *   -> cand_tok [B][N], margin [B][N]
+ */
+int mcsd_oracle_draft_sample(int B, int N, int V, int P, int variant, const float *draft_logits,
+                             const int32_t *q_row, const int32_t *parent, const float *u_draw,
+                             const float *temperature, int32_t *cand_tok, double *margin,
+                             int n_threads)
+{
+    for (int i = 0; i < N; ++i)
+        if (parent[i] < -1 || parent[i] >= i) return -2;
+    if (n_threads < 1) n_threads = 1;
+    int status = 0;
+    long rows = (long)B * (1 + N);
+#pragma omp parallel for schedule(dynamic, 1) num_threads(n_threads)
+    for (long r = 0; r < rows; ++r) {
+        int b = (int)(r / (1 + N));
+        int row = (int)(r % (1 + N));
+        int kids[1024];
+        int k = 0;
+        for (int i = 0; i < N && k < 1024; ++i)
+            if (parent[i] == row - 1) kids[k++] = i;
+        if (k == 0) continue;
+        int rc = 0;
+        if (q_row[row] < 0 || q_row[row] >= P) {
+            rc = -1;
+        } else {
+            float us[1024];
+            int32_t toks[1024];
+            double mg[1024];
+            for (int i = 0; i < k; ++i) us[i] = u_draw[(size_t)b * N + kids[i]];
+            rc = mcsd_oracle_draft_parent(V, k, variant, (double)temperature[b],
+                                          draft_logits + ((size_t)b * P + q_row[row]) * V, us, toks, mg);
+            if (rc == 0)
+                for (int i = 0; i < k; ++i) {
+                    cand_tok[(size_t)b * N + kids[i]] = toks[i];
+                    margin[(size_t)b * N + kids[i]] = mg[i];
+                }
+        }
+        if (rc != 0) {
+#pragma omp critical
+            status = rc;
+        }
+    }
+    return status;
 }

@@ -48,6 +48,10 @@ def lib() -> ctypes.CDLL:
             [c.c_double] + [c.c_void_p] * 5
         L.mcsd_oracle_verify.restype = c.c_int
         L.mcsd_oracle_verify.argtypes = [c.c_int] * 5 + [c.c_void_p] * 16 + [c.c_int, c.c_int]
+        L.mcsd_oracle_draft_parent.restype = c.c_int
+        L.mcsd_oracle_draft_parent.argtypes = [c.c_int, c.c_int, c.c_int, c.c_double] + [c.c_void_p] * 4
+        L.mcsd_oracle_draft_sample.restype = c.c_int
+        L.mcsd_oracle_draft_sample.argtypes = [c.c_int] * 5 + [c.c_void_p] * 7 + [c.c_int]
         _lib = L
     return _lib
 
@@ -171,3 +175,35 @@ def verify(target_logits, draft_logits, q_row, parent, cand_tok, u_accept, u_end
         raise ValueError(f"mcsd_oracle_verify failed: {rc}")
     return VerifyResult(acc_child, endpoint, ratio, margin, residual, n_accepted, accepted_path,
                         out_tokens)
+
+
+def draft_parent(z_q, u, k: int, variant: int, T: float = 1.0):
+    """Candidates of one parent (Sec. 3.1; Eq. (1) for variant 1): (tokens int32 [k], margin fp64 [k])."""
+    z_q = np.ascontiguousarray(z_q, dtype=np.float32)
+    u = np.ascontiguousarray(u, dtype=np.float32).reshape(-1)
+    assert u.shape[0] >= k
+    tok = np.empty(max(k, 1), dtype=np.int32)
+    margin = np.empty(max(k, 1), dtype=np.float64)
+    rc = lib().mcsd_oracle_draft_parent(int(z_q.shape[0]), int(k), int(variant), float(T), _ptr(z_q), _ptr(u),
+                                        _ptr(tok), _ptr(margin))
+    if rc != 0:
+        raise ValueError(f"mcsd_oracle_draft_parent failed: {rc}")
+    return tok[:k], margin[:k]
+
+
+def draft_sample(draft_logits, q_row, parent, u_draw, temperature, variant: int, n_threads: int = 1):
+    """Candidates of whole trees: (cand_tok int32 [B][N], margin fp64 [B][N])."""
+    draft_logits = np.ascontiguousarray(draft_logits, dtype=np.float32)
+    B, P, V = draft_logits.shape
+    parent = np.ascontiguousarray(parent, dtype=np.int32)
+    N = parent.shape[0]
+    q_row = np.ascontiguousarray(q_row, dtype=np.int32)
+    u_draw = np.ascontiguousarray(u_draw, dtype=np.float32).reshape(B, N)
+    temperature = np.ascontiguousarray(temperature, dtype=np.float32).reshape(B)
+    cand = np.full((B, N), -1, dtype=np.int32)
+    margin = np.full((B, N), np.inf, dtype=np.float64)
+    rc = lib().mcsd_oracle_draft_sample(B, N, V, P, int(variant), _ptr(draft_logits), _ptr(q_row), _ptr(parent),
+                                        _ptr(u_draw), _ptr(temperature), _ptr(cand), _ptr(margin), int(n_threads))
+    if rc != 0:
+        raise ValueError(f"mcsd_oracle_draft_sample failed: {rc}")
+    return cand, margin
