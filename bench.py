@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--stage", default="verify_step", choices=["verify_step", "draft_sample"],
+                    help="verify_step (default): the headline step; draft_sample: the draft-side candidate "
+                         "sampler that precedes it, measured on its own")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--sets", type=int, default=0, help="rotating input copies (0 = enough for >= 1 GiB)")
@@ -99,6 +102,57 @@ def cpu_baseline(w, ai, vi, target_seconds):
     }
 
 
+def bench_draft_sample(args, torch, M, D, W):
+    """The sampler that produces the candidates the verification step consumes: one launch per
+    step over all draft rows of the workload (B x P rows of V fp32 logits, each read once)."""
+    w = W.WORKLOADS[args.workload]
+    vi = W.gen_verify_inputs(w)
+    u = W.open_uniform(np.random.default_rng(w.seed + 7), (vi.B, vi.N))
+    design_bytes = vi.B * vi.P * vi.V * 4
+    n_sets = args.sets if args.sets > 0 else max(2, int(np.ceil((1 << 30) / design_bytes)))
+    n_sets = min(n_sets, 64)
+    sets = [D.make_draft_call(vi, u) for _ in range(n_sets)]
+    torch.cuda.synchronize()
+
+    def run(n, off=0):
+        for i in range(n):
+            M.mcsd_draft_sample(sets[(off + i) % n_sets].args)
+
+    run(args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps, args.warmup)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    M.mcsd_kernel_timing(True)
+    run(args.steps, args.warmup + args.steps)
+    torch.cuda.synchronize()
+    kt = M.mcsd_kernel_timing_read()
+    M.mcsd_kernel_timing(False)
+    k_us = 1e3 * kt["draft_rows"][0] / kt["draft_rows"][1]
+    out = {
+        "metric": "draft candidates sampled per second (k per parent from softmax(z_q/T))",
+        "value": vi.B * vi.N / (ms * 1e-3), "unit": "candidates/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name} draft rows: {w.description}", "B": w.B, "draft_rows": vi.P,
+                   "nodes": vi.N, "V": vi.V, "input_sets": n_sets,
+                   "variant": "without_replacement" if vi.variant else "with_replacement"},
+        "roofline": {"kernel": "draft_rows", "bound": "hbm", "achieved": design_bytes / (k_us * 1e-6) / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": design_bytes / (k_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                     "traffic": None, "algorithmic_bytes": design_bytes, "avg_kernel_us": k_us},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import mcsd_oracle as O
+        threads = min(O.max_threads(), os.cpu_count() or 1)
+        t0 = time.perf_counter()
+        O.draft_sample(vi.draft_logits, vi.tree.q_row, vi.tree.parent, u, vi.temperature, vi.variant, n_threads=threads)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": vi.B * vi.N / dt, "unit": "candidates/s", "cores": threads, "kind": "oracle",
+                               "sample": f"all {vi.B * vi.P} draft rows of the workload in {dt:.3f} s"}
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -122,6 +176,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes": src.numel() * 4, "copies": 4}))
+        return
+    if args.stage == "draft_sample":
+        bench_draft_sample(args, torch, M, D, W)
         return
     w = W.WORKLOADS[args.workload]
     ai = W.gen_attn_inputs(w)

@@ -2,7 +2,7 @@
  * mcsd.h - C ABI of libmcsd: the target-side verification step of
  * Multi-Candidate Speculative Decoding (MCSD) on one AMD MI355X (gfx950).
  *
- * Three operations, all enqueued asynchronously on a caller-supplied HIP stream:
+ * Operations, all enqueued asynchronously on a caller-supplied HIP stream:
  *
  *   mcsd_tree_attn      Tree attention (Sec. 3.3 of the paper): all candidate
  *                       tokens of the draft tree are scored in one pass against
@@ -15,6 +15,9 @@
  *                       turns the per-node outcomes into the accepted path.
  *   mcsd_verify_step    Both, back to back on one stream: one layer's tree
  *                       attention followed by one verification.
+ *   mcsd_draft_sample   The step before: the k candidates of every parent drawn
+ *                       from the draft distribution (Sec. 3.1; Eq. (1) when
+ *                       sampling without replacement).
  *
  * Conventions
  *   - Plain C, plain-old-data structs; the first field of every struct is its
@@ -76,7 +79,8 @@ enum {
     MCSD_FLAG_ZERO_DRAFT_PROB = 8,    /* q(candidate) == 0: ratio taken as 1 if p > 0 else 0 */
     MCSD_FLAG_ZERO_RESIDUAL = 16,     /* sum max(0, p - q) was not positive after a rejection */
     MCSD_FLAG_NONFINITE = 32,         /* a softmax normaliser was not finite and positive */
-    MCSD_FLAG_BAD_TREE = 64           /* a row with children has no valid q_row entry: handled as a leaf */
+    MCSD_FLAG_BAD_TREE = 64,          /* a row with children has no valid q_row entry: handled as a leaf */
+    MCSD_FLAG_NEAR_TIE_DRAW = 128     /* mcsd_draft_sample: u_draw within near_tie_eps of an edge of the chosen CDF interval */
 };
 
 const char *mcsd_last_error(void);
@@ -185,6 +189,46 @@ int32_t mcsd_verify_sample(const mcsd_verify_desc *desc, const mcsd_verify_bufs 
 int32_t mcsd_verify_step(const mcsd_attn_desc *attn_desc, const mcsd_attn_bufs *attn_bufs,
                          const mcsd_verify_desc *verify_desc, const mcsd_verify_bufs *verify_bufs,
                          void *stream);
+
+/* ------------------------------------------------------- draft-side candidates
+ * Sec. 3.1: the k candidates of every row that has children, sampled from the
+ * draft distribution q_r = softmax(draft_logits[b][q_row[r]] / T); this is the
+ * step just before verification and its output is the cand_tok input above.
+ * For the children c_1 < c_2 < ... < c_k of row r:
+ *   MCSD_WITH_REPLACEMENT     cand_tok[b][c_i] = inverse CDF of q_r at u_draw[b][c_i]
+ *                             (token-id order, smallest x whose cumulative probability
+ *                             exceeds the uniform): k independent draws, Algorithm 1's input;
+ *   MCSD_WITHOUT_REPLACEMENT  the same, but draw i is taken from q_r with the tokens
+ *                             of draws 1..i-1 zeroed and the rest renormalised (q-bar of
+ *                             Eq. (1)): k distinct tokens, Algorithm 2's input;
+ *   T == 0                    the k largest draft logits in descending order, lowest id
+ *                             on ties; uniforms are not read.
+ * Entries of cand_tok whose parent row has no valid q_row are set to -1 and flagged
+ * MCSD_FLAG_BAD_TREE.  Requires k <= V for every row.  Elementwise math in fp32
+ * (the same exponentials as mcsd_verify_sample), cumulative sums in fp64.
+ */
+typedef struct {
+    uint32_t struct_size;
+    int32_t B;
+    int32_t N;              /* tree nodes per sequence, 1..MCSD_MAX_NODES */
+    int32_t V;              /* vocabulary, 1..MCSD_MAX_VOCAB */
+    int32_t P;              /* rows of draft_logits per sequence */
+    int32_t variant;        /* MCSD_WITH_REPLACEMENT | MCSD_WITHOUT_REPLACEMENT */
+    float near_tie_eps;     /* threshold of MCSD_FLAG_NEAR_TIE_DRAW, e.g. 1e-6 */
+} mcsd_draft_desc;
+
+typedef struct {
+    uint32_t struct_size;
+    const float *draft_logits;   /* [B][P][V], 16-byte aligned */
+    const int32_t *q_row;        /* [1+N] row of draft_logits for each tree row, -1 for leaves */
+    const int32_t *parent;       /* [N] shared by the batch */
+    const float *u_draw;         /* [B][N] uniform in (0,1) for each node's draw */
+    const float *temperature;    /* [B], 0 = top-k */
+    int32_t *cand_tok;           /* [B][N] out */
+    uint32_t *flags;             /* [B][N] out: MCSD_FLAG_NEAR_TIE_DRAW / MCSD_FLAG_BAD_TREE / MCSD_FLAG_NONFINITE per node */
+} mcsd_draft_bufs;
+
+int32_t mcsd_draft_sample(const mcsd_draft_desc *desc, const mcsd_draft_bufs *bufs, void *stream);
 
 /* ------------------------------------------------------------ profiling aid
  * Not part of the verification step.  mcsd_kernel_timing(1) makes every kernel

@@ -26,6 +26,7 @@ FLAG_ZERO_DRAFT_PROB, FLAG_ZERO_RESIDUAL, FLAG_NONFINITE, FLAG_BAD_TREE = 8, 16,
 
 EXPORTS = ["mcsd_last_error", "mcsd_version", "mcsd_tree_validate", "mcsd_attn_workspace_bytes",
            "mcsd_tree_attn", "mcsd_verify_workspace_bytes", "mcsd_verify_sample", "mcsd_verify_step",
+           "mcsd_draft_sample",
            "mcsd_kernel_timing", "mcsd_kernel_count", "mcsd_kernel_name", "mcsd_kernel_timing_read"]
 
 
@@ -61,6 +62,16 @@ class VerifyBufs(C.Structure):
         "flags", "residual_out", "workspace")] + [("workspace_bytes", C.c_size_t)]
 
 
+class DraftDesc(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("B", C.c_int32), ("N", C.c_int32), ("V", C.c_int32),
+                ("P", C.c_int32), ("variant", C.c_int32), ("near_tie_eps", C.c_float)]
+
+
+class DraftBufs(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32)] + [(n, C.c_void_p) for n in (
+        "draft_logits", "q_row", "parent", "u_draw", "temperature", "cand_tok", "flags")]
+
+
 _lib: Optional[C.CDLL] = None
 
 
@@ -88,6 +99,8 @@ def lib() -> C.CDLL:
         L.mcsd_verify_step.argtypes = [C.POINTER(AttnDesc), C.POINTER(AttnBufs), C.POINTER(VerifyDesc),
                                        C.POINTER(VerifyBufs), C.c_void_p]
         L.mcsd_verify_step.restype = C.c_int32
+        L.mcsd_draft_sample.argtypes = [C.POINTER(DraftDesc), C.POINTER(DraftBufs), C.c_void_p]
+        L.mcsd_draft_sample.restype = C.c_int32
         L.mcsd_kernel_timing.argtypes = [C.c_int32]
         L.mcsd_kernel_timing.restype = C.c_int32
         L.mcsd_kernel_count.restype = C.c_int32
@@ -244,6 +257,36 @@ def mcsd_verify_sample(args: VerifyArgs, stream=None) -> None:
 def mcsd_verify_step(attn: AttnArgs, verify: VerifyArgs, stream=None) -> None:
     _check(lib().mcsd_verify_step(C.byref(attn.desc), C.byref(attn.bufs), C.byref(verify.desc),
                                   C.byref(verify.bufs), _stream(stream)))
+
+
+# ----------------------------------------------------------- draft-side candidates
+@dataclass
+class DraftArgs:
+    desc: DraftDesc
+    bufs: DraftBufs
+    keep: tuple
+
+
+def draft_args(draft_logits, q_row, parent, u_draw, temperature, cand_tok, flags, variant: int,
+               near_tie_eps: float = 1e-6) -> DraftArgs:
+    """Shapes: draft_logits [B][P][V]; q_row int32 [1+N]; parent int32 [N]; u_draw [B][N];
+    temperature [B]; outputs cand_tok int32 [B][N], flags int32 [B][N]."""
+    B, P, V = draft_logits.shape
+    N = parent.shape[0]
+    f32, i32 = torch.float32, torch.int32
+    for t, shp in [(q_row, (1 + N,)), (u_draw, (B, N)), (temperature, (B,)), (cand_tok, (B, N)), (flags, (B, N))]:
+        if tuple(t.shape) != shp:
+            raise ValueError(f"shape mismatch: got {tuple(t.shape)}, expected {shp}")
+    desc = DraftDesc(C.sizeof(DraftDesc), B, N, V, P, int(variant), float(near_tie_eps))
+    bufs = DraftBufs(C.sizeof(DraftBufs), _ptr(draft_logits, f32, "draft_logits"), _ptr(q_row, i32, "q_row"),
+                     _ptr(parent, i32, "parent"), _ptr(u_draw, f32, "u_draw"),
+                     _ptr(temperature, f32, "temperature"), _ptr(cand_tok, i32, "cand_tok"),
+                     _ptr(flags, i32, "flags"))
+    return DraftArgs(desc, bufs, (draft_logits, q_row, parent, u_draw, temperature, cand_tok, flags))
+
+
+def mcsd_draft_sample(args: DraftArgs, stream=None) -> None:
+    _check(lib().mcsd_draft_sample(C.byref(args.desc), C.byref(args.bufs), _stream(stream)))
 
 
 # ------------------------------------------------------------------- profiling aid

@@ -1,5 +1,5 @@
 // C ABI of libmcsd: argument validation, error reporting, optional per-kernel
-// event timing.  All compute happens in tree_attn.hip and verify_sample.hip.
+// event timing.  All compute happens in tree_attn.hip, verify_sample.hip and draft_sample.hip.
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
@@ -33,7 +33,7 @@ hipEvent_t g_open[K_COUNT];
 double g_total_ms[K_COUNT];
 long long g_count[K_COUNT];
 const char *const g_names[K_COUNT] = {"tree_attn_mfma", "tree_attn_generic", "tree_attn_combine",
-                                      "verify_rows", "walk"};
+                                      "verify_rows", "walk", "draft_rows"};
 }  // namespace
 
 void timing_begin(int id, hipStream_t stream)
@@ -167,6 +167,27 @@ static int32_t check_verify(const mcsd_verify_desc *d, const mcsd_verify_bufs *b
     return MCSD_OK;
 }
 
+static int32_t check_draft(const mcsd_draft_desc *d, const mcsd_draft_bufs *b)
+{
+    if (!d) { set_error("draft desc is NULL"); return MCSD_E_NULL; }
+    if (d->struct_size != sizeof(mcsd_draft_desc)) { set_error("draft desc struct_size %u != %zu", d->struct_size, sizeof(mcsd_draft_desc)); return MCSD_E_SHAPE; }
+    if (d->B < 1 || d->V < 1 || d->P < 1) { set_error("draft: non-positive size"); return MCSD_E_SHAPE; }
+    if (d->N < 1 || d->N > MCSD_MAX_NODES) { set_error("draft: N %d outside 1..%d", d->N, MCSD_MAX_NODES); return MCSD_E_TREE; }
+    if (d->P > 1 + d->N) { set_error("draft: P %d > 1+N", d->P); return MCSD_E_SHAPE; }
+    if (d->B > 65535) { set_error("draft: B %d > 65535", d->B); return MCSD_E_UNSUPPORTED; }
+    if (d->V > MCSD_MAX_VOCAB) { set_error("draft: V %d > %d", d->V, MCSD_MAX_VOCAB); return MCSD_E_UNSUPPORTED; }
+    if (d->variant != MCSD_WITH_REPLACEMENT && d->variant != MCSD_WITHOUT_REPLACEMENT) { set_error("draft: unknown variant %d", d->variant); return MCSD_E_UNSUPPORTED; }
+    if (!(d->near_tie_eps >= 0.f)) { set_error("draft: near_tie_eps must be >= 0"); return MCSD_E_SHAPE; }
+    if (!b) { set_error("draft bufs is NULL"); return MCSD_E_NULL; }
+    if (b->struct_size != sizeof(mcsd_draft_bufs)) { set_error("draft bufs struct_size %u != %zu", b->struct_size, sizeof(mcsd_draft_bufs)); return MCSD_E_SHAPE; }
+    if (!b->draft_logits || !b->q_row || !b->parent || !b->u_draw || !b->temperature || !b->cand_tok || !b->flags) {
+        set_error("draft: NULL buffer");
+        return MCSD_E_NULL;
+    }
+    if (d->V % 4 == 0 && ((uintptr_t)b->draft_logits & 15u)) { set_error("draft: draft_logits must be 16-byte aligned"); return MCSD_E_SHAPE; }
+    return MCSD_OK;
+}
+
 size_t mcsd_attn_workspace_bytes(const mcsd_attn_desc *desc)
 {
     AttnPlan plan;
@@ -195,6 +216,13 @@ int32_t mcsd_verify_sample(const mcsd_verify_desc *desc, const mcsd_verify_bufs 
     int32_t rc = check_verify(desc, bufs);
     if (rc != MCSD_OK) return rc;
     return launch_verify(*desc, *bufs, (hipStream_t)stream);
+}
+
+int32_t mcsd_draft_sample(const mcsd_draft_desc *desc, const mcsd_draft_bufs *bufs, void *stream)
+{
+    int32_t rc = check_draft(desc, bufs);
+    if (rc != MCSD_OK) return rc;
+    return launch_draft_sample(*desc, *bufs, (hipStream_t)stream);
 }
 
 int32_t mcsd_verify_step(const mcsd_attn_desc *ad, const mcsd_attn_bufs *ab, const mcsd_verify_desc *vd,

@@ -9,7 +9,7 @@
 namespace mcsd {
 
 // Kernel ids for the optional per-kernel event timing.
-enum KernelId { K_ATTN_MFMA = 0, K_ATTN_GENERIC = 1, K_ATTN_COMBINE = 2, K_VERIFY_ROWS = 3, K_WALK = 4, K_COUNT = 5 };
+enum KernelId { K_ATTN_MFMA = 0, K_ATTN_GENERIC = 1, K_ATTN_COMBINE = 2, K_VERIFY_ROWS = 3, K_WALK = 4, K_DRAFT_ROWS = 5, K_COUNT = 6 };
 
 void set_error(const char *fmt, ...);
 
@@ -38,5 +38,8 @@ int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const
 
 // ---- verification ---------------------------------------------------------
 int32_t launch_verify(const mcsd_verify_desc &d, const mcsd_verify_bufs &b, hipStream_t stream);
+
+// ---- draft-side candidates ------------------------------------------------
+int32_t launch_draft_sample(const mcsd_draft_desc &d, const mcsd_draft_bufs &b, hipStream_t stream);
 
 }  // namespace mcsd

@@ -98,3 +98,32 @@ def make_verify_call(vi: VerifyInputs, device="cuda:0", want_ratio: bool = True,
                             vi.variant, ratio=t["ratio"], residual_out=t["residual_out"],
                             near_tie_eps=near_tie_eps)
     return VerifyCall(args, t)
+
+
+@dataclass
+class DraftCall:
+    args: "mcsd.DraftArgs"
+    tensors: Dict[str, Optional[torch.Tensor]]
+
+    def results(self) -> Dict[str, np.ndarray]:
+        return {n: self.tensors[n].detach().cpu().numpy() for n in ("cand_tok", "flags")}
+
+
+def make_draft_call(vi: VerifyInputs, u_draw: np.ndarray, device="cuda:0", near_tie_eps: float = 1e-6,
+                    cand_tok: Optional[torch.Tensor] = None) -> DraftCall:
+    """Draft-side sampling for the trees of `vi` (its draft logits, tree, temperatures and variant) with
+    the uniforms u_draw [B][N].  `cand_tok` may be the candidate tensor of a verification call, which
+    then consumes the sampler's output on the same stream."""
+    B, N = vi.B, vi.N
+    t: Dict[str, Optional[torch.Tensor]] = {
+        "draft_logits": torch.from_numpy(vi.draft_logits).to(device),
+        "q_row": torch.from_numpy(vi.tree.q_row.astype(np.int32)).to(device),
+        "parent": torch.from_numpy(vi.tree.parent.astype(np.int32)).to(device),
+        "u_draw": torch.from_numpy(np.ascontiguousarray(u_draw, dtype=np.float32)).to(device),
+        "temperature": torch.from_numpy(vi.temperature).to(device),
+        "cand_tok": cand_tok if cand_tok is not None else torch.full((B, N), -7, dtype=torch.int32, device=device),
+        "flags": torch.full((B, N), -7, dtype=torch.int32, device=device),
+    }
+    args = mcsd.draft_args(t["draft_logits"], t["q_row"], t["parent"], t["u_draw"], t["temperature"],
+                           t["cand_tok"], t["flags"], vi.variant, near_tie_eps=near_tie_eps)
+    return DraftCall(args, t)

@@ -43,7 +43,9 @@ def test_struct_layout_matches_header(tmp_path):
               "mcsd_attn_bufs": (M.AttnBufs, ["q", "prefix_len", "out", "workspace", "workspace_bytes"]),
               "mcsd_verify_desc": (M.VerifyDesc, ["V", "P", "variant", "gamma_max", "near_tie_eps"]),
               "mcsd_verify_bufs": (M.VerifyBufs, ["target_logits", "temperature", "acc_child", "ratio",
-                                                  "flags", "residual_out", "workspace_bytes"])}
+                                                  "flags", "residual_out", "workspace_bytes"]),
+              "mcsd_draft_desc": (M.DraftDesc, ["B", "V", "P", "variant", "near_tie_eps"]),
+              "mcsd_draft_bufs": (M.DraftBufs, ["draft_logits", "q_row", "u_draw", "temperature", "cand_tok", "flags"])}
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "mcsd.h"', "int main(void){"]
     for cname, (_, fs) in fields.items():
         lines.append(f'printf("{cname} %zu\\n", sizeof({cname}));')
@@ -155,3 +157,27 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(M, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(FileNotFoundError):
         M.lib()
+
+
+def test_draft_descriptor_errors(lib):
+    def desc(**kw):
+        a = dict(B=2, N=6, V=64, P=3, variant=0, near_tie_eps=1e-6)
+        a.update(kw)
+        return M.DraftDesc(C.sizeof(M.DraftDesc), a["B"], a["N"], a["V"], a["P"], a["variant"], a["near_tie_eps"])
+    ptrs = [4096] * 7
+    bufs = M.DraftBufs(C.sizeof(M.DraftBufs), *ptrs)
+    cases = [(dict(N=0), -4), (dict(N=200), -4), (dict(V=0), -2), (dict(V=40000), -3), (dict(P=9), -2),
+             (dict(variant=3), -3), (dict(near_tie_eps=-1.0), -2), (dict(B=70000), -3), (dict(P=0), -2)]
+    for kw, code in cases:
+        d = desc(**kw)
+        assert lib.mcsd_draft_sample(C.byref(d), C.byref(bufs), None) == code, kw
+        assert len(lib.mcsd_last_error()) > 0
+    d = desc()
+    assert lib.mcsd_draft_sample(None, C.byref(bufs), None) == -1
+    assert lib.mcsd_draft_sample(C.byref(d), None, None) == -1
+    for i in range(7):
+        p2 = list(ptrs); p2[i] = None
+        assert lib.mcsd_draft_sample(C.byref(d), C.byref(M.DraftBufs(C.sizeof(M.DraftBufs), *p2)), None) == -1, i
+    assert lib.mcsd_draft_sample(C.byref(d), C.byref(M.DraftBufs(5, *ptrs)), None) == -2
+    p2 = list(ptrs); p2[0] = 4096 + 4
+    assert lib.mcsd_draft_sample(C.byref(d), C.byref(M.DraftBufs(C.sizeof(M.DraftBufs), *p2)), None) == -2

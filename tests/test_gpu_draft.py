@@ -1,0 +1,159 @@
+"""mcsd_draft_sample against the oracle: candidate tokens bit-exact except where the oracle's
+margin (distance of the uniform to an edge of the chosen CDF interval) is inside the near-tie band,
+where the kernel must have set MCSD_FLAG_NEAR_TIE_DRAW or agree anyway."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mcsd_oracle as O
+from paper_2401_06706_amd import binding as M
+from paper_2401_06706_amd import device as D
+from paper_2401_06706_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+NEAR = 1e-6
+FLAG_DRAW, FLAG_BAD_TREE = 128, 64
+
+
+def run(vi, u_draw, threads=8):
+    call = D.make_draft_call(vi, u_draw)
+    M.mcsd_draft_sample(call.args)
+    torch.cuda.synchronize()
+    got = call.results()
+    ref_tok, ref_margin = O.draft_sample(vi.draft_logits, vi.tree.q_row, vi.tree.parent, u_draw, vi.temperature,
+                                         vi.variant, n_threads=threads)
+    return got, ref_tok, ref_margin
+
+
+def compare(vi, got, ref_tok, ref_margin, label):
+    tok, flags = got["cand_tok"], got["flags"]
+    assert tok.shape == ref_tok.shape
+    decided = ref_margin >= NEAR
+    if vi.variant == W.WITHOUT_REPLACEMENT:
+        # a near-tie in an earlier draw of the same parent changes what later draws see
+        for b in range(vi.B):
+            for row in range(1 + vi.N):
+                kids = vi.tree.children[row]
+                for i, c in enumerate(kids):
+                    if any(ref_margin[b, kids[j]] < NEAR for j in range(i)):
+                        decided[b, c] = False
+    bad = decided & (tok != ref_tok)
+    assert not bad.any(), f"{label}: {int(bad.sum())} mismatches, first at {np.argwhere(bad)[:4].tolist()}"
+    assert np.all((flags & ~np.int32(FLAG_DRAW)) == 0), f"{label}: unexpected flags {np.unique(flags)}"
+    assert ((tok >= 0) & (tok < vi.V)).all()
+    return {"nodes": int(tok.size), "near_tie": int((~decided).sum()), "flagged": int((flags != 0).sum())}
+
+
+@pytest.mark.parametrize("variant", [W.WITH_REPLACEMENT, W.WITHOUT_REPLACEMENT])
+def test_c1_many_seeds(variant):
+    # 10^4 independent (logit row, uniforms) cases: B sequences with their own rows
+    w = W.WORKLOADS["c1"].with_(variant=variant, B=4000)
+    vi = W.gen_verify_inputs(w)
+    u = W.open_uniform(np.random.default_rng(5), (vi.B, vi.N))
+    got, rt, rm = run(vi, u)
+    st = compare(vi, got, rt, rm, f"c1-{variant}")
+    total = st["nodes"]
+    assert total >= 10000
+
+
+@pytest.mark.parametrize("name", ["c2", "c3", "c5"])
+def test_llama_shaped_workloads(name):
+    w = W.WORKLOADS[name]
+    vi = W.gen_verify_inputs(w)
+    u = W.open_uniform(np.random.default_rng(w.seed + 7), (vi.B, vi.N))
+    got, rt, rm = run(vi, u)
+    compare(vi, got, rt, rm, name)
+
+
+@pytest.mark.parametrize("variant", [W.WITH_REPLACEMENT, W.WITHOUT_REPLACEMENT])
+def test_c4_full_size_sampled_and_top_k(variant):
+    w = W.WORKLOADS["c4"].with_(variant=variant)
+    vi = W.gen_verify_inputs(w)
+    u = W.open_uniform(np.random.default_rng(w.seed + 7), (vi.B, vi.N))
+    got, rt, rm = run(vi, u, threads=16)
+    st = compare(vi, got, rt, rm, f"c4-{variant}")
+    # greedy sequences (temperature 0): top-k in descending order, exactly what the input generator proposes
+    g = vi.temperature == 0
+    np.testing.assert_array_equal(got["cand_tok"][g], vi.cand_tok[g])
+    # a draw is flagged when u is within 1e-6 of an edge of its token's interval: with 32000
+    # tokens, most of them rarer than that, a few percent of the draws are
+    assert st["flagged"] <= 0.1 * st["nodes"] and st["near_tie"] <= 0.1 * st["nodes"]
+
+
+@pytest.mark.parametrize("V", [1, 3, 64, 4095, 4096, 4097, 8190, 12345, 16384, 16388, 31999, 32768])
+def test_vocabulary_sizes(V):
+    w = W.WORKLOADS["c2"].with_(B=2, V=V, kconfig=(2, 1) if V < 4 else (4, 2))
+    if V == 1:
+        w = w.with_(kconfig=(1, 1), variant=W.WITH_REPLACEMENT)
+    vi = W.gen_verify_inputs(w)
+    u = W.open_uniform(np.random.default_rng(V), (vi.B, vi.N))
+    got, rt, rm = run(vi, u)
+    compare(vi, got, rt, rm, f"V{V}")
+
+
+@pytest.mark.parametrize("T", [0.3, 1.0, 2.0])
+def test_temperatures_and_sampler_feeds_verifier(T):
+    w = W.WORKLOADS["c3"].with_(B=3, V=8192)
+    vi = W.gen_verify_inputs(w, temperature=[T, 0.0, T])
+    u = W.open_uniform(np.random.default_rng(3), (vi.B, vi.N))
+    ver = D.make_verify_call(vi)
+    draft = D.make_draft_call(vi, u, cand_tok=ver.tensors["cand_tok"])
+    M.mcsd_draft_sample(draft.args)
+    M.mcsd_verify_sample(ver.args)           # same stream: consumes the sampler's candidates
+    torch.cuda.synchronize()
+    rt, rm = O.draft_sample(vi.draft_logits, vi.tree.q_row, vi.tree.parent, u, vi.temperature, vi.variant, n_threads=8)
+    compare(vi, draft.results(), rt, rm, f"T{T}")
+    if (rm >= NEAR).all():
+        ref = O.verify(vi.target_logits, vi.draft_logits, vi.tree.q_row, vi.tree.parent, rt, vi.u_accept,
+                       vi.u_endpoint, vi.temperature, vi.variant, gamma_max=vi.tree.gamma, n_threads=8)
+        res = ver.results()
+        ok = ref.margin >= NEAR
+        np.testing.assert_array_equal(res["acc_child"][ok], ref.acc_child[ok])
+
+
+def test_duplicate_uniforms_and_extreme_uniforms():
+    w = W.WORKLOADS["c2"].with_(B=2, V=5000, kconfig=(6,))
+    for variant in (W.WITH_REPLACEMENT, W.WITHOUT_REPLACEMENT):
+        vi = W.gen_verify_inputs(w.with_(variant=variant))
+        u = np.full((vi.B, vi.N), 0.37, np.float32)
+        u[1] = [1e-7, 0.9999999, 0.5, 1e-7, 0.9999999, 0.5]
+        got, rt, rm = run(vi, u)
+        compare(vi, got, rt, rm, f"dup-{variant}")
+        if variant == W.WITH_REPLACEMENT:
+            assert len(set(got["cand_tok"][0].tolist())) == 1
+        else:
+            assert len(set(got["cand_tok"][0].tolist())) == vi.N
+
+
+def test_bad_row_map_is_flagged_not_dereferenced():
+    w = W.WORKLOADS["c2"].with_(B=2, V=4096)
+    vi = W.gen_verify_inputs(w)
+    u = W.open_uniform(np.random.default_rng(1), (vi.B, vi.N))
+    call = D.make_draft_call(vi, u)
+    q_row = vi.tree.q_row.astype(np.int32).copy()
+    q_row[0] = 10 ** 6                      # the root's draft row is out of range
+    call.tensors["q_row"].copy_(torch.from_numpy(q_row))
+    M.mcsd_draft_sample(call.args)
+    torch.cuda.synchronize()
+    got = call.results()
+    kids = vi.tree.children[0]
+    assert (got["cand_tok"][:, kids] == -1).all() and (got["flags"][:, kids] == FLAG_BAD_TREE).all()
+    rt, rm = O.draft_sample(vi.draft_logits, vi.tree.q_row, vi.tree.parent, u, vi.temperature, vi.variant)
+    others = [c for c in range(vi.N) if c not in kids]
+    ok = rm[:, others] >= NEAR
+    assert (got["cand_tok"][:, others][ok] == rt[:, others][ok]).all()
+
+
+def test_deterministic_and_other_stream():
+    w = W.WORKLOADS["c3"].with_(B=2)
+    vi = W.gen_verify_inputs(w)
+    u = W.open_uniform(np.random.default_rng(2), (vi.B, vi.N))
+    a, b = D.make_draft_call(vi, u), D.make_draft_call(vi, u)
+    M.mcsd_draft_sample(a.args)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        M.mcsd_draft_sample(b.args, stream=s)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(a.results()["cand_tok"], b.results()["cand_tok"])
+    np.testing.assert_array_equal(a.results()["flags"], b.results()["flags"])
