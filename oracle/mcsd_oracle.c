@@ -29,6 +29,10 @@
  *                              (input of Algorithm 1) or sequential draws without
  *                              replacement from q-bar of Eq. (1) (input of
  *                              Algorithm 2).
+ *   mcsd_oracle_tree_build     Sec. 3 / Sec. 4.3: the k-ary candidate tree of a
+ *                              k-configuration in generation order (Sec. 3.3).
+ *   mcsd_oracle_kv_commit      Sec. 3.3: keys and values of generated tokens are
+ *                              cached; the accepted path joins the prefix cache.
  *
  * Pins (tests/test_oracle_*.py): exact enumeration of the output distribution
  * against the theorems of Appendix A and B, the per-round accept / reject
@@ -37,7 +41,10 @@
  * brute-force per-path causal attention; for the draft sampler the measure of
  * the uniforms mapped to each candidate tuple against q and Eq. (1), numpy's
  * cumulative-sum search, and the end-to-end law (sampler + Algorithm 1 / 2
- * returns the target distribution).  No function here is unpinned.
+ * returns the target distribution); for the tree builder a queue-based
+ * construction and the level-size products; for the KV commit textbook
+ * attention over the committed cache against tree attention of the accepted
+ * node.  No function here is unpinned.
  *
  * Readings taken where the paper is silent (listed in full in the design notes
  * of this repository): self is attendable; the root is the last context token
@@ -497,4 +504,89 @@ int mcsd_oracle_draft_sample(int B, int N, int V, int P, int variant, const floa
         }
     }
     return status;
+}
+
+/* ------------------------------------------------ candidate tree and KV commit
+ *
+ * mcsd_oracle_tree_build: the k-ary candidate tree of a k-configuration
+ * (k_1, ..., k_gamma) (Sec. 3, verification as a walk over the k branches of a
+ * tree; Sec. 4.3 for the k-configuration), laid out in generation order as
+ * Sec. 3.3 packs the candidates into one sequence: level by level, every node
+ * of level i-1 (the root for i = 1) receives k_i children, the children of one
+ * parent are consecutive.  Node ids exclude the root.
+ *   parent[N] (-1: child of the root), depth[N] (1-based), q_row[1+N] (index of
+ *   the draft row of every tree row that has children, in row order; -1 for the
+ *   leaves).  Returns N, or -1 if a k_i is < 1 or N would exceed max_nodes.
+ */
+int mcsd_oracle_tree_build(const int32_t *kconfig, int gamma, int max_nodes, int32_t *parent,
+                           int32_t *depth, int32_t *q_row)
+{
+    int n = 0;
+    int level_begin = -1, level_count = 1; /* the root alone forms level 0 */
+    for (int lvl = 1; lvl <= gamma; ++lvl) {
+        int k = kconfig[lvl - 1];
+        if (k < 1) return -1;
+        int first = n;
+        for (int j = 0; j < level_count; ++j) {
+            int par = (lvl == 1) ? -1 : level_begin + j;
+            for (int c = 0; c < k; ++c) {
+                if (n >= max_nodes) return -1;
+                parent[n] = par;
+                depth[n] = lvl;
+                ++n;
+            }
+        }
+        level_begin = first;
+        level_count = n - first;
+    }
+    int next = 0;
+    for (int row = 0; row <= n; ++row) {
+        int has_child = 0;
+        for (int i = 0; i < n; ++i)
+            if (parent[i] == row - 1) has_child = 1;
+        q_row[row] = has_child ? next++ : -1;
+    }
+    return n;
+}
+
+/*
+ * mcsd_oracle_kv_commit: the keys and values of generated tokens stay unchanged
+ * and are cached for reuse (Sec. 3.3); after verification the accepted candidates
+ * are generated tokens, so their K/V rows move from the tree block to the tail of
+ * the prefix cache, in path order, and the prefix grows by the number accepted.
+ * The endpoint token (position n_accepted of out_tokens) is the next step's root.
+ *   k/v_prefix [n_layers][B][H_kv][L_stride][d] (in/out), k/v_tree [n_layers][B][H_kv][N][d],
+ *   elem_bytes per element; n_accepted [B], accepted_path [B][gamma_max],
+ *   out_tokens [B][gamma_max+1]; prefix_len [B] (in/out); next_root [B]; full [B]
+ *   (1 where prefix_len + n_accepted would exceed L_stride: nothing is copied and
+ *   prefix_len keeps its value).
+ */
+int mcsd_oracle_kv_commit(int n_layers, int B, int N, int H_kv, int d, int elem_bytes, long L_stride,
+                          int gamma_max, unsigned char *k_prefix, unsigned char *v_prefix,
+                          const unsigned char *k_tree, const unsigned char *v_tree,
+                          const int32_t *n_accepted, const int32_t *accepted_path,
+                          const int32_t *out_tokens, int32_t *prefix_len, int32_t *next_root,
+                          int32_t *full)
+{
+    size_t row = (size_t)d * (size_t)elem_bytes;
+    for (int b = 0; b < B; ++b) {
+        int n = n_accepted[b];
+        if (n < 0 || n > gamma_max) return -1;
+        next_root[b] = out_tokens[(size_t)b * (gamma_max + 1) + n];
+        long L = prefix_len[b];
+        full[b] = (L + n > L_stride) ? 1 : 0;
+        if (full[b]) continue;
+        for (int layer = 0; layer < n_layers; ++layer)
+            for (int g = 0; g < H_kv; ++g)
+                for (int j = 0; j < n; ++j) {
+                    int node = accepted_path[(size_t)b * gamma_max + j];
+                    if (node < 0 || node >= N) return -2;
+                    size_t src = ((((size_t)layer * B + b) * H_kv + g) * (size_t)N + node) * row;
+                    size_t dst = ((((size_t)layer * B + b) * H_kv + g) * (size_t)L_stride + (size_t)(L + j)) * row;
+                    memcpy(k_prefix + dst, k_tree + src, row);
+                    memcpy(v_prefix + dst, v_tree + src, row);
+                }
+        prefix_len[b] = (int32_t)(L + n);
+    }
+    return 0;
 }

@@ -51,6 +51,10 @@ def lib() -> ctypes.CDLL:
         L.mcsd_oracle_draft_parent.restype = c.c_int
         L.mcsd_oracle_draft_parent.argtypes = [c.c_int, c.c_int, c.c_int, c.c_double] + [c.c_void_p] * 4
         L.mcsd_oracle_draft_sample.restype = c.c_int
+        L.mcsd_oracle_tree_build.restype = c.c_int
+        L.mcsd_oracle_tree_build.argtypes = [c.c_void_p, c.c_int, c.c_int] + [c.c_void_p] * 3
+        L.mcsd_oracle_kv_commit.restype = c.c_int
+        L.mcsd_oracle_kv_commit.argtypes = [c.c_int] * 6 + [c.c_long, c.c_int] + [c.c_void_p] * 10
         L.mcsd_oracle_draft_sample.argtypes = [c.c_int] * 5 + [c.c_void_p] * 7 + [c.c_int]
         _lib = L
     return _lib
@@ -207,3 +211,40 @@ def draft_sample(draft_logits, q_row, parent, u_draw, temperature, variant: int,
     if rc != 0:
         raise ValueError(f"mcsd_oracle_draft_sample failed: {rc}")
     return cand, margin
+
+
+def tree_build(kconfig, max_nodes: int = 128):
+    """(parent int32 [N], depth int32 [N], q_row int32 [1+N]) of the k-ary candidate tree."""
+    kc = np.ascontiguousarray(kconfig, dtype=np.int32)
+    parent = np.empty(max_nodes, dtype=np.int32)
+    depth = np.empty(max_nodes, dtype=np.int32)
+    q_row = np.empty(max_nodes + 1, dtype=np.int32)
+    n = lib().mcsd_oracle_tree_build(_ptr(kc), int(kc.shape[0]), int(max_nodes), _ptr(parent), _ptr(depth), _ptr(q_row))
+    if n < 0:
+        raise ValueError("mcsd_oracle_tree_build: bad k-configuration or too many nodes")
+    return parent[:n].copy(), depth[:n].copy(), q_row[:n + 1].copy()
+
+
+def kv_commit(k_prefix, v_prefix, k_tree, v_tree, n_accepted, accepted_path, out_tokens, prefix_len):
+    """Arrays [n_layers][B][H_kv][L_stride | N][d] (any 2- or 4-byte element type).  Returns new
+    (k_prefix, v_prefix, prefix_len, next_root, full); the inputs are not modified."""
+    k_prefix, v_prefix = np.array(k_prefix, copy=True, order="C"), np.array(v_prefix, copy=True, order="C")
+    k_tree, v_tree = np.ascontiguousarray(k_tree), np.ascontiguousarray(v_tree)
+    n_layers, B, H_kv, L_stride, d = k_prefix.shape
+    N = k_tree.shape[3]
+    assert k_tree.shape == (n_layers, B, H_kv, N, d) and v_tree.shape == k_tree.shape and v_prefix.shape == k_prefix.shape
+    assert k_prefix.dtype == k_tree.dtype == v_prefix.dtype == v_tree.dtype
+    n_accepted = np.ascontiguousarray(n_accepted, dtype=np.int32).reshape(B)
+    accepted_path = np.ascontiguousarray(accepted_path, dtype=np.int32)
+    gamma_max = accepted_path.shape[1]
+    out_tokens = np.ascontiguousarray(out_tokens, dtype=np.int32).reshape(B, gamma_max + 1)
+    prefix_len = np.array(prefix_len, dtype=np.int32, copy=True).reshape(B)
+    next_root = np.empty(B, dtype=np.int32)
+    full = np.empty(B, dtype=np.int32)
+    rc = lib().mcsd_oracle_kv_commit(n_layers, B, N, H_kv, d, k_prefix.dtype.itemsize, L_stride, gamma_max,
+                                     _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tree), _ptr(v_tree), _ptr(n_accepted),
+                                     _ptr(accepted_path), _ptr(out_tokens), _ptr(prefix_len), _ptr(next_root),
+                                     _ptr(full))
+    if rc != 0:
+        raise ValueError(f"mcsd_oracle_kv_commit failed: {rc}")
+    return k_prefix, v_prefix, prefix_len, next_root, full
