@@ -40,9 +40,10 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5"])
-    ap.add_argument("--stage", default="verify_step", choices=["verify_step", "draft_sample"],
+    ap.add_argument("--stage", default="verify_step", choices=["verify_step", "draft_sample", "kv_commit"],
                     help="verify_step (default): the headline step; draft_sample: the draft-side candidate "
-                         "sampler that precedes it, measured on its own")
+                         "sampler that precedes it; kv_commit: tree build + commit of the accepted path that "
+                         "follows it (8 layers); each measured on its own")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--sets", type=int, default=0, help="rotating input copies (0 = enough for >= 1 GiB)")
@@ -153,6 +154,83 @@ def bench_draft_sample(args, torch, M, D, W):
     print(json.dumps(out))
 
 
+def bench_kv_commit(args, torch, M, D, W):
+    """mcsd_tree_build + mcsd_kv_commit for the workload's shape with 8 layers of cache: the accepted
+    paths come from one verification of the workload; prefix_len is reset on the device between steps."""
+    from oracle import mcsd_oracle as O
+    w = W.WORKLOADS[args.workload]
+    ai, vi = W.gen_attn_inputs(w), W.gen_verify_inputs(w)
+    n_layers, dev = 8, "cuda:0"
+    ref = O.verify(vi.target_logits, vi.draft_logits, vi.tree.q_row, vi.tree.parent, vi.cand_tok, vi.u_accept,
+                   vi.u_endpoint, vi.temperature, vi.variant, gamma_max=vi.tree.gamma, n_threads=16)
+    B, N, H_kv, d, Ls, G = ai.B, ai.N, ai.H_kv, ai.d, ai.k_prefix.shape[2], vi.tree.gamma
+    bf = torch.bfloat16
+    kp = torch.zeros((n_layers, B, H_kv, Ls, d), dtype=bf, device=dev)
+    vp = torch.zeros_like(kp)
+    kt = torch.randn((n_layers, B, H_kv, N, d), device=dev).to(bf)
+    vt = torch.randn((n_layers, B, H_kv, N, d), device=dev).to(bf)
+    L0 = torch.from_numpy(np.minimum(ai.prefix_len, Ls - G).astype(np.int32)).to(dev)
+    L = L0.clone()
+    i32 = dict(dtype=torch.int32, device=dev)
+    n_acc = torch.from_numpy(ref.n_accepted).to(dev)
+    path = torch.from_numpy(ref.accepted_path).to(dev)
+    otok = torch.from_numpy(ref.out_tokens).to(dev)
+    nxt, fl = torch.empty((B,), **i32), torch.empty((B,), **i32)
+    parent, depth = torch.empty((N,), **i32), torch.empty((N,), **i32)
+    q_row, pos = torch.empty((N + 1,), **i32), torch.empty((B, N), **i32)
+    cargs = M.commit_args(kp, vp, kt, vt, n_acc, path, otok, L, nxt, fl)
+    moved = int(ref.n_accepted.sum()) * H_kv * d * 2 * 2 * 2 * n_layers      # K and V, read + write
+
+    def run(n):
+        for _ in range(n):
+            L.copy_(L0)
+            M.mcsd_tree_build(w.kconfig, parent, depth, q_row, prefix_len=L, position_ids=pos)
+            M.mcsd_kv_commit(cargs)
+
+    run(args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    M.mcsd_kernel_timing(True)
+    run(args.steps)
+    torch.cuda.synchronize()
+    kt_ = M.mcsd_kernel_timing_read()
+    M.mcsd_kernel_timing(False)
+    kernels = {k: 1e3 * ms_ / n for k, (ms_, n) in kt_.items() if n}
+    out = {
+        "metric": "tree build + KV commit of the accepted paths (8 layers) per second", "value": 1e3 / ms,
+        "unit": "commits/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name} commit: {w.description}", "B": B, "layers": n_layers, "H_kv": H_kv, "d": d,
+                   "accepted_total": int(ref.n_accepted.sum()), "bytes_moved": moved,
+                   "note": "ms_per_step includes the device-side reset of prefix_len (one small copy)"},
+        "roofline": {"kernel": "kv_copy", "bound": "hbm", "achieved": moved / (kernels["kv_copy"] * 1e-6) / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": moved / (kernels["kv_copy"] * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                     "traffic": None, "algorithmic_bytes": moved, "avg_kernel_us": kernels["kv_copy"]},
+        "kernels_us": kernels,
+    }
+    if not args.no_cpu_baseline:
+        kph, vph = kp.view(torch.int16).cpu().numpy().view(np.uint16), vp.view(torch.int16).cpu().numpy().view(np.uint16)
+        kth, vth = kt.view(torch.int16).cpu().numpy().view(np.uint16), vt.view(torch.int16).cpu().numpy().view(np.uint16)
+        Lh = L0.cpu().numpy()
+        import ctypes
+        lib, P_ = O.lib(), O._ptr
+        nr, full = np.empty(B, np.int32), np.empty(B, np.int32)
+        t0 = time.perf_counter()
+        reps = 20
+        for _ in range(reps):
+            Lc = Lh.copy()
+            O.tree_build(w.kconfig)
+            lib.mcsd_oracle_kv_commit(n_layers, B, N, H_kv, d, 2, Ls, G, P_(kph), P_(vph), P_(kth), P_(vth),
+                                      P_(ref.n_accepted), P_(ref.accepted_path), P_(ref.out_tokens), P_(Lc), P_(nr), P_(full))
+        dt = (time.perf_counter() - t0) / reps
+        out["cpu_baseline"] = {"value": 1.0 / dt, "unit": "commits/s", "cores": 1, "kind": "oracle",
+                               "sample": f"the same commit, in place on host copies of the caches, {reps} repetitions"}
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -179,6 +257,9 @@ def main():
         return
     if args.stage == "draft_sample":
         bench_draft_sample(args, torch, M, D, W)
+        return
+    if args.stage == "kv_commit":
+        bench_kv_commit(args, torch, M, D, W)
         return
     w = W.WORKLOADS[args.workload]
     ai = W.gen_attn_inputs(w)

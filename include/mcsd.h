@@ -18,6 +18,11 @@
  *   mcsd_draft_sample   The step before: the k candidates of every parent drawn
  *                       from the draft distribution (Sec. 3.1; Eq. (1) when
  *                       sampling without replacement).
+ *   mcsd_tree_build     The candidate tree of a k-configuration (parent, depth,
+ *                       draft-row map, position ids) built on the device.
+ *   mcsd_kv_commit      The step after: the accepted path's keys and values join
+ *                       the prefix cache, prefix_len grows, the endpoint becomes
+ *                       the next root.
  *
  * Conventions
  *   - Plain C, plain-old-data structs; the first field of every struct is its
@@ -80,7 +85,8 @@ enum {
     MCSD_FLAG_ZERO_RESIDUAL = 16,     /* sum max(0, p - q) was not positive after a rejection */
     MCSD_FLAG_NONFINITE = 32,         /* a softmax normaliser was not finite and positive */
     MCSD_FLAG_BAD_TREE = 64,          /* a row with children has no valid q_row entry: handled as a leaf */
-    MCSD_FLAG_NEAR_TIE_DRAW = 128     /* mcsd_draft_sample: u_draw within near_tie_eps of an edge of the chosen CDF interval */
+    MCSD_FLAG_NEAR_TIE_DRAW = 128,    /* mcsd_draft_sample: u_draw within near_tie_eps of an edge of the chosen CDF interval */
+    MCSD_FLAG_CACHE_FULL = 256        /* mcsd_kv_commit: prefix_len + n_accepted > L_stride, nothing committed for this sequence */
 };
 
 const char *mcsd_last_error(void);
@@ -229,6 +235,63 @@ typedef struct {
 } mcsd_draft_bufs;
 
 int32_t mcsd_draft_sample(const mcsd_draft_desc *desc, const mcsd_draft_bufs *bufs, void *stream);
+
+/* ------------------------------------------------ candidate tree and KV commit
+ * The two bookkeeping steps around the verification, on the device so that a
+ * decode loop needs no host round trip (prefix_len lives in device memory).
+ *
+ * mcsd_tree_size / mcsd_tree_build: the k-ary candidate tree of a k-configuration
+ * (k_1 .. k_gamma; Sec. 3 and Sec. 4.3), in the generation order in which Sec. 3.3
+ * packs the candidates into one sequence: level by level, every node of level i-1
+ * (the root for i = 1) gets k_i consecutive children.
+ *   parent[N], depth[N] (1-based), q_row[1+N] (draft row of every tree row with
+ *   children, numbered in row order; -1 for leaves),
+ *   position_ids[B][N] = prefix_len[b] + depth[i] - 1 (each candidate keeps the
+ *   position it has in its own sequence; nullable, then prefix_len may be NULL too).
+ * kconfig is HOST memory (gamma <= 16 entries, each >= 1); N must not exceed
+ * MCSD_MAX_NODES (MCSD_E_TREE).  mcsd_tree_size only computes N and P on the host.
+ */
+int32_t mcsd_tree_size(const int32_t *kconfig_host, int32_t gamma, int32_t *n_nodes, int32_t *n_draft_rows);
+int32_t mcsd_tree_build(const int32_t *kconfig_host, int32_t gamma, int32_t B, const int32_t *prefix_len,
+                        int32_t *parent, int32_t *depth, int32_t *q_row, int32_t *position_ids, void *stream);
+
+/* mcsd_kv_commit: keys and values of generated tokens are cached for reuse (Sec. 3.3);
+ * after verification the accepted candidates are generated tokens.  For sequence b with
+ * n = n_accepted[b] and L = prefix_len[b], and every layer and KV head:
+ *   k_prefix[layer][b][g][L + j] = k_tree[layer][b][g][accepted_path[b][j]],  j = 0..n-1 (same for V)
+ *   prefix_len[b] = L + n;  next_root[b] = out_tokens[b][n]  (the endpoint, root of the next tree)
+ * If L + n > L_stride nothing is copied, prefix_len[b] is left alone and flags[b] gets
+ * MCSD_FLAG_CACHE_FULL (0 otherwise); path entries outside [0, N) end the copy there and set
+ * MCSD_FLAG_BAD_TREE.  n_accepted, accepted_path and out_tokens are the outputs of
+ * mcsd_verify_sample.  The caches of n_layers layers lie back to back.
+ */
+typedef struct {
+    uint32_t struct_size;
+    int32_t B;
+    int32_t N;              /* tree nodes per sequence, 1..MCSD_MAX_NODES */
+    int32_t H_kv;
+    int32_t d;              /* head dim; d * element size must be a multiple of 16 bytes */
+    int32_t dtype;          /* MCSD_DTYPE_* of the caches */
+    int32_t L_stride;       /* rows allocated per (sequence, KV head) in the prefix cache */
+    int32_t gamma_max;      /* row length of accepted_path; out_tokens rows have gamma_max+1 */
+    int32_t n_layers;       /* >= 1 */
+} mcsd_commit_desc;
+
+typedef struct {
+    uint32_t struct_size;
+    void *k_prefix;                 /* [n_layers][B][H_kv][L_stride][d] in/out */
+    void *v_prefix;                 /* [n_layers][B][H_kv][L_stride][d] in/out */
+    const void *k_tree;             /* [n_layers][B][H_kv][N][d] */
+    const void *v_tree;             /* [n_layers][B][H_kv][N][d] */
+    const int32_t *n_accepted;      /* [B] */
+    const int32_t *accepted_path;   /* [B][gamma_max] */
+    const int32_t *out_tokens;      /* [B][gamma_max+1] */
+    int32_t *prefix_len;            /* [B] in/out */
+    int32_t *next_root;             /* [B] out */
+    uint32_t *flags;                /* [B] out */
+} mcsd_commit_bufs;
+
+int32_t mcsd_kv_commit(const mcsd_commit_desc *desc, const mcsd_commit_bufs *bufs, void *stream);
 
 /* ------------------------------------------------------------ profiling aid
  * Not part of the verification step.  mcsd_kernel_timing(1) makes every kernel

@@ -26,7 +26,7 @@ FLAG_ZERO_DRAFT_PROB, FLAG_ZERO_RESIDUAL, FLAG_NONFINITE, FLAG_BAD_TREE = 8, 16,
 
 EXPORTS = ["mcsd_last_error", "mcsd_version", "mcsd_tree_validate", "mcsd_attn_workspace_bytes",
            "mcsd_tree_attn", "mcsd_verify_workspace_bytes", "mcsd_verify_sample", "mcsd_verify_step",
-           "mcsd_draft_sample",
+           "mcsd_draft_sample", "mcsd_tree_size", "mcsd_tree_build", "mcsd_kv_commit",
            "mcsd_kernel_timing", "mcsd_kernel_count", "mcsd_kernel_name", "mcsd_kernel_timing_read"]
 
 
@@ -72,6 +72,18 @@ class DraftBufs(C.Structure):
         "draft_logits", "q_row", "parent", "u_draw", "temperature", "cand_tok", "flags")]
 
 
+class CommitDesc(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("B", C.c_int32), ("N", C.c_int32), ("H_kv", C.c_int32),
+                ("d", C.c_int32), ("dtype", C.c_int32), ("L_stride", C.c_int32), ("gamma_max", C.c_int32),
+                ("n_layers", C.c_int32)]
+
+
+class CommitBufs(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32)] + [(n, C.c_void_p) for n in (
+        "k_prefix", "v_prefix", "k_tree", "v_tree", "n_accepted", "accepted_path", "out_tokens",
+        "prefix_len", "next_root", "flags")]
+
+
 _lib: Optional[C.CDLL] = None
 
 
@@ -101,6 +113,12 @@ def lib() -> C.CDLL:
         L.mcsd_verify_step.restype = C.c_int32
         L.mcsd_draft_sample.argtypes = [C.POINTER(DraftDesc), C.POINTER(DraftBufs), C.c_void_p]
         L.mcsd_draft_sample.restype = C.c_int32
+        L.mcsd_tree_size.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        L.mcsd_tree_size.restype = C.c_int32
+        L.mcsd_tree_build.argtypes = [C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 5 + [C.c_void_p]
+        L.mcsd_tree_build.restype = C.c_int32
+        L.mcsd_kv_commit.argtypes = [C.POINTER(CommitDesc), C.POINTER(CommitBufs), C.c_void_p]
+        L.mcsd_kv_commit.restype = C.c_int32
         L.mcsd_kernel_timing.argtypes = [C.c_int32]
         L.mcsd_kernel_timing.restype = C.c_int32
         L.mcsd_kernel_count.restype = C.c_int32
@@ -287,6 +305,83 @@ def draft_args(draft_logits, q_row, parent, u_draw, temperature, cand_tok, flags
 
 def mcsd_draft_sample(args: DraftArgs, stream=None) -> None:
     _check(lib().mcsd_draft_sample(C.byref(args.desc), C.byref(args.bufs), _stream(stream)))
+
+
+# ---------------------------------------------------- candidate tree and KV commit
+def mcsd_tree_size(kconfig) -> tuple:
+    """(N, P) of the k-ary candidate tree; host only."""
+    import numpy as np
+    kc = np.ascontiguousarray(kconfig, dtype=np.int32)
+    n, pr = C.c_int32(0), C.c_int32(0)
+    _check(lib().mcsd_tree_size(kc.ctypes.data_as(C.c_void_p), kc.shape[0], C.byref(n), C.byref(pr)))
+    return int(n.value), int(pr.value)
+
+
+def mcsd_tree_build(kconfig, parent, depth, q_row, prefix_len=None, position_ids=None, stream=None) -> None:
+    """kconfig: host sequence; parent/depth int32 [N], q_row int32 [1+N] device tensors;
+    position_ids int32 [B][N] (optional, needs prefix_len int32 [B])."""
+    import numpy as np
+    kc = np.ascontiguousarray(kconfig, dtype=np.int32)
+    N, _ = mcsd_tree_size(kc)
+    i32 = torch.int32
+    if tuple(parent.shape) != (N,) or tuple(depth.shape) != (N,) or tuple(q_row.shape) != (N + 1,):
+        raise ValueError("parent / depth must be [N], q_row [1+N]")
+    B = 1
+    if position_ids is not None:
+        B = position_ids.shape[0]
+        if tuple(position_ids.shape) != (B, N) or prefix_len is None or tuple(prefix_len.shape) != (B,):
+            raise ValueError("position_ids must be [B][N] with prefix_len [B]")
+    _check(lib().mcsd_tree_build(kc.ctypes.data_as(C.c_void_p), kc.shape[0], B, _ptr(prefix_len, i32, "prefix_len"),
+                                 _ptr(parent, i32, "parent"), _ptr(depth, i32, "depth"), _ptr(q_row, i32, "q_row"),
+                                 _ptr(position_ids, i32, "position_ids"), _stream(stream)))
+
+
+@dataclass
+class CommitArgs:
+    desc: CommitDesc
+    bufs: CommitBufs
+    keep: tuple
+
+
+def commit_args(k_prefix, v_prefix, k_tree, v_tree, n_accepted, accepted_path, out_tokens, prefix_len,
+                next_root, flags) -> CommitArgs:
+    """k/v_prefix [n_layers][B][H_kv][L_stride][d] (or 4-D for one layer), k/v_tree [...][N][d];
+    n_accepted [B], accepted_path [B][gamma_max], out_tokens [B][gamma_max+1], prefix_len [B] (in/out),
+    next_root [B], flags [B]."""
+    if k_prefix.dim() == 4:
+        n_layers, (B, H_kv, L_stride, d) = 1, k_prefix.shape
+    else:
+        n_layers, B, H_kv, L_stride, d = k_prefix.shape
+    N = k_tree.shape[-2]
+    lead = () if k_prefix.dim() == 4 else (n_layers,)
+    if tuple(v_prefix.shape) != tuple(k_prefix.shape) or tuple(k_tree.shape) != lead + (B, H_kv, N, d) or \
+            tuple(v_tree.shape) != tuple(k_tree.shape):
+        raise ValueError("cache shape mismatch")
+    gamma_max = accepted_path.shape[1]
+    for t, shp in [(n_accepted, (B,)), (accepted_path, (B, gamma_max)), (out_tokens, (B, gamma_max + 1)),
+                   (prefix_len, (B,)), (next_root, (B,)), (flags, (B,))]:
+        if tuple(t.shape) != shp:
+            raise ValueError(f"shape mismatch: got {tuple(t.shape)}, expected {shp}")
+    if k_prefix.dtype == torch.float32:
+        dt = DTYPE_FP32
+    elif k_prefix.dtype == torch.bfloat16:
+        dt = DTYPE_BF16
+    else:
+        raise ValueError(f"unsupported dtype {k_prefix.dtype}")
+    i32 = torch.int32
+    desc = CommitDesc(C.sizeof(CommitDesc), B, N, H_kv, d, dt, L_stride, gamma_max, n_layers)
+    bufs = CommitBufs(C.sizeof(CommitBufs), _ptr(k_prefix, k_prefix.dtype, "k_prefix"),
+                      _ptr(v_prefix, k_prefix.dtype, "v_prefix"), _ptr(k_tree, k_prefix.dtype, "k_tree"),
+                      _ptr(v_tree, k_prefix.dtype, "v_tree"), _ptr(n_accepted, i32, "n_accepted"),
+                      _ptr(accepted_path, i32, "accepted_path"), _ptr(out_tokens, i32, "out_tokens"),
+                      _ptr(prefix_len, i32, "prefix_len"), _ptr(next_root, i32, "next_root"),
+                      _ptr(flags, i32, "flags"))
+    return CommitArgs(desc, bufs, (k_prefix, v_prefix, k_tree, v_tree, n_accepted, accepted_path, out_tokens,
+                                   prefix_len, next_root, flags))
+
+
+def mcsd_kv_commit(args: CommitArgs, stream=None) -> None:
+    _check(lib().mcsd_kv_commit(C.byref(args.desc), C.byref(args.bufs), _stream(stream)))
 
 
 # ------------------------------------------------------------------- profiling aid

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmcsd.so")
-SOURCES = ["api.hip", "tree_attn.hip", "verify_sample.hip", "draft_sample.hip"]
+SOURCES = ["api.hip", "tree_attn.hip", "verify_sample.hip", "draft_sample.hip", "tree_commit.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

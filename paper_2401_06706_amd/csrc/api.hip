@@ -1,5 +1,5 @@
 // C ABI of libmcsd: argument validation, error reporting, optional per-kernel
-// event timing.  All compute happens in tree_attn.hip, verify_sample.hip and draft_sample.hip.
+// event timing.  All compute happens in tree_attn.hip, verify_sample.hip, draft_sample.hip and tree_commit.hip.
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
@@ -33,7 +33,7 @@ hipEvent_t g_open[K_COUNT];
 double g_total_ms[K_COUNT];
 long long g_count[K_COUNT];
 const char *const g_names[K_COUNT] = {"tree_attn_mfma", "tree_attn_generic", "tree_attn_combine",
-                                      "verify_rows", "walk", "draft_rows"};
+                                      "verify_rows", "walk", "draft_rows", "tree_build", "kv_copy", "kv_finish"};
 }  // namespace
 
 void timing_begin(int id, hipStream_t stream)
@@ -223,6 +223,56 @@ int32_t mcsd_draft_sample(const mcsd_draft_desc *desc, const mcsd_draft_bufs *bu
     int32_t rc = check_draft(desc, bufs);
     if (rc != MCSD_OK) return rc;
     return launch_draft_sample(*desc, *bufs, (hipStream_t)stream);
+}
+
+int32_t mcsd_tree_size(const int32_t *kconfig, int32_t gamma, int32_t *n_nodes, int32_t *n_draft_rows)
+{
+    if (!kconfig) { set_error("tree: kconfig is NULL"); return MCSD_E_NULL; }
+    if (gamma < 1 || gamma > MAX_GAMMA) { set_error("tree: gamma %d outside 1..%d", gamma, MAX_GAMMA); return MCSD_E_SHAPE; }
+    long level = 1, n = 0, internal = 1;
+    for (int i = 0; i < gamma; ++i) {
+        if (kconfig[i] < 1) { set_error("tree: k_%d = %d < 1", i + 1, kconfig[i]); return MCSD_E_SHAPE; }
+        level *= kconfig[i];
+        n += level;
+        if (n > MCSD_MAX_NODES) { set_error("tree: more than %d nodes", MCSD_MAX_NODES); return MCSD_E_TREE; }
+        if (i + 1 < gamma) internal += level;
+    }
+    if (n_nodes) *n_nodes = (int32_t)n;
+    if (n_draft_rows) *n_draft_rows = (int32_t)internal;
+    return MCSD_OK;
+}
+
+int32_t mcsd_tree_build(const int32_t *kconfig, int32_t gamma, int32_t B, const int32_t *prefix_len, int32_t *parent,
+                        int32_t *depth, int32_t *q_row, int32_t *position_ids, void *stream)
+{
+    int32_t n = 0;
+    int32_t rc = mcsd_tree_size(kconfig, gamma, &n, nullptr);
+    if (rc != MCSD_OK) return rc;
+    if (!parent || !depth || !q_row) { set_error("tree: NULL output"); return MCSD_E_NULL; }
+    if (position_ids && !prefix_len) { set_error("tree: position_ids needs prefix_len"); return MCSD_E_NULL; }
+    if (position_ids && (B < 1 || B > 65535)) { set_error("tree: B %d outside 1..65535", B); return MCSD_E_SHAPE; }
+    return launch_tree_build(kconfig, gamma, n, B, prefix_len, parent, depth, q_row, position_ids, (hipStream_t)stream);
+}
+
+int32_t mcsd_kv_commit(const mcsd_commit_desc *d, const mcsd_commit_bufs *b, void *stream)
+{
+    if (!d) { set_error("commit desc is NULL"); return MCSD_E_NULL; }
+    if (d->struct_size != sizeof(mcsd_commit_desc)) { set_error("commit desc struct_size %u != %zu", d->struct_size, sizeof(mcsd_commit_desc)); return MCSD_E_SHAPE; }
+    if (d->B < 1 || d->H_kv < 1 || d->d < 1 || d->L_stride < 1 || d->gamma_max < 1 || d->n_layers < 1) { set_error("commit: non-positive size"); return MCSD_E_SHAPE; }
+    if (d->N < 1 || d->N > MCSD_MAX_NODES) { set_error("commit: N %d outside 1..%d", d->N, MCSD_MAX_NODES); return MCSD_E_TREE; }
+    if (d->dtype != MCSD_DTYPE_FP32 && d->dtype != MCSD_DTYPE_BF16) { set_error("commit: unknown dtype %d", d->dtype); return MCSD_E_UNSUPPORTED; }
+    const int esize = d->dtype == MCSD_DTYPE_FP32 ? 4 : 2;
+    if ((d->d * esize) % 16 != 0) { set_error("commit: d * element size must be a multiple of 16 bytes"); return MCSD_E_SHAPE; }
+    if (d->B > 65535 || d->gamma_max > 65535 || d->n_layers > 65535) { set_error("commit: grid too large"); return MCSD_E_UNSUPPORTED; }
+    if (!b) { set_error("commit bufs is NULL"); return MCSD_E_NULL; }
+    if (b->struct_size != sizeof(mcsd_commit_bufs)) { set_error("commit bufs struct_size %u != %zu", b->struct_size, sizeof(mcsd_commit_bufs)); return MCSD_E_SHAPE; }
+    if (!b->k_prefix || !b->v_prefix || !b->k_tree || !b->v_tree || !b->n_accepted || !b->accepted_path ||
+        !b->out_tokens || !b->prefix_len || !b->next_root || !b->flags) { set_error("commit: NULL buffer"); return MCSD_E_NULL; }
+    if (((uintptr_t)b->k_prefix | (uintptr_t)b->v_prefix | (uintptr_t)b->k_tree | (uintptr_t)b->v_tree) & 15u) {
+        set_error("commit: caches must be 16-byte aligned");
+        return MCSD_E_SHAPE;
+    }
+    return launch_kv_commit(*d, *b, (hipStream_t)stream);
 }
 
 int32_t mcsd_verify_step(const mcsd_attn_desc *ad, const mcsd_attn_bufs *ab, const mcsd_verify_desc *vd,

@@ -9,7 +9,7 @@
 namespace mcsd {
 
 // Kernel ids for the optional per-kernel event timing.
-enum KernelId { K_ATTN_MFMA = 0, K_ATTN_GENERIC = 1, K_ATTN_COMBINE = 2, K_VERIFY_ROWS = 3, K_WALK = 4, K_DRAFT_ROWS = 5, K_COUNT = 6 };
+enum KernelId { K_ATTN_MFMA = 0, K_ATTN_GENERIC = 1, K_ATTN_COMBINE = 2, K_VERIFY_ROWS = 3, K_WALK = 4, K_DRAFT_ROWS = 5, K_TREE_BUILD = 6, K_KV_COPY = 7, K_KV_FINISH = 8, K_COUNT = 9 };
 
 void set_error(const char *fmt, ...);
 
@@ -41,5 +41,11 @@ int32_t launch_verify(const mcsd_verify_desc &d, const mcsd_verify_bufs &b, hipS
 
 // ---- draft-side candidates ------------------------------------------------
 int32_t launch_draft_sample(const mcsd_draft_desc &d, const mcsd_draft_bufs &b, hipStream_t stream);
+
+// ---- candidate tree and KV commit -----------------------------------------
+constexpr int MAX_GAMMA = 16;
+int32_t launch_tree_build(const int32_t *kconfig, int gamma, int n_nodes, int B, const int32_t *prefix_len,
+                          int32_t *parent, int32_t *depth, int32_t *q_row, int32_t *position_ids, hipStream_t stream);
+int32_t launch_kv_commit(const mcsd_commit_desc &d, const mcsd_commit_bufs &b, hipStream_t stream);
 
 }  // namespace mcsd

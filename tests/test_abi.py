@@ -45,7 +45,10 @@ def test_struct_layout_matches_header(tmp_path):
               "mcsd_verify_bufs": (M.VerifyBufs, ["target_logits", "temperature", "acc_child", "ratio",
                                                   "flags", "residual_out", "workspace_bytes"]),
               "mcsd_draft_desc": (M.DraftDesc, ["B", "V", "P", "variant", "near_tie_eps"]),
-              "mcsd_draft_bufs": (M.DraftBufs, ["draft_logits", "q_row", "u_draw", "temperature", "cand_tok", "flags"])}
+              "mcsd_draft_bufs": (M.DraftBufs, ["draft_logits", "q_row", "u_draw", "temperature", "cand_tok", "flags"]),
+              "mcsd_commit_desc": (M.CommitDesc, ["B", "H_kv", "dtype", "L_stride", "gamma_max", "n_layers"]),
+              "mcsd_commit_bufs": (M.CommitBufs, ["k_prefix", "v_tree", "n_accepted", "out_tokens", "prefix_len",
+                                                  "next_root", "flags"])}
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "mcsd.h"', "int main(void){"]
     for cname, (_, fs) in fields.items():
         lines.append(f'printf("{cname} %zu\\n", sizeof({cname}));')
@@ -181,3 +184,43 @@ def test_draft_descriptor_errors(lib):
     assert lib.mcsd_draft_sample(C.byref(d), C.byref(M.DraftBufs(5, *ptrs)), None) == -2
     p2 = list(ptrs); p2[0] = 4096 + 4
     assert lib.mcsd_draft_sample(C.byref(d), C.byref(M.DraftBufs(C.sizeof(M.DraftBufs), *p2)), None) == -2
+
+
+def test_tree_size_and_build_errors(lib):
+    assert M.mcsd_tree_size((4, 2, 2, 1, 1)) == (60, 45)
+    assert M.mcsd_tree_size((2, 2)) == (6, 3)
+    assert M.mcsd_tree_size((128,)) == (128, 1)
+    for bad, code in [((4, 4, 4, 2), -4), ((2, 0), -2), ((), -2), ((1,) * 17, -2)]:
+        with pytest.raises(M.McsdError) as e:
+            M.mcsd_tree_size(bad)
+        assert e.value.code == code
+    kc = np.array([2, 2], np.int32)
+    kp = kc.ctypes.data_as(C.c_void_p)
+    assert lib.mcsd_tree_size(None, 2, None, None) == -1
+    assert lib.mcsd_tree_build(kp, 2, 1, None, None, 4096, 4096, None, None) == -1      # NULL output
+    assert lib.mcsd_tree_build(kp, 2, 1, None, 4096, 4096, 4096, 4096, None) == -1      # position ids without prefix_len
+    assert lib.mcsd_tree_build(kp, 2, 0, 4096, 4096, 4096, 4096, 4096, None) == -2      # B = 0 with position ids
+
+
+def test_commit_descriptor_errors(lib):
+    def desc(**kw):
+        a = dict(B=2, N=6, H_kv=2, d=128, dtype=M.DTYPE_BF16, L_stride=64, gamma_max=2, n_layers=1)
+        a.update(kw)
+        return M.CommitDesc(C.sizeof(M.CommitDesc), a["B"], a["N"], a["H_kv"], a["d"], a["dtype"], a["L_stride"],
+                            a["gamma_max"], a["n_layers"])
+    ptrs = [4096] * 10
+    bufs = M.CommitBufs(C.sizeof(M.CommitBufs), *ptrs)
+    cases = [(dict(N=0), -4), (dict(N=129), -4), (dict(B=0), -2), (dict(H_kv=0), -2), (dict(d=4), -2),
+             (dict(dtype=5), -3), (dict(L_stride=0), -2), (dict(gamma_max=0), -2), (dict(n_layers=0), -2),
+             (dict(B=70000), -3)]
+    for kw, code in cases:
+        d = desc(**kw)
+        assert lib.mcsd_kv_commit(C.byref(d), C.byref(bufs), None) == code, kw
+    d = desc()
+    assert lib.mcsd_kv_commit(None, C.byref(bufs), None) == -1
+    assert lib.mcsd_kv_commit(C.byref(d), None, None) == -1
+    for i in range(10):
+        p2 = list(ptrs); p2[i] = None
+        assert lib.mcsd_kv_commit(C.byref(d), C.byref(M.CommitBufs(C.sizeof(M.CommitBufs), *p2)), None) == -1, i
+    p2 = list(ptrs); p2[2] = 4096 + 8
+    assert lib.mcsd_kv_commit(C.byref(d), C.byref(M.CommitBufs(C.sizeof(M.CommitBufs), *p2)), None) == -2
