@@ -20,6 +20,9 @@
  *                              and Algorithm 2 (without replacement, q-bar of
  *                              Eq. (1)); the k=1 case is the speculative
  *                              sampling rule of Sec. 2.
+ *                              Variant 2 is multi-candidate naive sampling, the
+ *                              comparison rule of the ablation (Sec. 4.5, footnote;
+ *                              naive sampling of Sec. 2 for k = 1).
  *   mcsd_oracle_verify         Sec. 3, the paragraph describing verification as
  *                              a walk from the root of the candidate tree to a
  *                              leaf, with the endpoint rules of Sec. 2.
@@ -67,6 +70,7 @@
 
 #define VARIANT_WITH_REPLACEMENT 0
 #define VARIANT_WITHOUT_REPLACEMENT 1
+#define VARIANT_NAIVE 2 /* multi-candidate naive sampling (Sec. 4.5, footnote; Sec. 2 for k = 1) */
 
 static double load_elem(const void *base, int dtype, size_t idx)
 {
@@ -265,6 +269,24 @@ int mcsd_oracle_verify_parent(int V, int k, int variant, double T, const float *
     double *p = (double *)malloc(sizeof(double) * (size_t)V);
     double *q = (double *)malloc(sizeof(double) * (size_t)V);
     softmax_T(z_p, V, T, p);
+
+    if (variant == VARIANT_NAIVE) {
+        /* multi-candidate naive sampling: a token x is drawn from p first (with the endpoint
+         * uniform); a candidate is accepted iff it equals x (the first such), otherwise the
+         * candidates are rejected and x is returned.  q and the accept uniforms are not used. */
+        double mg;
+        int x = inverse_cdf(p, V, u_end, &mg);
+        *margin = mg;
+        for (int i = 0; i < k; ++i) {
+            if (tok[i] < 0 || tok[i] >= V) { free(p); free(q); return -3; }
+            if (*accepted < 0 && tok[i] == x) *accepted = i;
+        }
+        if (*accepted < 0) *endpoint = x;
+        if (residual) memcpy(residual, p, sizeof(double) * (size_t)V);
+        free(p);
+        free(q);
+        return 0;
+    }
     if (k > 0) softmax_T(z_q, V, T, q);
 
     for (int i = 0; i < k; ++i) {

@@ -448,3 +448,85 @@ def test_walk_outputs_are_consistent():
             prev = int(path[i])
         assert 0 <= res.out_tokens[b, n] < w.V
         assert res.endpoint[b, 1 + prev] == res.out_tokens[b, n]
+
+
+# ----------------------------------------------------------------- naive sampling (ablation rule)
+NAIVE = 2
+
+
+def test_naive_sampling_always_returns_the_token_drawn_from_p():
+    # whatever the candidates, the emitted token is the inverse-CDF draw from p at u_end
+    rng = np.random.default_rng(41)
+    V, k = 9, 3
+    for _ in range(200):
+        p, q = rng.dirichlet(np.ones(V)), rng.dirichlet(np.ones(V))
+        zp, zq = np.log(p).astype(np.float32), np.log(q).astype(np.float32)
+        tok = rng.integers(0, V, k)
+        u_end = float(rng.random())
+        res = O.verify_parent(zp, zq, tok, rng.random(k), u_end, NAIVE)
+        p64 = np.exp(zp.astype(np.float64)); p64 /= p64.sum()
+        x = int(np.searchsorted(np.cumsum(p64), u_end, side="right"))
+        if res.margin > 1e-9:
+            emitted = tok[res.accepted] if res.accepted >= 0 else res.endpoint
+            assert emitted == x
+            assert (res.accepted >= 0) == (x in tok.tolist())
+            if res.accepted >= 0:
+                assert res.accepted == tok.tolist().index(x) and res.endpoint == -1
+
+
+def test_naive_acceptance_rate_matches_appendix_c_formula():
+    # i.i.d. candidates from q: P(all k rejected, x returned) = p(x) (1 - q(x))^k  (Appendix C)
+    rng = np.random.default_rng(42)
+    V, k, G = 4, 2, 4000
+    p, q = rng.dirichlet(np.ones(V)), rng.dirichlet(np.ones(V))
+    zp, zq = np.log(p).astype(np.float32), np.log(q).astype(np.float32)
+    p64 = np.exp(zp.astype(np.float64)); p64 /= p64.sum()
+    q64 = np.exp(zq.astype(np.float64)); q64 /= q64.sum()
+    grid = (np.arange(G) + 0.5) / G
+    reject_mass = np.zeros(V)
+    for tok in itertools.product(range(V), repeat=k):
+        w = np.prod(q64[list(tok)])
+        hits = np.zeros(V)
+        for u in grid:
+            res = O.verify_parent(zp, zq, tok, [0.5] * k, float(u), NAIVE)
+            if res.accepted < 0:
+                hits[res.endpoint] += 1
+        reject_mass += w * hits / G
+    np.testing.assert_allclose(reject_mass, p64 * (1 - q64) ** k, atol=3.0 / G)
+
+
+def test_naive_equals_without_replacement_rule_at_temperature_zero():
+    # Sec. 4.5: with argmax sampling, sampling without replacement and naive sampling coincide
+    rng = np.random.default_rng(43)
+    V, k = 50, 4
+    for _ in range(100):
+        zp = rng.standard_normal(V).astype(np.float32)
+        zq = (zp + rng.standard_normal(V)).astype(np.float32)
+        tok = np.argsort(-zq, kind="stable")[:k]
+        a = O.verify_parent(zp, zq, tok, rng.random(k), float(rng.random()), NAIVE, T=0.0)
+        b = O.verify_parent(zp, zq, tok, rng.random(k), float(rng.random()), 1, T=0.0)
+        assert (a.accepted, a.endpoint) == (b.accepted, b.endpoint)
+
+
+def test_speculative_acceptance_is_at_least_naive_acceptance():
+    # Appendix C, through the oracle's own outputs: alpha_k (Alg. 1) >= 1 - sum_x p(x) (1 - q(x))^k
+    rng = np.random.default_rng(44)
+    V, k = 5, 3
+    for _ in range(20):
+        p, q = rng.dirichlet(np.ones(V)), rng.dirichlet(np.ones(V))
+        zp, zq = np.log(p).astype(np.float32), np.log(q).astype(np.float32)
+        p64 = np.exp(zp.astype(np.float64)); p64 /= p64.sum()
+        q64 = np.exp(zq.astype(np.float64)); q64 /= q64.sum()
+        alpha = 0.0
+        for tok in itertools.product(range(V), repeat=k):
+            w = np.prod(q64[list(tok)])
+            # probability of accepting somewhere = 1 - prod (1 - ratio_i) along the all-reject branch
+            res = O.verify_parent(zp, zq, tok, [1.0 - 1e-7] * k, 0.5, 0)      # rejects unless ratio == 1
+            rej = 1.0
+            for r in res.ratio:
+                if np.isnan(r):
+                    break
+                rej *= (1.0 - r)
+            alpha += w * (1.0 - rej)
+        naive = 1.0 - np.sum(p64 * (1 - q64) ** k)
+        assert alpha >= naive - 1e-9
