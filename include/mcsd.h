@@ -74,7 +74,8 @@ enum {
 };
 
 enum { MCSD_DTYPE_FP32 = 0, MCSD_DTYPE_BF16 = 1 };
-enum { MCSD_WITH_REPLACEMENT = 0, MCSD_WITHOUT_REPLACEMENT = 1 };
+enum { MCSD_WITH_REPLACEMENT = 0, MCSD_WITHOUT_REPLACEMENT = 1,
+       MCSD_NAIVE = 2 /* verification only: multi-candidate naive sampling, the ablation's comparison rule */ };
 
 /* bits of mcsd_verify_bufs.flags[b][row] */
 enum {
@@ -146,6 +147,10 @@ int32_t mcsd_tree_attn(const mcsd_attn_desc *desc, const mcsd_attn_bufs *bufs, v
  *       order, smallest x whose cumulative probability exceeds u_endpoint[b][r])
  *   walk: r = 0; while a child c of r was accepted: emit cand_tok[c], r = 1 + c;
  *       then emit the endpoint of r.
+ *   variant MCSD_NAIVE (Sec. 4.5, footnote; naive sampling of Sec. 2 for one candidate): a
+ *       token x is drawn from p_r by inverse CDF at u_endpoint[b][r]; the first child whose
+ *       token equals x is accepted, otherwise x is the endpoint; draft logits and u_accept
+ *       are not read, ratio is NaN.
  *   T == 0 (argmax sampling, Sec. 4.1/4.4): accept the first child whose token is
  *       argmax target_logits[b][r] (lowest id on ties), otherwise that argmax is
  *       the endpoint; draft logits and uniforms are not read.
@@ -160,7 +165,7 @@ typedef struct {
     int32_t N;              /* tree nodes per sequence, 1..MCSD_MAX_NODES */
     int32_t V;              /* vocabulary, 1..MCSD_MAX_VOCAB */
     int32_t P;              /* rows of draft_logits per sequence (rows of the tree that have children) */
-    int32_t variant;        /* MCSD_WITH_REPLACEMENT | MCSD_WITHOUT_REPLACEMENT */
+    int32_t variant;        /* MCSD_WITH_REPLACEMENT | MCSD_WITHOUT_REPLACEMENT | MCSD_NAIVE */
     int32_t gamma_max;      /* depth bound: row length of accepted_path; out_tokens rows have gamma_max+1 */
     float near_tie_eps;     /* threshold of the MCSD_FLAG_NEAR_TIE_* bits, e.g. 1e-6 */
 } mcsd_verify_desc;

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmcsd.so")
 
 DTYPE_FP32, DTYPE_BF16 = 0, 1
-WITH_REPLACEMENT, WITHOUT_REPLACEMENT = 0, 1
+WITH_REPLACEMENT, WITHOUT_REPLACEMENT, NAIVE = 0, 1, 2
 MAX_NODES, MAX_VOCAB = 128, 32768
 
 FLAG_NEAR_TIE_ACCEPT, FLAG_NEAR_TIE_ENDPOINT, FLAG_BAD_TOKEN = 1, 2, 4

@@ -153,7 +153,7 @@ static int32_t check_verify(const mcsd_verify_desc *d, const mcsd_verify_bufs *b
     if (d->P > 1 + d->N) { set_error("verify: P %d > 1+N", d->P); return MCSD_E_SHAPE; }
     if (d->B > 65535) { set_error("verify: B %d > 65535", d->B); return MCSD_E_UNSUPPORTED; }
     if (d->V > MCSD_MAX_VOCAB) { set_error("verify: V %d > %d", d->V, MCSD_MAX_VOCAB); return MCSD_E_UNSUPPORTED; }
-    if (d->variant != MCSD_WITH_REPLACEMENT && d->variant != MCSD_WITHOUT_REPLACEMENT) { set_error("verify: unknown variant %d", d->variant); return MCSD_E_UNSUPPORTED; }
+    if (d->variant != MCSD_WITH_REPLACEMENT && d->variant != MCSD_WITHOUT_REPLACEMENT && d->variant != MCSD_NAIVE) { set_error("verify: unknown variant %d", d->variant); return MCSD_E_UNSUPPORTED; }
     if (!(d->near_tie_eps >= 0.f)) { set_error("verify: near_tie_eps must be >= 0"); return MCSD_E_SHAPE; }
     if (!b) return MCSD_OK;
     if (b->struct_size != sizeof(mcsd_verify_bufs)) { set_error("verify bufs struct_size %u != %zu", b->struct_size, sizeof(mcsd_verify_bufs)); return MCSD_E_SHAPE; }

@@ -127,7 +127,8 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     float4 a[ITEMS];
     load_row<ITEMS, VT, ALIGNED>(zp_row, V, a);
     const int qr = p.q_row[row];
-    const bool have_q = (qr >= 0 && qr < p.P) && (T != 0.f);
+    const bool naive = (p.variant == MCSD_NAIVE);      // the draft row is not needed: candidates are only compared
+    const bool have_q = (qr >= 0 && qr < p.P) && (T != 0.f) && !naive;
     const float *zq_row = have_q ? p.draft_logits + ((size_t)b * p.P + qr) * (size_t)V : zp_row;
     float4 eq[ITEMS];
     if (have_q) {
@@ -209,14 +210,14 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     float mp = row_max<ITEMS>(a), mq = row_max<ITEMS>(eq);
     block_max2<NWAVES>(mp, mq, s_redf, s_redf2);
     double A = row_exp<ITEMS>(a, mp, c2);                 // a = e_p, A = Z_p
-    double Zq0 = (k > 0) ? row_exp<ITEMS>(eq, mq, c2) : 0.0;
+    double Zq0 = (k > 0 && !naive) ? row_exp<ITEMS>(eq, mq, c2) : 0.0;
     block_sum2<NWAVES>(A, Zq0, s_red, s_red2);
-    if (!(A > 0.0) || !isfinite(A) || (k > 0 && (!(Zq0 > 0.0) || !isfinite(Zq0)))) {
+    if (!(A > 0.0) || !isfinite(A) || (k > 0 && !naive && (!(Zq0 > 0.0) || !isfinite(Zq0)))) {
         if (t == 0) atomicOr(&s_flags, (uint32_t)MCSD_FLAG_NONFINITE);
     }
 
     int accepted = -1;
-    if (k > 0) {
+    if (k > 0 && !naive) {
         // fp64 track of the candidate tokens: thread c follows candidate c
         int my_tok = -1;
         double my_a = 0.0, my_q = 0.0;
@@ -319,6 +320,25 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
         const double u = (double)p.u_endpoint[rix];
         endpoint = inverse_cdf<ITEMS, VT>(a, A, u, (double)p.eps, s_red, s_seg, s_int, &s_flags);
         if (endpoint < 0 || endpoint >= V) endpoint = V - 1;
+    }
+    if (naive && k > 0) {
+        // multi-candidate naive sampling (the comparison rule of the ablation, Sec. 4.5): the
+        // token just drawn from p is kept; a candidate equal to it is accepted, the first such
+        if (t == 0) {
+            int acc = -1;
+            uint32_t fl = 0u;
+            for (int i = 0; i < k; ++i) {
+                const int tok = p.cand_tok[(size_t)b * N + s_kids[i]];
+                if (tok < 0 || tok >= V) fl |= MCSD_FLAG_BAD_TOKEN;
+                else if (acc < 0 && tok == endpoint) acc = i;
+            }
+            if (fl) atomicOr(&s_flags, fl);
+            s_accept = acc;
+        }
+        if (p.ratio && t < k) p.ratio[(size_t)b * N + s_kids[t]] = NaN;
+        __syncthreads();
+        accepted = s_accept;
+        if (accepted >= 0) endpoint = -1;
     }
     if (p.residual_out) {
         const float inv = (A > 0.0) ? (float)(1.0 / A) : 0.f;

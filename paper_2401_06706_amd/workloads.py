@@ -22,6 +22,7 @@ import numpy as np
 
 WITH_REPLACEMENT = 0
 WITHOUT_REPLACEMENT = 1
+NAIVE = 2                    # verification only: multi-candidate naive sampling (ablation rule)
 
 SEED_BASE = 0x4D435344  # "MCSD"
 
@@ -290,7 +291,8 @@ def draw_candidates(rng: np.random.Generator, q: np.ndarray, k: int, variant: in
 
 def gen_verify_inputs(w: Workload, rng: Optional[np.random.Generator] = None,
                       variant: Optional[int] = None,
-                      temperature: Optional[Sequence[float]] = None) -> VerifyInputs:
+                      temperature: Optional[Sequence[float]] = None,
+                      draw_candidates_on_host: bool = True) -> VerifyInputs:
     """Target logits z ~ N(0, 3^2); draft logits z + N(0, sigma_q^2); one
     independent row pair per row owner.  Candidates of a sampled sequence are
     drawn from softmax(draft row / T); a greedy sequence proposes the top-k
@@ -312,7 +314,7 @@ def gen_verify_inputs(w: Workload, rng: Optional[np.random.Generator] = None,
             noise = rng.standard_normal((w.B, V), dtype=np.float32)
             draft[:, r, :] = target[:, row, :] + np.float32(w.sigma_q) * noise
     cand = np.zeros((w.B, N), dtype=np.int32)
-    for b in range(w.B):
+    for b in range(w.B if draw_candidates_on_host else 0):    # otherwise the GPU sampler fills them in
         T = float(temperature[b])
         for row in range(1 + N):
             kids = tree.children[row]

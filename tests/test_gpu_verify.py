@@ -148,3 +148,18 @@ def test_runtime_errors_are_return_codes():
     with pytest.raises(M.McsdError) as e:
         M.mcsd_verify_sample(call.args)
     assert e.value.code == -3
+
+
+def test_naive_sampling_variant_tiny_and_full_vocab():
+    """Multi-candidate naive sampling (the ablation's comparison rule) against the oracle:
+    10^4 tiny sequences, then the batched workload at full size (greedy + sampled)."""
+    w = W.WORKLOADS["c1"].with_(B=10000, variant=W.NAIVE)
+    vi = W.gen_verify_inputs(w.with_(variant=W.WITH_REPLACEMENT), np.random.default_rng(w.seed + 5))
+    vi.variant = W.NAIVE                      # candidates drawn i.i.d., verified by the naive rule
+    gpu, orc, st = check(vi, "c1-naive", want_residual=True)
+    assert np.isnan(gpu["ratio"]).all()
+    assert (orc.n_accepted > 0).any() and (orc.n_accepted == 0).any()
+    w = W.WORKLOADS["c4"]
+    vi = W.gen_verify_inputs(w)
+    vi.variant = W.NAIVE
+    check(vi, "c4-naive")
