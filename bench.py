@@ -40,10 +40,12 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5"])
-    ap.add_argument("--stage", default="verify_step", choices=["verify_step", "draft_sample", "kv_commit"],
+    ap.add_argument("--stage", default="verify_step", choices=["verify_step", "draft_sample", "kv_commit", "no_tree_attention"],
                     help="verify_step (default): the headline step; draft_sample: the draft-side candidate "
                          "sampler that precedes it; kv_commit: tree build + commit of the accepted path that "
-                         "follows it (8 layers); each measured on its own")
+                         "follows it (8 layers); no_tree_attention: the same attention with one private "
+                         "prefix-cache copy per candidate sequence (what tree attention replaces), timed next to "
+                         "tree attention; each measured on its own")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--sets", type=int, default=0, help="rotating input copies (0 = enough for >= 1 GiB)")
@@ -231,6 +233,45 @@ def bench_kv_commit(args, torch, M, D, W):
     print(json.dumps(out))
 
 
+def bench_no_tree_attention(args, torch, M, D, W):
+    """Tree attention against the arrangement it replaces (Sec. 3.3): every root-to-leaf candidate
+    sequence as a sequence of its own with a private copy of the prefix cache, run through the same
+    kernel as a chain.  One input set each (the replicated caches are n_leaves times larger)."""
+    w = W.WORKLOADS[args.workload]
+    ai = W.gen_attn_inputs(w)
+    tree = D.make_attn_call(ai)
+    rep = D.make_replicated_attn_call(tree, ai)
+    n_leaves, depth = len(rep.paths), len(rep.paths[0])
+    e = 2 if ai.dtype == "bf16" else 4
+    rep_bytes = 2 * ai.H_kv * ai.d * e * n_leaves * (int(ai.prefix_len.sum()) + ai.B * depth) \
+        + 2 * ai.B * n_leaves * depth * ai.H_q * ai.d * e
+    res = {}
+    for name, call in (("tree", tree), ("replicated", rep)):
+        for _ in range(args.warmup):
+            M.mcsd_tree_attn(call.args)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            M.mcsd_tree_attn(call.args)
+        torch.cuda.synchronize()
+        res[name] = (time.perf_counter() - t0) * 1e6 / args.steps
+    out = {
+        "metric": "attention time without / with tree attention (same candidates, same kernel)",
+        "value": res["replicated"] / res["tree"], "unit": "x", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["tree"] * 1e-3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if ai.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name} attention: {w.description}", "candidate_sequences": ai.B * n_leaves,
+                   "depth": depth, "tree_nodes": ai.N, "input_sets": 1},
+        "tree_us": res["tree"], "replicated_us": res["replicated"],
+        "tree_bytes": ai.algorithmic_bytes(), "replicated_bytes": rep_bytes,
+        "tree_gbs": ai.algorithmic_bytes() / res["tree"] / 1e3, "replicated_gbs": rep_bytes / res["replicated"] / 1e3,
+        "roofline": {"kernel": "tree_attn_mfma (replicated sequences)", "bound": "hbm",
+                     "achieved": rep_bytes / res["replicated"] / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": rep_bytes / res["replicated"] / 1e3 / HBM_PEAK_GBS, "traffic": None},
+    }
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -260,6 +301,9 @@ def main():
         return
     if args.stage == "kv_commit":
         bench_kv_commit(args, torch, M, D, W)
+        return
+    if args.stage == "no_tree_attention":
+        bench_no_tree_attention(args, torch, M, D, W)
         return
     w = W.WORKLOADS[args.workload]
     ai = W.gen_attn_inputs(w)

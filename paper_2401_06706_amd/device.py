@@ -127,3 +127,54 @@ def make_draft_call(vi: VerifyInputs, u_draw: np.ndarray, device="cuda:0", near_
     args = mcsd.draft_args(t["draft_logits"], t["q_row"], t["parent"], t["u_draw"], t["temperature"],
                            t["cand_tok"], t["flags"], vi.variant, near_tie_eps=near_tie_eps)
     return DraftCall(args, t)
+
+
+def leaf_paths(parent: np.ndarray):
+    """Root-to-leaf node paths of a tree given by its parent array: list of lists of node ids."""
+    n = parent.shape[0]
+    has_child = np.zeros(n, dtype=bool)
+    has_child[parent[parent >= 0]] = True
+    paths = []
+    for leaf in np.flatnonzero(~has_child):
+        path, v = [], int(leaf)
+        while v >= 0:
+            path.append(v)
+            v = int(parent[v])
+        paths.append(path[::-1])
+    return paths
+
+
+def make_replicated_attn_call(tree_call: AttnCall, ai: AttnInputs, device="cuda:0") -> AttnCall:
+    """The same attention problem WITHOUT tree attention (the arrangement Sec. 3.3 starts from):
+    every candidate sequence (root-to-leaf path) becomes a sequence of its own with a private copy
+    of the prefix cache and its candidates as a chain.  Built on the device from the tensors of
+    `tree_call` by copies and gathers only.  Replica r = b * n_leaves + leaf index; all leaves
+    must have the same depth (true for k-configuration trees)."""
+    paths = leaf_paths(ai.parent)
+    depth = len(paths[0])
+    if any(len(p) != depth for p in paths):
+        raise ValueError("leaves of different depth")
+    n_leaves = len(paths)
+    idx = torch.tensor(paths, dtype=torch.long, device=device)           # [n_leaves][depth]
+    t0 = tree_call.tensors
+    B = ai.B
+    t = {
+        # q [B][N][H_q][d] -> [B][n_leaves][depth][H_q][d]
+        "q": t0["q"][:, idx].reshape(B * n_leaves, depth, ai.H_q, ai.d).contiguous(),
+        # k_tree [B][H_kv][N][d] -> [B][n_leaves][H_kv][depth][d]
+        "k_tree": t0["k_tree"][:, :, idx].permute(0, 2, 1, 3, 4).reshape(B * n_leaves, ai.H_kv, depth, ai.d).contiguous(),
+        "v_tree": t0["v_tree"][:, :, idx].permute(0, 2, 1, 3, 4).reshape(B * n_leaves, ai.H_kv, depth, ai.d).contiguous(),
+        "k_prefix": t0["k_prefix"].repeat_interleave(n_leaves, dim=0),
+        "v_prefix": t0["v_prefix"].repeat_interleave(n_leaves, dim=0),
+        "prefix_len": t0["prefix_len"].repeat_interleave(n_leaves),
+        "parent": torch.arange(-1, depth - 1, dtype=torch.int32, device=device),
+    }
+    t["out"] = torch.zeros_like(t["q"])
+    dt = mcsd.DTYPE_FP32 if ai.dtype == "fp32" else mcsd.DTYPE_BF16
+    desc = mcsd.attn_desc(B * n_leaves, depth, ai.H_q, ai.H_kv, ai.d, dt, ai.L_stride, ai.scale)
+    t["workspace"] = torch.empty(max(mcsd.mcsd_attn_workspace_bytes(desc), 256), dtype=torch.uint8, device=device)
+    args = mcsd.attn_args(t["q"], t["k_prefix"], t["v_prefix"], t["prefix_len"], t["k_tree"], t["v_tree"],
+                          t["parent"], t["out"], ai.scale, t["workspace"])
+    call = AttnCall(args, t)
+    call.paths = paths
+    return call

@@ -162,3 +162,25 @@ def test_workspace_too_small_is_an_error():
     with pytest.raises(M.McsdError) as e:
         M.mcsd_tree_attn(call.args)
     assert e.value.code == -5
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3"])
+def test_tree_attention_equals_replicated_candidate_sequences(name):
+    """Without tree attention every candidate sequence carries its own copy of the prefix cache
+    (Sec. 3.3); the outputs are the same, node by node."""
+    w = W.WORKLOADS[name]
+    ai = W.gen_attn_inputs(w)
+    tree = D.make_attn_call(ai)
+    rep = D.make_replicated_attn_call(tree, ai)
+    M.mcsd_tree_attn(tree.args)
+    M.mcsd_tree_attn(rep.args)
+    torch.cuda.synchronize()
+    a = tree.out.float().cpu().numpy()                                   # [B][N][H][d]
+    r = rep.out.float().cpu().numpy()                                    # [B*leaves][depth][H][d]
+    n_leaves = len(rep.paths)
+    tol = 1e-5 if ai.dtype == "fp32" else 2e-2
+    for b in range(ai.B):
+        for li, path in enumerate(rep.paths):
+            got = r[b * n_leaves + li]
+            want = a[b, path]
+            assert np.abs(got - want).max() <= tol, (b, li)
