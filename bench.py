@@ -40,12 +40,14 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5"])
-    ap.add_argument("--stage", default="verify_step", choices=["verify_step", "draft_sample", "kv_commit", "no_tree_attention"],
+    ap.add_argument("--stage", default="verify_step", choices=["verify_step", "draft_sample", "kv_commit", "no_tree_attention", "paged_attention"],
                     help="verify_step (default): the headline step; draft_sample: the draft-side candidate "
                          "sampler that precedes it; kv_commit: tree build + commit of the accepted path that "
                          "follows it (8 layers); no_tree_attention: the same attention with one private "
                          "prefix-cache copy per candidate sequence (what tree attention replaces), timed next to "
-                         "tree attention; each measured on its own")
+                         "tree attention; paged_attention: tree attention with the prefix cache in a page pool "
+                         "(--page-size), timed next to the contiguous layout; each measured on its own")
+    ap.add_argument("--page-size", type=int, default=64, help="tokens per page for --stage paged_attention")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--sets", type=int, default=0, help="rotating input copies (0 = enough for >= 1 GiB)")
@@ -272,6 +274,46 @@ def bench_no_tree_attention(args, torch, M, D, W):
     print(json.dumps(out))
 
 
+def bench_paged_attention(args, torch, M, D, W):
+    """mcsd_tree_attn_paged (prefix cache scattered over a page pool in random page order) next to
+    mcsd_tree_attn on the same data; rotating input sets as in the headline benchmark."""
+    w = W.WORKLOADS[args.workload]
+    ai = W.gen_attn_inputs(w)
+    n_sets = args.sets if args.sets > 0 else max(2, int(np.ceil((1 << 30) / ai.algorithmic_bytes())))
+    n_sets = min(n_sets, 64)
+    cont = [D.make_attn_call(ai) for _ in range(n_sets)]
+    paged = [D.make_paged_attn_call(c, ai, args.page_size, seed=i)[:2] for i, c in enumerate(cont)]
+    torch.cuda.synchronize()
+    res = {}
+    for name in ("contiguous", "paged"):
+        def run(n, off=0):
+            for i in range(n):
+                j = (off + i) % n_sets
+                if name == "contiguous":
+                    M.mcsd_tree_attn(cont[j].args)
+                else:
+                    M.mcsd_tree_attn_paged(paged[j][0].args, paged[j][1])
+        run(args.warmup)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(args.steps, args.warmup)
+        torch.cuda.synchronize()
+        res[name] = (time.perf_counter() - t0) * 1e6 / args.steps
+    b = ai.algorithmic_bytes()
+    out = {
+        "metric": "tree attention over a paged prefix cache: achieved HBM GB/s (attention + combine)",
+        "value": b / res["paged"] / 1e3, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["paged"] * 1e-3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if ai.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name} attention: {w.description}", "page_size": args.page_size, "input_sets": n_sets},
+        "paged_us": res["paged"], "contiguous_us": res["contiguous"], "contiguous_gbs": b / res["contiguous"] / 1e3,
+        "roofline": {"kernel": "tree_attn_mfma (paged) + combine", "bound": "hbm", "achieved": b / res["paged"] / 1e3,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": b / res["paged"] / 1e3 / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes": b},
+    }
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -304,6 +346,9 @@ def main():
         return
     if args.stage == "no_tree_attention":
         bench_no_tree_attention(args, torch, M, D, W)
+        return
+    if args.stage == "paged_attention":
+        bench_paged_attention(args, torch, M, D, W)
         return
     w = W.WORKLOADS[args.workload]
     ai = W.gen_attn_inputs(w)

@@ -135,6 +135,27 @@ typedef struct {
 size_t mcsd_attn_workspace_bytes(const mcsd_attn_desc *desc);
 int32_t mcsd_tree_attn(const mcsd_attn_desc *desc, const mcsd_attn_bufs *bufs, void *stream);
 
+/* Paged prefix cache.  The same operation, but the prefix keys and values live in a pool of
+ * fixed-size pages shared by all sequences (the usual serving layout): bufs->k_prefix and
+ * bufs->v_prefix point to pools [n_pages][H_kv][page_size][d], and logical prefix row r of
+ * sequence b is row r % page_size of page block_table[b][r / page_size].  page_size is a
+ * multiple of 32; desc->L_stride is the logical capacity, <= max_pages_per_seq * page_size;
+ * only the pages that hold rows below prefix_len[b] are read.  A table entry outside
+ * [0, n_pages) is a data error: its keys read as zeros (bf16 matrix-core path) or as page 0 /
+ * n_pages-1 (other paths); memory outside the pool is never touched.  Everything else (tree
+ * block, outputs, workspace) is as for mcsd_tree_attn.
+ */
+typedef struct {
+    uint32_t struct_size;
+    int32_t page_size;              /* tokens per page, multiple of 32 */
+    int32_t n_pages;                /* pages in the pools */
+    int32_t max_pages_per_seq;      /* row length of block_table */
+    const int32_t *block_table;     /* [B][max_pages_per_seq] device */
+} mcsd_paged_kv;
+
+int32_t mcsd_tree_attn_paged(const mcsd_attn_desc *desc, const mcsd_attn_bufs *bufs, const mcsd_paged_kv *paged,
+                             void *stream);
+
 /* --------------------------------------------------------------- verification
  * Algorithm 1 / Algorithm 2 for every row that has children, endpoint draws,
  * and the walk (Sec. 3).  Per sequence b with temperature T = temperature[b]:

@@ -248,3 +248,16 @@ def kv_commit(k_prefix, v_prefix, k_tree, v_tree, n_accepted, accepted_path, out
     if rc != 0:
         raise ValueError(f"mcsd_oracle_kv_commit failed: {rc}")
     return k_prefix, v_prefix, prefix_len, next_root, full
+
+
+def gather_pages(pool: np.ndarray, block_table: np.ndarray, L_stride: int) -> np.ndarray:
+    """Definition of the paged prefix layout: pool [n_pages][H_kv][page_size][d], block_table
+    [B][pages per sequence]; logical row r of sequence b is pool[block_table[b][r // page_size]][:, r % page_size].
+    Returns the contiguous cache [B][H_kv][L_stride][d]."""
+    n_pages, H_kv, page_size, d = pool.shape
+    B = block_table.shape[0]
+    out = np.empty((B, H_kv, L_stride, d), dtype=pool.dtype)
+    for b in range(B):
+        for r in range(L_stride):
+            out[b, :, r, :] = pool[block_table[b, r // page_size], :, r % page_size, :]
+    return out

@@ -25,7 +25,7 @@ FLAG_NEAR_TIE_ACCEPT, FLAG_NEAR_TIE_ENDPOINT, FLAG_BAD_TOKEN = 1, 2, 4
 FLAG_ZERO_DRAFT_PROB, FLAG_ZERO_RESIDUAL, FLAG_NONFINITE, FLAG_BAD_TREE = 8, 16, 32, 64
 
 EXPORTS = ["mcsd_last_error", "mcsd_version", "mcsd_tree_validate", "mcsd_attn_workspace_bytes",
-           "mcsd_tree_attn", "mcsd_verify_workspace_bytes", "mcsd_verify_sample", "mcsd_verify_step",
+           "mcsd_tree_attn", "mcsd_tree_attn_paged", "mcsd_verify_workspace_bytes", "mcsd_verify_sample", "mcsd_verify_step",
            "mcsd_draft_sample", "mcsd_tree_size", "mcsd_tree_build", "mcsd_kv_commit",
            "mcsd_kernel_timing", "mcsd_kernel_count", "mcsd_kernel_name", "mcsd_kernel_timing_read"]
 
@@ -60,6 +60,11 @@ class VerifyBufs(C.Structure):
         "target_logits", "draft_logits", "q_row", "parent", "cand_tok", "u_accept", "u_endpoint",
         "temperature", "n_accepted", "accepted_path", "out_tokens", "acc_child", "endpoint", "ratio",
         "flags", "residual_out", "workspace")] + [("workspace_bytes", C.c_size_t)]
+
+
+class PagedKV(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("page_size", C.c_int32), ("n_pages", C.c_int32),
+                ("max_pages_per_seq", C.c_int32), ("block_table", C.c_void_p)]
 
 
 class DraftDesc(C.Structure):
@@ -106,6 +111,8 @@ def lib() -> C.CDLL:
         L.mcsd_verify_workspace_bytes.restype = C.c_size_t
         L.mcsd_tree_attn.argtypes = [C.POINTER(AttnDesc), C.POINTER(AttnBufs), C.c_void_p]
         L.mcsd_tree_attn.restype = C.c_int32
+        L.mcsd_tree_attn_paged.argtypes = [C.POINTER(AttnDesc), C.POINTER(AttnBufs), C.POINTER(PagedKV), C.c_void_p]
+        L.mcsd_tree_attn_paged.restype = C.c_int32
         L.mcsd_verify_sample.argtypes = [C.POINTER(VerifyDesc), C.POINTER(VerifyBufs), C.c_void_p]
         L.mcsd_verify_sample.restype = C.c_int32
         L.mcsd_verify_step.argtypes = [C.POINTER(AttnDesc), C.POINTER(AttnBufs), C.POINTER(VerifyDesc),
@@ -216,6 +223,39 @@ def attn_args(q, k_prefix, v_prefix, prefix_len, k_tree, v_tree, parent, out, sc
 
 def mcsd_tree_attn(args: AttnArgs, stream=None) -> None:
     _check(lib().mcsd_tree_attn(C.byref(args.desc), C.byref(args.bufs), _stream(stream)))
+
+
+def paged_attn_args(q, k_pool, v_pool, block_table, prefix_len, k_tree, v_tree, parent, out, scale, L_stride: int,
+                    workspace: Optional[torch.Tensor] = None):
+    """Like attn_args, with the prefix in pools [n_pages][H_kv][page_size][d] and block_table
+    int32 [B][max_pages_per_seq].  Returns (AttnArgs, PagedKV)."""
+    B, N, H_q, d = q.shape
+    n_pages, H_kv, page_size, _ = k_pool.shape
+    if tuple(v_pool.shape) != tuple(k_pool.shape) or k_pool.shape[3] != d:
+        raise ValueError("pool shape mismatch")
+    if block_table.dim() != 2 or block_table.shape[0] != B:
+        raise ValueError("block_table must be [B][max_pages_per_seq]")
+    if q.dtype == torch.float32:
+        dt = DTYPE_FP32
+    elif q.dtype == torch.bfloat16:
+        dt = DTYPE_BF16
+    else:
+        raise ValueError(f"unsupported dtype {q.dtype}")
+    desc = attn_desc(B, N, H_q, H_kv, d, dt, L_stride, scale, parent.dim() == 2)
+    bufs = AttnBufs(C.sizeof(AttnBufs), _ptr(q, q.dtype, "q"), _ptr(k_pool, q.dtype, "k_pool"),
+                    _ptr(v_pool, q.dtype, "v_pool"), _ptr(prefix_len, torch.int32, "prefix_len"),
+                    _ptr(k_tree, q.dtype, "k_tree"), _ptr(v_tree, q.dtype, "v_tree"),
+                    _ptr(parent, torch.int32, "parent"), _ptr(out, q.dtype, "out"),
+                    _ptr(workspace, None, "workspace"),
+                    0 if workspace is None else workspace.numel() * workspace.element_size())
+    paged = PagedKV(C.sizeof(PagedKV), page_size, n_pages, block_table.shape[1],
+                    _ptr(block_table, torch.int32, "block_table"))
+    keep = (q, k_pool, v_pool, block_table, prefix_len, k_tree, v_tree, parent, out, workspace)
+    return AttnArgs(desc, bufs, keep), paged
+
+
+def mcsd_tree_attn_paged(args: AttnArgs, paged: PagedKV, stream=None) -> None:
+    _check(lib().mcsd_tree_attn_paged(C.byref(args.desc), C.byref(args.bufs), C.byref(paged), _stream(stream)))
 
 
 # -------------------------------------------------------------------- verification

@@ -210,6 +210,22 @@ int32_t mcsd_tree_attn(const mcsd_attn_desc *desc, const mcsd_attn_bufs *bufs, v
     return launch_tree_attn(*desc, *bufs, plan, (hipStream_t)stream);
 }
 
+int32_t mcsd_tree_attn_paged(const mcsd_attn_desc *desc, const mcsd_attn_bufs *bufs, const mcsd_paged_kv *paged,
+                             void *stream)
+{
+    AttnPlan plan;
+    if (!bufs) { set_error("attn bufs is NULL"); return MCSD_E_NULL; }
+    if (!paged) { set_error("paged descriptor is NULL"); return MCSD_E_NULL; }
+    int32_t rc = check_attn(desc, bufs, &plan);
+    if (rc != MCSD_OK) return rc;
+    if (paged->struct_size != sizeof(mcsd_paged_kv)) { set_error("paged struct_size %u != %zu", paged->struct_size, sizeof(mcsd_paged_kv)); return MCSD_E_SHAPE; }
+    if (!paged->block_table) { set_error("paged: block_table is NULL"); return MCSD_E_NULL; }
+    if (paged->page_size < 32 || paged->page_size % 32 != 0) { set_error("paged: page_size %d is not a positive multiple of 32", paged->page_size); return MCSD_E_SHAPE; }
+    if (paged->n_pages < 1 || paged->max_pages_per_seq < 1) { set_error("paged: non-positive size"); return MCSD_E_SHAPE; }
+    if ((long)paged->max_pages_per_seq * paged->page_size < (long)desc->L_stride) { set_error("paged: L_stride %d exceeds max_pages_per_seq * page_size", desc->L_stride); return MCSD_E_SHAPE; }
+    return launch_tree_attn(*desc, *bufs, plan, (hipStream_t)stream, paged);
+}
+
 int32_t mcsd_verify_sample(const mcsd_verify_desc *desc, const mcsd_verify_bufs *bufs, void *stream)
 {
     if (!bufs) { set_error("verify bufs is NULL"); return MCSD_E_NULL; }

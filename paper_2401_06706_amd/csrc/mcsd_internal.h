@@ -34,7 +34,7 @@ struct AttnPlan {
 
 bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan);
 int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const AttnPlan &plan,
-                         hipStream_t stream);
+                         hipStream_t stream, const mcsd_paged_kv *paged = nullptr);
 
 // ---- verification ---------------------------------------------------------
 int32_t launch_verify(const mcsd_verify_desc &d, const mcsd_verify_bufs &b, hipStream_t stream);

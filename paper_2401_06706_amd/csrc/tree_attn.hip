@@ -49,6 +49,11 @@ struct AttnParams {
     int R;                // rows per (b, g) in the partial buffers
     int split_bias;       // see split_tiles
     float scale_log2;     // scale * log2(e)
+    // paged prefix cache (block_table != nullptr): k_prefix / v_prefix are pools
+    // [n_pages][H_kv][page_size][d]; logical row r of sequence b lives in page
+    // block_table[b][r / page_size], slot r % page_size
+    const int32_t *block_table;
+    int page_size, n_pages, max_pages;
 };
 
 
@@ -117,7 +122,7 @@ __device__ __forceinline__ void build_ancestor_masks(const int32_t *parent, int 
 //   V  global -> registers (a lane reads 8 key rows x 16 contiguous bytes, neighbouring
 //      lanes neighbouring bytes; one tile ahead), in-lane 8x8 transpose of the 16-bit
 //      elements, registers -> the same LDS area -> operand (exchange inside 16-lane groups).
-template <int RH, int KS>
+template <int RH, int KS, bool PAGED>
 __global__ __launch_bounds__(RH * KS * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void tree_attn_mfma_kernel(AttnParams p)
 {
@@ -202,8 +207,8 @@ void tree_attn_mfma_kernel(AttnParams p)
             }
             __syncthreads();
             const int pair = s_pair_of_rank[blockIdx.z * p.n_chunks_max + chunk];
-            b = pair / p.n_chunks_max;
-            chunk = pair % p.n_chunks_max;
+            b = __builtin_amdgcn_readfirstlane(pair / p.n_chunks_max);       // read from LDS: make it scalar again
+            chunk = __builtin_amdgcn_readfirstlane(pair % p.n_chunks_max);
         }
         L = p.prefix_len[b];
         L = max(0, min(L, p.L_stride));
@@ -256,12 +261,14 @@ void tree_attn_mfma_kernel(AttnParams p)
         // exactly the valid rows (prefix_len rows of the cache slab, N rows of the tree block):
         // the tile base is a scalar offset, the lane offset a constant, and rows past the end of
         // a partial tile read as zero instead of leaving the array (their scores are masked).
-        const __amdgpu_buffer_rsrc_t rs_kpre = make_rsrc(static_cast<const char *>(p.k_prefix) + kv_head * (size_t)p.L_stride * (D * 2), (uint32_t)L * (D * 2));
-        const __amdgpu_buffer_rsrc_t rs_vpre = make_rsrc(static_cast<const char *>(p.v_prefix) + kv_head * (size_t)p.L_stride * (D * 2), (uint32_t)L * (D * 2));
+        // (paged cache: the prefix resources are empty and every prefix tile gets a resource of
+        // its own over the page slice it lies in)
+        const __amdgpu_buffer_rsrc_t rs_kpre = make_rsrc(static_cast<const char *>(p.k_prefix) + (PAGED ? 0 : kv_head * (size_t)p.L_stride * (D * 2)), PAGED ? 0u : (uint32_t)L * (D * 2));
+        const __amdgpu_buffer_rsrc_t rs_vpre = make_rsrc(static_cast<const char *>(p.v_prefix) + (PAGED ? 0 : kv_head * (size_t)p.L_stride * (D * 2)), PAGED ? 0u : (uint32_t)L * (D * 2));
         const __amdgpu_buffer_rsrc_t rs_ktre = make_rsrc(static_cast<const char *>(p.k_tree) + kv_head * (size_t)p.N * (D * 2), (uint32_t)p.N * (D * 2));
         const __amdgpu_buffer_rsrc_t rs_vtre = make_rsrc(static_cast<const char *>(p.v_tree) + kv_head * (size_t)p.N * (D * 2), (uint32_t)p.N * (D * 2));
 
-        struct TileRef { int off; int nvalid; bool tree; int tt; };
+        struct TileRef { int off; int nvalid; bool tree; int tt; size_t page_off; bool paged; };
         // Tiles at or past t_end are requested at an offset beyond every buffer's extent: the
         // hardware returns zeros without touching memory.  This keeps the prefetch of the next
         // tile unconditional, so the wait for one tile's data never has to cover the loads issued
@@ -269,10 +276,23 @@ void tree_attn_mfma_kernel(AttnParams p)
         constexpr int OFF_NOWHERE = 0x7fff0000;
         auto tile_ref = [&](int t) {
             TileRef r;
+            r.page_off = 0; r.paged = false;
             if (t >= t_end) {
                 r.off = OFF_NOWHERE; r.nvalid = KT; r.tree = false; r.tt = 0;
             } else if (t < tilesP) {
                 r.off = t * TILE_BYTES; r.nvalid = min(KT, L - t * KT); r.tree = false; r.tt = 0;
+                if (PAGED) {
+                    const int row = t * KT;
+                    const int page = row / p.page_size;
+                    const int blk = p.block_table[(size_t)b * p.max_pages + page];
+                    if ((unsigned)blk < (unsigned)p.n_pages) {
+                        r.paged = true;
+                        r.off = 0;
+                        r.page_off = (((size_t)blk * p.H_kv + g) * (size_t)p.page_size + (size_t)(row % p.page_size)) * (D * 2);
+                    } else {
+                        r.off = OFF_NOWHERE;       // an entry outside the pool reads as zero keys, never as memory
+                    }
+                }
             } else {
                 r.tt = t - tilesP;
                 r.off = r.tt * TILE_BYTES; r.nvalid = min(KT, p.N - r.tt * KT); r.tree = true;
@@ -281,13 +301,15 @@ void tree_attn_mfma_kernel(AttnParams p)
         };
         u32x4 kraw[8];
         auto load_k = [&](const TileRef &r) {
-            const __amdgpu_buffer_rsrc_t rs = r.tree ? rs_ktre : rs_kpre;
+            __amdgpu_buffer_rsrc_t rs = r.tree ? rs_ktre : rs_kpre;
+            if (PAGED && r.paged) rs = make_rsrc(static_cast<const char *>(p.k_prefix) + r.page_off, (uint32_t)r.nvalid * (D * 2));
 #pragma unroll
             for (int i = 0; i < 8; ++i) kraw[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off + i * 1024, r.off, 0);
         };
         u32x4 vcur[8];
         auto load_v = [&](const TileRef &r) {
-            const __amdgpu_buffer_rsrc_t rs = r.tree ? rs_vtre : rs_vpre;
+            __amdgpu_buffer_rsrc_t rs = r.tree ? rs_vtre : rs_vpre;
+            if (PAGED && r.paged) rs = make_rsrc(static_cast<const char *>(p.v_prefix) + r.page_off, (uint32_t)r.nvalid * (D * 2));
 #pragma unroll
             for (int s = 0; s < 8; ++s)
                 vcur[s] = __builtin_amdgcn_raw_buffer_load_b128(rs, v_lane_off + ((s < 4) ? 0 : 4096) + (s & 3) * 256, r.off, 0);
@@ -607,8 +629,16 @@ __global__ __launch_bounds__(256) void tree_attn_generic_kernel(AttnParams p)
     int L = p.prefix_len[b];
     L = max(0, min(L, p.L_stride));
     const size_t kv_head = (size_t)b * p.H_kv + g;
-    const T *kpre = static_cast<const T *>(p.k_prefix) + kv_head * (size_t)p.L_stride * d;
-    const T *vpre = static_cast<const T *>(p.v_prefix) + kv_head * (size_t)p.L_stride * d;
+    const bool paged = p.block_table != nullptr;
+    const T *kpre = static_cast<const T *>(p.k_prefix) + (paged ? 0 : kv_head * (size_t)p.L_stride * d);
+    const T *vpre = static_cast<const T *>(p.v_prefix) + (paged ? 0 : kv_head * (size_t)p.L_stride * d);
+    // row index (in units of d elements) of logical prefix row r inside kpre / vpre
+    auto prefix_row = [&](int r) -> size_t {
+        if (!paged) return (size_t)r;
+        int blk = p.block_table[(size_t)b * p.max_pages + r / p.page_size];
+        blk = min(max(blk, 0), p.n_pages - 1);      // an entry outside the pool never leaves it
+        return ((size_t)blk * p.H_kv + g) * (size_t)p.page_size + (size_t)(r % p.page_size);
+    };
     const T *ktre = static_cast<const T *>(p.k_tree) + kv_head * (size_t)p.N * d;
     const T *vtre = static_cast<const T *>(p.v_tree) + kv_head * (size_t)p.N * d;
     const int n_keys = L + p.N;
@@ -620,7 +650,7 @@ __global__ __launch_bounds__(256) void tree_attn_generic_kernel(AttnParams p)
         if (key < n_keys) {
             bool on = true;
             const T *kr;
-            if (key < L) kr = kpre + (size_t)key * d;
+            if (key < L) kr = kpre + prefix_row(key) * d;
             else {
                 const int a = key - L;
                 on = (s_anc[node][a >> 5] >> (a & 31)) & 1u;
@@ -649,7 +679,7 @@ __global__ __launch_bounds__(256) void tree_attn_generic_kernel(AttnParams p)
             float acc = 0.f;
             for (int j = 0; j < cnt; ++j) {
                 const int kj = k0 + j;
-                const T *vr = (kj < L) ? vpre + (size_t)kj * d : vtre + (size_t)(kj - L) * d;
+                const T *vr = (kj < L) ? vpre + prefix_row(kj) * d : vtre + (size_t)(kj - L) * d;
                 acc += s_p[j] * load_as_float<T>(vr, tid);
             }
             o_acc = o_acc * alpha + acc;
@@ -737,9 +767,13 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
 }
 
 int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const AttnPlan &plan,
-                         hipStream_t stream)
+                         hipStream_t stream, const mcsd_paged_kv *paged)
 {
     AttnParams p = {};
+    if (paged) {
+        p.block_table = paged->block_table; p.page_size = paged->page_size;
+        p.n_pages = paged->n_pages; p.max_pages = paged->max_pages_per_seq;
+    }
     p.q = b.q; p.k_prefix = b.k_prefix; p.v_prefix = b.v_prefix; p.k_tree = b.k_tree; p.v_tree = b.v_tree;
     p.prefix_len = b.prefix_len; p.parent = b.parent; p.out = b.out;
     p.B = d.B; p.N = d.N; p.H_q = d.H_q; p.H_kv = d.H_kv; p.G = d.H_q / d.H_kv; p.d = d.d;
@@ -771,8 +805,13 @@ int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const
     }
     const dim3 grid(d.H_kv, plan.n_chunks_max * plan.n_row_tiles, d.B);
     timing_begin(K_ATTN_MFMA, stream);
-    if (plan.variant == 0) hipLaunchKernelGGL((tree_attn_mfma_kernel<1, 4>), grid, dim3(256), 0, stream, p);
-    else hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2>), grid, dim3(256), 0, stream, p);
+    if (paged) {
+        if (plan.variant == 0) hipLaunchKernelGGL((tree_attn_mfma_kernel<1, 4, true>), grid, dim3(256), 0, stream, p);
+        else hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, true>), grid, dim3(256), 0, stream, p);
+    } else {
+        if (plan.variant == 0) hipLaunchKernelGGL((tree_attn_mfma_kernel<1, 4, false>), grid, dim3(256), 0, stream, p);
+        else hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, false>), grid, dim3(256), 0, stream, p);
+    }
     timing_end(K_ATTN_MFMA, stream);
     e = hipGetLastError();
     if (e != hipSuccess) { set_error("tree_attn_mfma launch failed: %s", hipGetErrorString(e)); return MCSD_E_HIP; }

@@ -178,3 +178,33 @@ def make_replicated_attn_call(tree_call: AttnCall, ai: AttnInputs, device="cuda:
     call = AttnCall(args, t)
     call.paths = paths
     return call
+
+
+def make_paged_attn_call(tree_call: AttnCall, ai: AttnInputs, page_size: int, seed: int = 0, spare_pages: int = 3,
+                         device="cuda:0"):
+    """The attention problem of `tree_call` with its prefix cache scattered into a page pool in a
+    random page order (device copies only).  Returns (AttnCall, PagedKV, block_table numpy)."""
+    B, H_kv, Ls, d = ai.B, ai.H_kv, ai.L_stride, ai.d
+    per_seq = (Ls + page_size - 1) // page_size
+    n_pages = B * per_seq + spare_pages
+    rng = np.random.default_rng(seed)
+    table = rng.permutation(n_pages)[: B * per_seq].reshape(B, per_seq).astype(np.int32)
+    t0 = tree_call.tensors
+    padded = per_seq * page_size
+    def scatter(cache):
+        pool = torch.full((n_pages, H_kv, page_size, d), float("nan"), dtype=cache.dtype, device=device)
+        c = cache
+        if padded != Ls:
+            c = torch.cat([cache, torch.zeros((B, H_kv, padded - Ls, d), dtype=cache.dtype, device=device)], dim=2)
+        pages = c.reshape(B, H_kv, per_seq, page_size, d).permute(0, 2, 1, 3, 4).reshape(B * per_seq, H_kv, page_size, d)
+        pool[torch.from_numpy(table.reshape(-1).astype(np.int64)).to(device)] = pages
+        return pool
+    t = dict(t0)
+    t["k_pool"], t["v_pool"] = scatter(t0["k_prefix"]), scatter(t0["v_prefix"])
+    t["block_table"] = torch.from_numpy(table).to(device)
+    t["out"] = torch.zeros_like(t0["out"])
+    t["workspace"] = torch.empty_like(t0["workspace"])
+    args, paged = mcsd.paged_attn_args(t["q"], t["k_pool"], t["v_pool"], t["block_table"], t["prefix_len"],
+                                       t["k_tree"], t["v_tree"], t["parent"], t["out"], ai.scale, Ls, t["workspace"])
+    del t["k_prefix"], t["v_prefix"]
+    return AttnCall(args, t), paged, table

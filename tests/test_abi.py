@@ -44,6 +44,7 @@ def test_struct_layout_matches_header(tmp_path):
               "mcsd_verify_desc": (M.VerifyDesc, ["V", "P", "variant", "gamma_max", "near_tie_eps"]),
               "mcsd_verify_bufs": (M.VerifyBufs, ["target_logits", "temperature", "acc_child", "ratio",
                                                   "flags", "residual_out", "workspace_bytes"]),
+              "mcsd_paged_kv": (M.PagedKV, ["page_size", "n_pages", "max_pages_per_seq", "block_table"]),
               "mcsd_draft_desc": (M.DraftDesc, ["B", "V", "P", "variant", "near_tie_eps"]),
               "mcsd_draft_bufs": (M.DraftBufs, ["draft_logits", "q_row", "u_draw", "temperature", "cand_tok", "flags"]),
               "mcsd_commit_desc": (M.CommitDesc, ["B", "H_kv", "dtype", "L_stride", "gamma_max", "n_layers"]),
@@ -224,3 +225,23 @@ def test_commit_descriptor_errors(lib):
         assert lib.mcsd_kv_commit(C.byref(d), C.byref(M.CommitBufs(C.sizeof(M.CommitBufs), *p2)), None) == -1, i
     p2 = list(ptrs); p2[2] = 4096 + 8
     assert lib.mcsd_kv_commit(C.byref(d), C.byref(M.CommitBufs(C.sizeof(M.CommitBufs), *p2)), None) == -2
+
+
+def test_paged_descriptor_errors(lib):
+    d = good_attn_desc()
+    need = M.mcsd_attn_workspace_bytes(d)
+    bufs = M.AttnBufs(C.sizeof(M.AttnBufs), 4096, 4096, 4096, 4096, 4096, 4096, 4096, 4096, 4096, need)
+    def paged(**kw):
+        a = dict(page_size=64, n_pages=200, max_pages_per_seq=64, block_table=4096)
+        a.update(kw)
+        return M.PagedKV(C.sizeof(M.PagedKV), a["page_size"], a["n_pages"], a["max_pages_per_seq"], a["block_table"])
+    cases = [(dict(page_size=48), -2), (dict(page_size=0), -2), (dict(n_pages=0), -2), (dict(max_pages_per_seq=0), -2),
+             (dict(max_pages_per_seq=63), -2), (dict(block_table=None), -1)]
+    for kw, code in cases:
+        pk = paged(**kw)
+        assert lib.mcsd_tree_attn_paged(C.byref(d), C.byref(bufs), C.byref(pk), None) == code, kw
+    pk = paged()
+    assert lib.mcsd_tree_attn_paged(C.byref(d), C.byref(bufs), None, None) == -1
+    assert lib.mcsd_tree_attn_paged(C.byref(d), None, C.byref(pk), None) == -1
+    pk.struct_size = 3
+    assert lib.mcsd_tree_attn_paged(C.byref(d), C.byref(bufs), C.byref(pk), None) == -2
