@@ -10,14 +10,16 @@
 // Work decomposition (bf16, d = 128: tree_attn_mfma_kernel)
 //   keys of a sequence = ceil(L/32) prefix tiles followed by ceil(N/32) tree tiles
 //   unit      = (sequence b, KV head g, tile of 32/64 query rows)
-//   segment   = one chunk of a unit, processed by one workgroup
+//   segment   = a run of consecutive key tiles of a unit, processed by one workgroup
 //               (4 waves): wave (rh, ks) owns 32 rows and every KS-th tile of the run and
 //               runs an independent online softmax with no workgroup barrier in the loop.
-//   The keys of a unit are cut into chunks of `chunk_tiles` tiles: grid (KV head, chunk x row
-//   tile, sequence).  The (sequence, chunk) pairs are handed out longest first.
-//   A segment that covers its whole unit writes the output rows itself; otherwise its
-//   (max, sum, O) partial goes to the workspace and tree_attn_combine_kernel merges the
-//   partials of a unit by log-sum-exp.
+//   The T tiles of a unit are cut into round(T / chunk_tiles) equal segments (at least one):
+//   grid (KV head, segment x row tile, sequence).  The (sequence, segment) pairs are handed
+//   out longest first.  A segment that covers its whole unit writes the output rows itself;
+//   otherwise its (max, sum, O) partial goes to the workspace and tree_attn_combine_kernel
+//   merges the partials of a unit by log-sum-exp.
+//   The prefix cache is either one contiguous slab per (sequence, KV head) or a pool of
+//   pages addressed through a block table (PAGED instantiation); the tiles are the same.
 //
 // Everything else (fp32 storage, other head dims) runs tree_attn_generic_kernel on
 // the vector ALUs.

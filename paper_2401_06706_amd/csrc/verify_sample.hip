@@ -1,10 +1,11 @@
 // Multi-candidate speculative sampling on gfx950: Algorithm 1 (with replacement),
 // Algorithm 2 (without replacement), the endpoint draws and the root-to-leaf walk.
 //
-// One 1024-thread workgroup owns one row of the tree (the root or a node).  Both
-// logit rows of that node are read from HBM exactly once with 128-bit loads and
-// stay in registers for all k sequential accept/reject rounds; every round is one
-// elementwise pass over the resident data plus one block reduction.
+// One workgroup (1024 threads, 512 for vocabularies above 16384) owns one row of the
+// tree (the root or a node).  Both logit rows of that node are read from HBM exactly
+// once with 128-bit loads and stay in registers for all k sequential accept/reject
+// rounds; every round is one elementwise pass over the resident data plus one block
+// reduction.
 //
 // Instead of renormalising after each rejection the kernel carries an
 // unnormalised residual a(x) and its sum A (p-hat = a / A), and the unnormalised
@@ -389,12 +390,6 @@ void launch_rows(const VerifyParams &p, hipStream_t stream)
         hipLaunchKernelGGL((verify_rows_kernel<ITEMS, VT, false>), grid, block, 0, stream, p);
 }
 
-int env_choice(const char *name, int dflt)
-{
-    const char *s = getenv(name);
-    return (s && *s) ? atoi(s) : dflt;
-}
-
 }  // namespace
 
 int32_t launch_verify(const mcsd_verify_desc &d, const mcsd_verify_bufs &b, hipStream_t stream)
@@ -413,12 +408,10 @@ int32_t launch_verify(const mcsd_verify_desc &d, const mcsd_verify_bufs &b, hipS
     // thread; beyond that 512 threads with twice the registers each (the 128-register
     // ceiling of a 1024-thread workgroup would spill).
     const int items1024 = (d.V + 4095) / 4096;
-    const bool wide = env_choice("MCSD_VERIFY_1024", 0) != 0;
     timing_begin(K_VERIFY_ROWS, stream);
     if (items1024 <= 1) launch_rows<1, 1024>(p, stream);
     else if (items1024 <= 2) launch_rows<2, 1024>(p, stream);
     else if (items1024 <= 4) launch_rows<4, 1024>(p, stream);
-    else if (wide) launch_rows<8, 1024>(p, stream);
     else launch_rows<16, 512>(p, stream);
     timing_end(K_VERIFY_ROWS, stream);
     hipError_t e = hipGetLastError();
