@@ -35,6 +35,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float LOG2E_F = 1.44269504088896340736f;
 constexpr float M_INIT = -1.0e30f;     // "no key seen yet" running max (finite so that differences stay finite)
@@ -522,9 +523,11 @@ void tree_attn_mfma_kernel(AttnParams p)
                     const uint2 pk = {pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv)};
                     const int gr = row0 + r, node = gr / p.G, hh = gr % p.G;
                     uint16_t *ob = static_cast<uint16_t *>(p.out);
-                    *reinterpret_cast<uint2 *>(ob + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + dcol) = pk;
+                    // outputs and partials are written once and not read again by this kernel: stored
+                    // non-temporally they do not sit dirty in L2 until the end-of-kernel write-back
+                    __builtin_nontemporal_store((u32x2){pk.x, pk.y}, reinterpret_cast<u32x2 *>(ob + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + dcol));
                 } else {
-                    *reinterpret_cast<f32x4 *>(p.part_o + (part_row + r) * D + dcol) = acc;
+                    __builtin_nontemporal_store(acc, reinterpret_cast<f32x4 *>(p.part_o + (part_row + r) * D + dcol));
                 }
             }
             __syncthreads();
@@ -587,7 +590,7 @@ __global__ __launch_bounds__(256) void tree_attn_combine_kernel(AttnParams p)
     const uint2 pk = {pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv)};
     const int node = r / p.G, hh = r % p.G;
     uint16_t *ob = static_cast<uint16_t *>(p.out);
-    *reinterpret_cast<uint2 *>(ob + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + 4 * d4) = pk;
+    __builtin_nontemporal_store((u32x2){pk.x, pk.y}, reinterpret_cast<u32x2 *>(ob + (((size_t)b * p.N + node) * p.H_q + (size_t)g * p.G + hh) * D + 4 * d4));
 }
 
 // ------------------------------------------------------------------ generic path
