@@ -99,7 +99,18 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     // sequence, then the argmax ones in their own order.  Done when B fits the workgroup.
     __shared__ int s_cnt[NWAVES];
     __shared__ int s_seq_of_rank[VT];
-    if (p.B > 1 && p.B <= VT) {
+    if (p.B > 1 && p.B <= 64) {
+        // one wavefront ranks up to 64 sequences by itself: one load, one ballot, one barrier
+        if (wave == 0) {
+            const bool sampled = (lane < p.B) && (p.temperature[lane] != 0.f);
+            const unsigned long long m = __ballot(sampled);
+            const int total = __popcll(m);
+            const int idx_s = __popcll(m & ((1ull << lane) - 1ull));    // sampled sequences before this one
+            if (lane < p.B) s_seq_of_rank[sampled ? idx_s : total + (lane - idx_s)] = lane;
+        }
+        __syncthreads();
+        b = s_seq_of_rank[blockIdx.y];
+    } else if (p.B > 1 && p.B <= VT) {
         const bool sampled = (t < p.B) && (p.temperature[t] != 0.f);
         const unsigned long long m = __ballot(sampled);
         if (lane == 0) s_cnt[wave] = __popcll(m);
