@@ -216,8 +216,10 @@ typedef struct {
 size_t mcsd_verify_workspace_bytes(const mcsd_verify_desc *desc);
 int32_t mcsd_verify_sample(const mcsd_verify_desc *desc, const mcsd_verify_bufs *bufs, void *stream);
 
-/* One verification step: mcsd_tree_attn then mcsd_verify_sample on `stream`.
- * Both argument sets are validated before anything is enqueued. */
+/* One verification step: mcsd_tree_attn and mcsd_verify_sample on `stream`.  Both argument sets
+ * are validated before anything is enqueued.  The results are those of the two calls made one
+ * after the other; the launches may be arranged differently (the merge of a split attention
+ * and the walk share one launch after the verification rows). */
 int32_t mcsd_verify_step(const mcsd_attn_desc *attn_desc, const mcsd_attn_bufs *attn_bufs,
                          const mcsd_verify_desc *verify_desc, const mcsd_verify_bufs *verify_bufs,
                          void *stream);

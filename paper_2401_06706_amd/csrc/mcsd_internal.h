@@ -17,6 +17,38 @@ void set_error(const char *fmt, ...);
 void timing_begin(int kernel_id, hipStream_t stream);
 void timing_end(int kernel_id, hipStream_t stream);
 
+// ---- the walk (Sec. 3), shared by verify_sample.hip and the fused tail of a step -------
+struct WalkParams {
+    int B, N, gamma_max;
+    const int32_t *acc_child, *endpoint, *cand_tok;
+    int32_t *n_accepted, *accepted_path, *out_tokens;
+};
+
+// From the root: an accepted child moves down one level, otherwise (or at a leaf) the row's
+// endpoint closes the block.
+__device__ __forceinline__ void walk_sequence(const WalkParams &w, int b)
+{
+    const int N = w.N, G = w.gamma_max;
+    int32_t *path = w.accepted_path + (size_t)b * G;
+    int32_t *out = w.out_tokens + (size_t)b * (G + 1);
+    for (int i = 0; i < G; ++i) path[i] = -1;
+    for (int i = 0; i <= G; ++i) out[i] = -1;
+    int row = 0, n = 0;
+    for (;;) {
+        const size_t rix = (size_t)b * (1 + N) + row;
+        const int c = w.acc_child[rix];
+        if (c < 0 || c >= N || n >= G) {
+            out[n] = w.endpoint[rix];
+            break;
+        }
+        path[n] = c;
+        out[n] = w.cand_tok[(size_t)b * N + c];
+        ++n;
+        row = 1 + c;
+    }
+    w.n_accepted[b] = n;
+}
+
 // ---- tree attention -------------------------------------------------------
 struct AttnPlan {
     bool use_mfma;        // bf16, d == 128: matrix-core kernel; otherwise the generic ALU kernel
@@ -33,11 +65,17 @@ struct AttnPlan {
 };
 
 bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan);
+// phases: the attention kernel, and the merge of the split partials (needed iff
+// plan.n_chunks_max > 1).  The merge launch can carry the walk of a verification that ran
+// before it on the same stream (tail_walk), which saves a step one kernel launch.
+enum { ATTN_PHASE_MAIN = 1, ATTN_PHASE_COMBINE = 2, ATTN_PHASE_ALL = 3 };
 int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const AttnPlan &plan,
-                         hipStream_t stream, const mcsd_paged_kv *paged = nullptr);
+                         hipStream_t stream, const mcsd_paged_kv *paged = nullptr, int phases = ATTN_PHASE_ALL,
+                         const WalkParams *tail_walk = nullptr);
 
 // ---- verification ---------------------------------------------------------
-int32_t launch_verify(const mcsd_verify_desc &d, const mcsd_verify_bufs &b, hipStream_t stream);
+int32_t launch_verify(const mcsd_verify_desc &d, const mcsd_verify_bufs &b, hipStream_t stream, bool with_walk = true);
+WalkParams make_walk_params(const mcsd_verify_desc &d, const mcsd_verify_bufs &b);
 
 // ---- draft-side candidates ------------------------------------------------
 int32_t launch_draft_sample(const mcsd_draft_desc &d, const mcsd_draft_bufs &b, hipStream_t stream);

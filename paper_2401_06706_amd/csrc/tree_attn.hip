@@ -540,9 +540,18 @@ void tree_attn_mfma_kernel(AttnParams p)
 }
 
 // Merges the chunks of one unit: out = sum_c 2^(m_c - m*) O_c / sum_c 2^(m_c - m*) l_c.
-__global__ __launch_bounds__(256) void tree_attn_combine_kernel(AttnParams p)
+// Blocks with blockIdx.x >= nx_combine carry the walk of a verification that ran before this
+// launch on the same stream (one thread per sequence), when the caller asked for that.
+__global__ __launch_bounds__(256) void tree_attn_combine_kernel(AttnParams p, int nx_combine, WalkParams w)
 {
     constexpr int D = 128;
+    if ((int)blockIdx.x >= nx_combine) {
+        if (blockIdx.y == 0 && blockIdx.z == 0) {
+            const int wb = ((int)blockIdx.x - nx_combine) * 256 + (int)threadIdx.x;
+            if (wb < w.B) walk_sequence(w, wb);
+        }
+        return;
+    }
     const int g = blockIdx.y, b = blockIdx.z;
     int L = p.prefix_len[b];
     L = max(0, min(L, p.L_stride));
@@ -772,7 +781,7 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
 }
 
 int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const AttnPlan &plan,
-                         hipStream_t stream, const mcsd_paged_kv *paged)
+                         hipStream_t stream, const mcsd_paged_kv *paged, int phases, const WalkParams *tail_walk)
 {
     AttnParams p = {};
     if (paged) {
@@ -808,22 +817,28 @@ int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const
         p.part_m = ws + rows * d.d;
         p.part_l = p.part_m + rows;
     }
-    const dim3 grid(d.H_kv, plan.n_chunks_max * plan.n_row_tiles, d.B);
-    timing_begin(K_ATTN_MFMA, stream);
-    if (paged) {
-        if (plan.variant == 0) hipLaunchKernelGGL((tree_attn_mfma_kernel<1, 4, true>), grid, dim3(256), 0, stream, p);
-        else hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, true>), grid, dim3(256), 0, stream, p);
-    } else {
-        if (plan.variant == 0) hipLaunchKernelGGL((tree_attn_mfma_kernel<1, 4, false>), grid, dim3(256), 0, stream, p);
-        else hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, false>), grid, dim3(256), 0, stream, p);
+    if (phases & ATTN_PHASE_MAIN) {
+        const dim3 grid(d.H_kv, plan.n_chunks_max * plan.n_row_tiles, d.B);
+        timing_begin(K_ATTN_MFMA, stream);
+        if (paged) {
+            if (plan.variant == 0) hipLaunchKernelGGL((tree_attn_mfma_kernel<1, 4, true>), grid, dim3(256), 0, stream, p);
+            else hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, true>), grid, dim3(256), 0, stream, p);
+        } else {
+            if (plan.variant == 0) hipLaunchKernelGGL((tree_attn_mfma_kernel<1, 4, false>), grid, dim3(256), 0, stream, p);
+            else hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, false>), grid, dim3(256), 0, stream, p);
+        }
+        timing_end(K_ATTN_MFMA, stream);
+        e = hipGetLastError();
+        if (e != hipSuccess) { set_error("tree_attn_mfma launch failed: %s", hipGetErrorString(e)); return MCSD_E_HIP; }
     }
-    timing_end(K_ATTN_MFMA, stream);
-    e = hipGetLastError();
-    if (e != hipSuccess) { set_error("tree_attn_mfma launch failed: %s", hipGetErrorString(e)); return MCSD_E_HIP; }
-    if (plan.n_chunks_max > 1) {
-        dim3 cgrid((plan.rows_per_kv + 7) / 8, d.H_kv, d.B);
+    if ((phases & ATTN_PHASE_COMBINE) && plan.n_chunks_max > 1) {
+        const int nx = (plan.rows_per_kv + 7) / 8;
+        WalkParams w = {};
+        int walk_blocks = 0;
+        if (tail_walk) { w = *tail_walk; walk_blocks = (w.B + 255) / 256; }
+        dim3 cgrid(nx + walk_blocks, d.H_kv, d.B);
         timing_begin(K_ATTN_COMBINE, stream);
-        hipLaunchKernelGGL(tree_attn_combine_kernel, cgrid, dim3(256), 0, stream, p);
+        hipLaunchKernelGGL(tree_attn_combine_kernel, cgrid, dim3(256), 0, stream, p, nx, w);
         timing_end(K_ATTN_COMBINE, stream);
         e = hipGetLastError();
         if (e != hipSuccess) { set_error("tree_attn_combine launch failed: %s", hipGetErrorString(e)); return MCSD_E_HIP; }

@@ -364,31 +364,10 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     }
 }
 
-// Sec. 3: walk from the root; an accepted child moves down one level, otherwise
-// (or at a leaf) the row's endpoint closes the block.
-__global__ void walk_kernel(VerifyParams p)
+__global__ void walk_kernel(WalkParams w)
 {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= p.B) return;
-    const int N = p.N, G = p.gamma_max;
-    int32_t *path = p.accepted_path + (size_t)b * G;
-    int32_t *out = p.out_tokens + (size_t)b * (G + 1);
-    for (int i = 0; i < G; ++i) path[i] = -1;
-    for (int i = 0; i <= G; ++i) out[i] = -1;
-    int row = 0, n = 0;
-    for (;;) {
-        const size_t rix = (size_t)b * (1 + N) + row;
-        const int c = p.acc_child[rix];
-        if (c < 0 || c >= N || n >= G) {
-            out[n] = p.endpoint[rix];
-            break;
-        }
-        path[n] = c;
-        out[n] = p.cand_tok[(size_t)b * N + c];
-        ++n;
-        row = 1 + c;
-    }
-    p.n_accepted[b] = n;
+    if (b < w.B) walk_sequence(w, b);
 }
 
 template <int ITEMS, int VT>
@@ -403,7 +382,16 @@ void launch_rows(const VerifyParams &p, hipStream_t stream)
 
 }  // namespace
 
-int32_t launch_verify(const mcsd_verify_desc &d, const mcsd_verify_bufs &b, hipStream_t stream)
+WalkParams make_walk_params(const mcsd_verify_desc &d, const mcsd_verify_bufs &b)
+{
+    WalkParams w;
+    w.B = d.B; w.N = d.N; w.gamma_max = d.gamma_max;
+    w.acc_child = b.acc_child; w.endpoint = b.endpoint; w.cand_tok = b.cand_tok;
+    w.n_accepted = b.n_accepted; w.accepted_path = b.accepted_path; w.out_tokens = b.out_tokens;
+    return w;
+}
+
+int32_t launch_verify(const mcsd_verify_desc &d, const mcsd_verify_bufs &b, hipStream_t stream, bool with_walk)
 {
     VerifyParams p;
     p.B = d.B; p.N = d.N; p.V = d.V; p.P = d.P; p.variant = d.variant; p.gamma_max = d.gamma_max;
@@ -430,8 +418,9 @@ int32_t launch_verify(const mcsd_verify_desc &d, const mcsd_verify_bufs &b, hipS
         set_error("verify_rows launch failed: %s", hipGetErrorString(e));
         return MCSD_E_HIP;
     }
+    if (!with_walk) return MCSD_OK;
     timing_begin(K_WALK, stream);
-    hipLaunchKernelGGL(walk_kernel, dim3((d.B + 63) / 64), dim3(64), 0, stream, p);
+    hipLaunchKernelGGL(walk_kernel, dim3((d.B + 63) / 64), dim3(64), 0, stream, make_walk_params(d, b));
     timing_end(K_WALK, stream);
     e = hipGetLastError();
     if (e != hipSuccess) {

@@ -54,11 +54,21 @@ def test_kernel_timing_counts_launches():
         M.mcsd_verify_step(a.args, v.args)
     t = M.mcsd_kernel_timing_read()
     M.mcsd_kernel_timing(False)
-    assert t["tree_attn_mfma"][1] == 3 and t["verify_rows"][1] == 3 and t["walk"][1] == 3
-    assert t["tree_attn_combine"][1] == 3          # 65 tiles per head: more than one chunk
+    assert t["tree_attn_mfma"][1] == 3 and t["verify_rows"][1] == 3
+    # 65 tiles per head: the attention is split, so the merge of its partials and the walk go out
+    # as one launch (the walk has none of its own)
+    assert t["tree_attn_combine"][1] == 3 and t["walk"][1] == 0
     assert all(ms > 0 for ms, n in t.values() if n)
     M.mcsd_verify_step(a.args, v.args)             # timing off again: nothing recorded
     assert M.mcsd_kernel_timing_read()["verify_rows"][1] == 3
+    # an attention that is not split keeps the separate walk launch
+    w1 = W.WORKLOADS["c2"].with_(prefix=(64, 64))
+    a1, v1 = D.make_attn_call(W.gen_attn_inputs(w1)), D.make_verify_call(W.gen_verify_inputs(w1))
+    M.mcsd_kernel_timing(True)
+    M.mcsd_verify_step(a1.args, v1.args)
+    t1 = M.mcsd_kernel_timing_read()
+    M.mcsd_kernel_timing(False)
+    assert t1["walk"][1] == 1 and t1["tree_attn_combine"][1] == 0
 
 
 def test_long_prefix_sampled_against_oracle():
