@@ -118,22 +118,23 @@ __global__ __launch_bounds__(VT) void draft_rows_kernel(DraftParams p)
             for (int w = 1; w < NWAVES; ++w)
                 if (s_bestv[w] > bv || (s_bestv[w] == bv && s_besti[w] < bi)) { bv = s_bestv[w]; bi = s_besti[w]; }
             __syncthreads();
-            // every remaining logit is -inf (or NaN): hand out the lowest ids not yet taken
-            // would need bookkeeping nobody wants; such rows are flagged instead
+            // nothing comparable left (only NaN logits remain): reported, token 0 handed out
             const bool none = (bi == 0x7fffffff);
             if (none) bi = 0;
             if (t == 0) {
                 p.cand_tok[(size_t)b * N + s_kids[i]] = bi;
                 p.flags[(size_t)b * N + s_kids[i]] = none ? (uint32_t)MCSD_FLAG_NONFINITE : 0u;
             }
-            // the winner leaves the row (ids are unique, one thread owns it)
+            // the winner leaves the row (ids are unique, one thread owns it): a NaN never wins a
+            // comparison, while a logit of -inf still can once everything above it is taken
+            const float gone = __int_as_float(0x7fc00000);
 #pragma unroll
             for (int j = 0; j < ITEMS; ++j) {
                 const int e = 4 * (t + VT * j);
-                if (bi == e) a[j].x = -INFINITY;
-                if (bi == e + 1) a[j].y = -INFINITY;
-                if (bi == e + 2) a[j].z = -INFINITY;
-                if (bi == e + 3) a[j].w = -INFINITY;
+                if (bi == e) a[j].x = gone;
+                if (bi == e + 1) a[j].y = gone;
+                if (bi == e + 2) a[j].z = gone;
+                if (bi == e + 3) a[j].w = gone;
             }
         }
         return;

@@ -157,3 +157,15 @@ def test_deterministic_and_other_stream():
     torch.cuda.synchronize()
     np.testing.assert_array_equal(a.results()["cand_tok"], b.results()["cand_tok"])
     np.testing.assert_array_equal(a.results()["flags"], b.results()["flags"])
+
+
+def test_top_k_with_minus_infinity_logits():
+    # only 3 finite logits but 6 candidates: after the finite ones, the -inf tokens in id order
+    w = W.WORKLOADS["c2"].with_(B=1, V=1000, kconfig=(6,))
+    vi = W.gen_verify_inputs(w, temperature=[0.0])
+    vi.draft_logits[:] = -np.inf
+    vi.draft_logits[0, 0, [700, 20, 333]] = [1.0, 3.0, 2.0]
+    u = np.full((1, vi.N), 0.5, np.float32)
+    got, rt, rm = run(vi, u)
+    assert rt[0].tolist() == [20, 333, 700, 0, 1, 2]
+    np.testing.assert_array_equal(got["cand_tok"], rt)
