@@ -83,3 +83,35 @@ def test_long_prefix_sampled_against_oracle():
     ref = O.tree_attn(ai.q, ai.k_prefix, ai.v_prefix, ai.prefix_len, ai.k_tree, ai.v_tree, ai.parent, ai.scale,
                       O.BF16, sel=sel, n_threads=4)
     assert np.abs(got[sel[:, 0], sel[:, 1], sel[:, 2]] - ref).max() <= 2e-2
+
+
+def test_step_can_be_captured_in_a_hip_graph_and_replayed():
+    """The library only enqueues kernels (no allocation, no memset, no synchronisation), so a step
+    can be captured; every replay, with eager work and synchronisations in between, reproduces
+    the eager results."""
+    w = W.WORKLOADS["c3"].with_(B=2, prefix=(1500, 2048))
+    ai, vi = W.gen_attn_inputs(w), W.gen_verify_inputs(w)
+    a, v = D.make_attn_call(ai), D.make_verify_call(vi)
+    M.mcsd_verify_step(a.args, v.args)
+    torch.cuda.synchronize()
+    ref_out = a.out.clone()
+    ref = {k: x.copy() for k, x in v.results().items()}
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        M.mcsd_verify_step(a.args, v.args, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    other = D.make_verify_call(W.gen_verify_inputs(W.WORKLOADS["c2"]))
+    for rep in range(4):
+        a.out.fill_(7.0)
+        for name in ("n_accepted", "accepted_path", "out_tokens", "acc_child", "endpoint", "flags"):
+            v.tensors[name].fill_(-3)
+        torch.cuda.synchronize()
+        g.replay()
+        M.mcsd_verify_sample(other.args)            # eager work of the program between replays
+        torch.cuda.synchronize()
+        assert torch.equal(a.out.view(torch.int16), ref_out.view(torch.int16)), rep
+        got = v.results()
+        for k in ("n_accepted", "accepted_path", "out_tokens", "acc_child", "endpoint", "flags"):
+            np.testing.assert_array_equal(got[k], ref[k], err_msg=f"{k} replay {rep}")
