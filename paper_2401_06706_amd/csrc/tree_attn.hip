@@ -93,16 +93,21 @@ __device__ __forceinline__ void split_tiles(int T, int chunk_tiles, int bias, in
     *seg = (T + nn - 1) / nn;
 }
 
-// anc[i] = {i} U anc[parent[i]]: one 128-bit mask per node, built by walking up.
-__device__ __forceinline__ void build_ancestor_masks(const int32_t *parent, int N, uint32_t (*s_anc)[4])
+// anc[i] = {i} U anc[parent[i]]: one 128-bit mask per node, built by walking up.  The parent
+// array is copied to LDS with one coalesced load first, so that the walk (one dependent read
+// per level) does not pay a global-memory latency per step.  Contains a workgroup barrier;
+// the caller adds the one that publishes the masks.
+__device__ __forceinline__ void build_ancestor_masks(const int32_t *parent, int N, uint32_t (*s_anc)[4], int *s_parent)
 {
+    for (int i = threadIdx.x; i < MCSD_MAX_NODES; i += blockDim.x) s_parent[i] = (i < N) ? parent[i] : -1;
+    __syncthreads();
     for (int i = threadIdx.x; i < MCSD_MAX_NODES; i += blockDim.x) {
         uint32_t m[4] = {0u, 0u, 0u, 0u};
         if (i < N) {
             int a = i;
             for (int step = 0; step < MCSD_MAX_NODES && a >= 0; ++step) {
                 m[a >> 5] |= 1u << (a & 31);
-                int pa = parent[a];
+                const int pa = s_parent[a];
                 a = (pa < a) ? pa : -1;      // a malformed array can not loop or index out of range
             }
         }
@@ -145,9 +150,10 @@ void tree_attn_mfma_kernel(AttnParams p)
 
     __shared__ __attribute__((aligned(16))) uint32_t s_big[NW * AREA_WORDS];
     __shared__ uint32_t s_anc[MCSD_MAX_NODES][4];
+    __shared__ int s_parent[MCSD_MAX_NODES];
     __shared__ float s_m[KS][ROWS], s_l[KS][ROWS];
     __shared__ float s_mstar[ROWS], s_linv[ROWS];
-    __shared__ int s_pair_len[NT], s_pair_of_rank[NT];
+    __shared__ int s_pair_len[NT], s_pair_of_rank[NT], s_seq_L[NT];
 
     // LDS positions (in 16-byte granules inside this wave's area).
     //   K granule (row r, granule c) is the operand of lane (c & 3, r & 15) for (sub = r >> 4, kk = c >> 2):
@@ -198,6 +204,7 @@ void tree_attn_mfma_kernel(AttnParams p)
                 split_tiles(Tb, p.chunk_tiles, p.split_bias, &nb, &segb);
                 my_len = max(0, min(segb, Tb - (tid % p.n_chunks_max) * segb));
                 s_pair_len[tid] = my_len;
+                if (tid % p.n_chunks_max == 0) s_seq_L[tid / p.n_chunks_max] = Lb;
             }
             __syncthreads();
             if (tid < n_pairs) {
@@ -212,9 +219,11 @@ void tree_attn_mfma_kernel(AttnParams p)
             const int pair = s_pair_of_rank[blockIdx.z * p.n_chunks_max + chunk];
             b = __builtin_amdgcn_readfirstlane(pair / p.n_chunks_max);       // read from LDS: make it scalar again
             chunk = __builtin_amdgcn_readfirstlane(pair % p.n_chunks_max);
+            L = __builtin_amdgcn_readfirstlane(s_seq_L[b]);      // already loaded and clamped: no second trip to memory
+        } else {
+            L = p.prefix_len[b];
+            L = max(0, min(L, p.L_stride));
         }
-        L = p.prefix_len[b];
-        L = max(0, min(L, p.L_stride));
         total_tiles = (L + KT - 1) / KT + p.tiles_tree;
         int n_seg, seg;
         split_tiles(total_tiles, p.chunk_tiles, p.split_bias, &n_seg, &seg);
@@ -227,11 +236,6 @@ void tree_attn_mfma_kernel(AttnParams p)
     {
         const int tilesP = (L + KT - 1) / KT;
         const int row0 = rt * ROWS;
-
-        if (t_end > tilesP) {
-            build_ancestor_masks(p.parent + (p.parent_per_seq ? (size_t)b * p.N : 0), p.N, s_anc);
-            __syncthreads();
-        }
 
         // Q operand, held in registers: lane (lj, lc) has Q[row0 + WROWS rh + 16 mt + lc][32 kk + 8 lj .. +7]
         bf16x8 qreg[MT][4];
@@ -321,6 +325,11 @@ void tree_attn_mfma_kernel(AttnParams p)
         int t = t_begin + ks;
         load_k(tile_ref(t));
         load_v(tile_ref(t));
+        // the masks are needed from the first tree tile on; built while the first loads are in flight
+        if (t_end > tilesP) {
+            build_ancestor_masks(p.parent + (p.parent_per_seq ? (size_t)b * p.N : 0), p.N, s_anc, s_parent);
+            __syncthreads();
+        }
         for (; t < t_end; t += KS) {
             const TileRef cur = tile_ref(t);
             // Both K and V run one tile ahead of their use: K(t) goes from its load registers to LDS
@@ -634,8 +643,9 @@ __global__ __launch_bounds__(256) void tree_attn_generic_kernel(AttnParams p)
     __shared__ float s_p[256];
     __shared__ float s_red[4];
     __shared__ uint32_t s_anc[MCSD_MAX_NODES][4];
+    __shared__ int s_parent[MCSD_MAX_NODES];
 
-    build_ancestor_masks(p.parent + (p.parent_per_seq ? (size_t)b * p.N : 0), p.N, s_anc);
+    build_ancestor_masks(p.parent + (p.parent_per_seq ? (size_t)b * p.N : 0), p.N, s_anc, s_parent);
     const T *qp = static_cast<const T *>(p.q) + (((size_t)b * p.N + node) * p.H_q + h) * (size_t)d;
     for (int c = tid; c < d; c += 256) s_q[c] = load_as_float<T>(qp, c);
     __syncthreads();
