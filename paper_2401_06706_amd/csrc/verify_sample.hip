@@ -99,19 +99,29 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     // sequence, then the argmax ones in their own order.  Done when B fits the workgroup.
     __shared__ int s_cnt[NWAVES];
     __shared__ int s_seq_of_rank[VT];
+    __shared__ float s_T_of_rank[VT];
+    // requested now, used after the ranking: the draft-row address needs it
+    const int qr = p.q_row[row];
+    float T = 1.f;
+    const bool ranked = p.B > 1 && p.B <= VT;
     if (p.B > 1 && p.B <= 64) {
         // one wavefront ranks up to 64 sequences by itself: one load, one ballot, one barrier
         if (wave == 0) {
-            const bool sampled = (lane < p.B) && (p.temperature[lane] != 0.f);
+            const float Tt = (lane < p.B) ? p.temperature[lane] : 1.f;
+            const bool sampled = (lane < p.B) && (Tt != 0.f);
             const unsigned long long m = __ballot(sampled);
             const int total = __popcll(m);
             const int idx_s = __popcll(m & ((1ull << lane) - 1ull));    // sampled sequences before this one
-            if (lane < p.B) s_seq_of_rank[sampled ? idx_s : total + (lane - idx_s)] = lane;
+            if (lane < p.B) {
+                const int r = sampled ? idx_s : total + (lane - idx_s);
+                s_seq_of_rank[r] = lane;
+                s_T_of_rank[r] = Tt;
+            }
         }
         __syncthreads();
-        b = s_seq_of_rank[blockIdx.y];
-    } else if (p.B > 1 && p.B <= VT) {
-        const bool sampled = (t < p.B) && (p.temperature[t] != 0.f);
+    } else if (ranked) {
+        const float Tt = (t < p.B) ? p.temperature[t] : 1.f;
+        const bool sampled = (t < p.B) && (Tt != 0.f);
         const unsigned long long m = __ballot(sampled);
         if (lane == 0) s_cnt[wave] = __popcll(m);
         __syncthreads();
@@ -123,9 +133,20 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
             total += c;
         }
         const int idx_s = before + __popcll(m & ((1ull << lane) - 1ull));   // sampled sequences before this one
-        if (t < p.B) s_seq_of_rank[sampled ? idx_s : total + (t - idx_s)] = t;
+        if (t < p.B) {
+            const int r = sampled ? idx_s : total + (t - idx_s);
+            s_seq_of_rank[r] = t;
+            s_T_of_rank[r] = Tt;
+        }
         __syncthreads();
-        b = s_seq_of_rank[blockIdx.y];
+    }
+    if (ranked) {
+        // back to wave-uniform values (they come out of LDS): addresses and branches stay scalar,
+        // and the temperature does not take a second trip to memory
+        b = __builtin_amdgcn_readfirstlane(s_seq_of_rank[blockIdx.y]);
+        T = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(s_T_of_rank[blockIdx.y])));
+    } else {
+        T = p.temperature[b];
     }
 
     // The two logit rows are requested first; the bookkeeping below (children list, flags)
@@ -133,12 +154,10 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     // also has children is checked afterwards (a mismatch is flagged, the row then counts
     // as a leaf and the extra row that was fetched is ignored).
     const size_t rix = (size_t)b * (1 + N) + row;
-    const float T = p.temperature[b];
     const float *zp_row = p.target_logits + rix * (size_t)V;
     const float NaN = __int_as_float(0x7fc00000);
     float4 a[ITEMS];
     load_row<ITEMS, VT, ALIGNED>(zp_row, V, a);
-    const int qr = p.q_row[row];
     const bool naive = (p.variant == MCSD_NAIVE);      // the draft row is not needed: candidates are only compared
     const bool have_q = (qr >= 0 && qr < p.P) && (T != 0.f) && !naive;
     const float *zq_row = have_q ? p.draft_logits + ((size_t)b * p.P + qr) * (size_t)V : zp_row;
