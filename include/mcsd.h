@@ -321,6 +321,15 @@ typedef struct {
 
 int32_t mcsd_kv_commit(const mcsd_commit_desc *desc, const mcsd_commit_bufs *bufs, void *stream);
 
+/* The same commit into a paged prefix cache (layout of mcsd_tree_attn_paged): bufs->k_prefix and
+ * bufs->v_prefix are pools [n_layers][n_pages][H_kv][page_size][d], and row L + j of sequence b
+ * is row (L + j) % page_size of page block_table[b][(L + j) / page_size]; the pages must already
+ * be assigned in the table.  desc->L_stride is the logical capacity (<= max_pages_per_seq *
+ * page_size).  A table entry outside [0, n_pages) ends the copy of that sequence there and sets
+ * MCSD_FLAG_BAD_TREE; nothing outside the pools is written. */
+int32_t mcsd_kv_commit_paged(const mcsd_commit_desc *desc, const mcsd_commit_bufs *bufs, const mcsd_paged_kv *paged,
+                             void *stream);
+
 /* ------------------------------------------------------------ profiling aid
  * Not part of the verification step.  mcsd_kernel_timing(1) makes every kernel
  * launch of the calls above be bracketed by a pair of HIP events on the launch

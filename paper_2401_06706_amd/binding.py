@@ -26,7 +26,7 @@ FLAG_ZERO_DRAFT_PROB, FLAG_ZERO_RESIDUAL, FLAG_NONFINITE, FLAG_BAD_TREE = 8, 16,
 
 EXPORTS = ["mcsd_last_error", "mcsd_version", "mcsd_tree_validate", "mcsd_attn_workspace_bytes",
            "mcsd_tree_attn", "mcsd_tree_attn_paged", "mcsd_verify_workspace_bytes", "mcsd_verify_sample", "mcsd_verify_step",
-           "mcsd_draft_sample", "mcsd_tree_size", "mcsd_tree_build", "mcsd_kv_commit",
+           "mcsd_draft_sample", "mcsd_tree_size", "mcsd_tree_build", "mcsd_kv_commit", "mcsd_kv_commit_paged",
            "mcsd_kernel_timing", "mcsd_kernel_count", "mcsd_kernel_name", "mcsd_kernel_timing_read"]
 
 
@@ -126,6 +126,8 @@ def lib() -> C.CDLL:
         L.mcsd_tree_build.restype = C.c_int32
         L.mcsd_kv_commit.argtypes = [C.POINTER(CommitDesc), C.POINTER(CommitBufs), C.c_void_p]
         L.mcsd_kv_commit.restype = C.c_int32
+        L.mcsd_kv_commit_paged.argtypes = [C.POINTER(CommitDesc), C.POINTER(CommitBufs), C.POINTER(PagedKV), C.c_void_p]
+        L.mcsd_kv_commit_paged.restype = C.c_int32
         L.mcsd_kernel_timing.argtypes = [C.c_int32]
         L.mcsd_kernel_timing.restype = C.c_int32
         L.mcsd_kernel_count.restype = C.c_int32
@@ -422,6 +424,42 @@ def commit_args(k_prefix, v_prefix, k_tree, v_tree, n_accepted, accepted_path, o
 
 def mcsd_kv_commit(args: CommitArgs, stream=None) -> None:
     _check(lib().mcsd_kv_commit(C.byref(args.desc), C.byref(args.bufs), _stream(stream)))
+
+
+def paged_commit_args(k_pool, v_pool, block_table, k_tree, v_tree, n_accepted, accepted_path, out_tokens, prefix_len,
+                      next_root, flags, L_stride: int):
+    """Like commit_args with the destination in pools [n_layers][n_pages][H_kv][page_size][d] (or 4-D
+    for one layer) and block_table int32 [B][max_pages_per_seq].  Returns (CommitArgs, PagedKV)."""
+    if k_pool.dim() == 4:
+        n_layers, (n_pages, H_kv, page_size, d) = 1, k_pool.shape
+    else:
+        n_layers, n_pages, H_kv, page_size, d = k_pool.shape
+    B, N = k_tree.shape[-4], k_tree.shape[-2]
+    gamma_max = accepted_path.shape[1]
+    if k_pool.dtype == torch.float32:
+        dt = DTYPE_FP32
+    elif k_pool.dtype == torch.bfloat16:
+        dt = DTYPE_BF16
+    else:
+        raise ValueError(f"unsupported dtype {k_pool.dtype}")
+    if tuple(v_pool.shape) != tuple(k_pool.shape) or tuple(v_tree.shape) != tuple(k_tree.shape):
+        raise ValueError("pool / tree shape mismatch")
+    if block_table.dim() != 2 or block_table.shape[0] != B:
+        raise ValueError("block_table must be [B][max_pages_per_seq]")
+    i32 = torch.int32
+    desc = CommitDesc(C.sizeof(CommitDesc), B, N, H_kv, d, dt, L_stride, gamma_max, n_layers)
+    bufs = CommitBufs(C.sizeof(CommitBufs), _ptr(k_pool, k_pool.dtype, "k_pool"), _ptr(v_pool, k_pool.dtype, "v_pool"),
+                      _ptr(k_tree, k_pool.dtype, "k_tree"), _ptr(v_tree, k_pool.dtype, "v_tree"),
+                      _ptr(n_accepted, i32, "n_accepted"), _ptr(accepted_path, i32, "accepted_path"),
+                      _ptr(out_tokens, i32, "out_tokens"), _ptr(prefix_len, i32, "prefix_len"),
+                      _ptr(next_root, i32, "next_root"), _ptr(flags, i32, "flags"))
+    paged = PagedKV(C.sizeof(PagedKV), page_size, n_pages, block_table.shape[1], _ptr(block_table, i32, "block_table"))
+    keep = (k_pool, v_pool, block_table, k_tree, v_tree, n_accepted, accepted_path, out_tokens, prefix_len, next_root, flags)
+    return CommitArgs(desc, bufs, keep), paged
+
+
+def mcsd_kv_commit_paged(args: CommitArgs, paged: PagedKV, stream=None) -> None:
+    _check(lib().mcsd_kv_commit_paged(C.byref(args.desc), C.byref(args.bufs), C.byref(paged), _stream(stream)))
 
 
 # ------------------------------------------------------------------- profiling aid

@@ -270,7 +270,7 @@ int32_t mcsd_tree_build(const int32_t *kconfig, int32_t gamma, int32_t B, const 
     return launch_tree_build(kconfig, gamma, n, B, prefix_len, parent, depth, q_row, position_ids, (hipStream_t)stream);
 }
 
-int32_t mcsd_kv_commit(const mcsd_commit_desc *d, const mcsd_commit_bufs *b, void *stream)
+static int32_t check_commit(const mcsd_commit_desc *d, const mcsd_commit_bufs *b)
 {
     if (!d) { set_error("commit desc is NULL"); return MCSD_E_NULL; }
     if (d->struct_size != sizeof(mcsd_commit_desc)) { set_error("commit desc struct_size %u != %zu", d->struct_size, sizeof(mcsd_commit_desc)); return MCSD_E_SHAPE; }
@@ -288,7 +288,27 @@ int32_t mcsd_kv_commit(const mcsd_commit_desc *d, const mcsd_commit_bufs *b, voi
         set_error("commit: caches must be 16-byte aligned");
         return MCSD_E_SHAPE;
     }
+    return MCSD_OK;
+}
+
+int32_t mcsd_kv_commit(const mcsd_commit_desc *d, const mcsd_commit_bufs *b, void *stream)
+{
+    const int32_t rc = check_commit(d, b);
+    if (rc != MCSD_OK) return rc;
     return launch_kv_commit(*d, *b, (hipStream_t)stream);
+}
+
+int32_t mcsd_kv_commit_paged(const mcsd_commit_desc *d, const mcsd_commit_bufs *b, const mcsd_paged_kv *paged, void *stream)
+{
+    int32_t rc = check_commit(d, b);
+    if (rc != MCSD_OK) return rc;
+    if (!paged) { set_error("paged descriptor is NULL"); return MCSD_E_NULL; }
+    if (paged->struct_size != sizeof(mcsd_paged_kv)) { set_error("paged struct_size %u != %zu", paged->struct_size, sizeof(mcsd_paged_kv)); return MCSD_E_SHAPE; }
+    if (!paged->block_table) { set_error("paged: block_table is NULL"); return MCSD_E_NULL; }
+    if (paged->page_size < 32 || paged->page_size % 32 != 0) { set_error("paged: page_size %d is not a positive multiple of 32", paged->page_size); return MCSD_E_SHAPE; }
+    if (paged->n_pages < 1 || paged->max_pages_per_seq < 1) { set_error("paged: non-positive size"); return MCSD_E_SHAPE; }
+    if ((long)paged->max_pages_per_seq * paged->page_size < (long)d->L_stride) { set_error("paged: L_stride %d exceeds max_pages_per_seq * page_size", d->L_stride); return MCSD_E_SHAPE; }
+    return launch_kv_commit(*d, *b, (hipStream_t)stream, paged);
 }
 
 int32_t mcsd_verify_step(const mcsd_attn_desc *ad, const mcsd_attn_bufs *ab, const mcsd_verify_desc *vd,

@@ -61,7 +61,23 @@ struct CommitParams {
     const int32_t *n_accepted, *accepted_path, *out_tokens;
     int32_t *prefix_len, *next_root;
     uint32_t *flags;
+    // paged destination (block_table != nullptr): pools [n_layers][n_pages][H_kv][page_size][d]
+    const int32_t *block_table;
+    int page_size, n_pages, max_pages;
 };
+
+// Rows of a paged cache that can be committed for sequence b starting at logical row L: the
+// first `n` rows whose pages are inside the pool.
+__device__ __forceinline__ int paged_rows_ok(const CommitParams &p, int b, long L, int n)
+{
+    int good = 0;
+    while (good < n) {
+        const int blk = p.block_table[(size_t)b * p.max_pages + (L + good) / p.page_size];
+        if ((unsigned)blk >= (unsigned)p.n_pages) break;
+        ++good;
+    }
+    return good;
+}
 
 // grid (gamma_max, B, n_layers): block (j, b, layer) copies path entry j of sequence b, all KV
 // heads, K and V.  prefix_len is only read here; kv_finish_kernel updates it afterwards.
@@ -80,10 +96,17 @@ __global__ __launch_bounds__(256) void kv_copy_kernel(CommitParams p)
     const int node = p.accepted_path[(size_t)b * p.gamma_max + j];
     const int vec_per_row = p.row_bytes / 16;
     const size_t lb = (size_t)layer * p.B + b;
+    size_t page_base = 0;       // paged: first row of the destination page slice of KV head 0
+    if (p.block_table) {
+        if (paged_rows_ok(p, b, L, j + 1) <= j) return;      // this row's page, or an earlier one, is not in the pool
+        const int blk = p.block_table[(size_t)b * p.max_pages + (L + j) / p.page_size];
+        page_base = ((size_t)layer * p.n_pages + blk) * (size_t)p.H_kv * p.page_size + (size_t)((L + j) % p.page_size);
+    }
     for (int e = threadIdx.x; e < p.H_kv * vec_per_row; e += blockDim.x) {
         const int g = e / vec_per_row, c = e % vec_per_row;
         const size_t src = ((lb * p.H_kv + g) * (size_t)p.N + node) * p.row_bytes + (size_t)c * 16;
-        const size_t dst = ((lb * p.H_kv + g) * (size_t)p.L_stride + (size_t)(L + j)) * p.row_bytes + (size_t)c * 16;
+        const size_t dst = (p.block_table ? page_base + (size_t)g * p.page_size
+                                          : (lb * p.H_kv + g) * (size_t)p.L_stride + (size_t)(L + j)) * p.row_bytes + (size_t)c * 16;
         *reinterpret_cast<uint4 *>(p.k_prefix + dst) = *reinterpret_cast<const uint4 *>(p.k_tree + src);
         *reinterpret_cast<uint4 *>(p.v_prefix + dst) = *reinterpret_cast<const uint4 *>(p.v_tree + src);
     }
@@ -107,6 +130,10 @@ __global__ void kv_finish_kernel(CommitParams p)
             if (nd < 0 || nd >= p.N) { fl |= (uint32_t)MCSD_FLAG_BAD_TREE; break; }
             ++good;
         }
+        if (p.block_table) {
+            const int ok = paged_rows_ok(p, b, L, good);
+            if (ok < good) { fl |= (uint32_t)MCSD_FLAG_BAD_TREE; good = ok; }
+        }
         p.prefix_len[b] = (int32_t)(L + good);
     }
     p.flags[b] = fl;
@@ -129,9 +156,15 @@ int32_t launch_tree_build(const int32_t *kconfig, int gamma, int n_nodes, int B,
     return MCSD_OK;
 }
 
-int32_t launch_kv_commit(const mcsd_commit_desc &d, const mcsd_commit_bufs &b, hipStream_t stream)
+int32_t launch_kv_commit(const mcsd_commit_desc &d, const mcsd_commit_bufs &b, hipStream_t stream,
+                         const mcsd_paged_kv *paged)
 {
     CommitParams p;
+    p.block_table = nullptr; p.page_size = p.n_pages = p.max_pages = 0;
+    if (paged) {
+        p.block_table = paged->block_table; p.page_size = paged->page_size;
+        p.n_pages = paged->n_pages; p.max_pages = paged->max_pages_per_seq;
+    }
     p.B = d.B; p.N = d.N; p.H_kv = d.H_kv; p.L_stride = d.L_stride; p.gamma_max = d.gamma_max; p.n_layers = d.n_layers;
     p.row_bytes = d.d * (d.dtype == MCSD_DTYPE_FP32 ? 4 : 2);
     p.k_prefix = static_cast<char *>(b.k_prefix); p.v_prefix = static_cast<char *>(b.v_prefix);

@@ -225,6 +225,14 @@ def test_commit_descriptor_errors(lib):
         assert lib.mcsd_kv_commit(C.byref(d), C.byref(M.CommitBufs(C.sizeof(M.CommitBufs), *p2)), None) == -1, i
     p2 = list(ptrs); p2[2] = 4096 + 8
     assert lib.mcsd_kv_commit(C.byref(d), C.byref(M.CommitBufs(C.sizeof(M.CommitBufs), *p2)), None) == -2
+    # paged form: the same descriptor checks, then the paged descriptor
+    pk = M.PagedKV(C.sizeof(M.PagedKV), 32, 10, 2, 4096)
+    assert lib.mcsd_kv_commit_paged(C.byref(desc(N=0)), C.byref(bufs), C.byref(pk), None) == -4
+    assert lib.mcsd_kv_commit_paged(C.byref(d), C.byref(bufs), None, None) == -1
+    for kw, code in [(dict(page_size=40), -2), (dict(n_pages=0), -2), (dict(max_pages=1), -2), (dict(table=None), -1)]:
+        a = dict(page_size=32, n_pages=10, max_pages=2, table=4096); a.update(kw)
+        pk = M.PagedKV(C.sizeof(M.PagedKV), a["page_size"], a["n_pages"], a["max_pages"], a["table"])
+        assert lib.mcsd_kv_commit_paged(C.byref(d), C.byref(bufs), C.byref(pk), None) == code, kw
 
 
 def test_paged_descriptor_errors(lib):

@@ -211,3 +211,71 @@ def test_decode_loop_three_steps_matches_oracle_loop():
     np.testing.assert_array_equal(t_kp.view(torch.int16).cpu().numpy().view(np.uint16), kp)
     np.testing.assert_array_equal(t_vp.view(torch.int16).cpu().numpy().view(np.uint16), vp)
     assert (L > L0).all() and (L - L0).sum() >= 6
+
+
+@pytest.mark.parametrize("page_size,n_layers", [(32, 1), (64, 3)])
+def test_kv_commit_paged_matches_contiguous_commit(page_size, n_layers):
+    """Commit into a page pool; gathering the pool back by the layout's definition gives the
+    oracle's contiguous commit, layer by layer.  Includes a sequence whose new rows cross a page
+    boundary, one without room, and untouched spare pages."""
+    rng = np.random.default_rng(11)
+    B, H_kv, d, kconfig = 4, 2, 16, (2, 2, 2)
+    per_seq = 3
+    Ls = per_seq * page_size
+    L = np.array([page_size - 1, 5, Ls - 1, 2 * page_size - 2], np.int32)
+    n_acc = np.array([3, 2, 2, 3], np.int32)          # seq 0 and 3 cross a page boundary; seq 2 does not fit
+    kp, vp, kt, vt, paths, out_tok, N, gamma = make_commit_case(rng, n_layers, B, H_kv, d, Ls, kconfig, "fp32", L, n_acc)
+    n_pages = B * per_seq + 2
+    table = rng.permutation(n_pages)[: B * per_seq].reshape(B, per_seq).astype(np.int32)
+    kpool = rng.standard_normal((n_layers, n_pages, H_kv, page_size, d)).astype(np.float32)
+    vpool = rng.standard_normal((n_layers, n_pages, H_kv, page_size, d)).astype(np.float32)
+    for layer in range(n_layers):
+        for b in range(B):
+            for pg in range(per_seq):
+                kpool[layer, table[b, pg]] = kp[layer, b, :, pg * page_size:(pg + 1) * page_size]
+                vpool[layer, table[b, pg]] = vp[layer, b, :, pg * page_size:(pg + 1) * page_size]
+    t = lambda a: torch.from_numpy(a).to(DEV)
+    t_kpool, t_vpool, t_L = t(kpool), t(vpool), dev_i32(L)
+    nxt = torch.full((B,), -9, dtype=torch.int32, device=DEV)
+    fl = torch.full((B,), -9, dtype=torch.int32, device=DEV)
+    args, paged = M.paged_commit_args(t_kpool, t_vpool, dev_i32(table), t(kt), t(vt), dev_i32(n_acc), dev_i32(paths),
+                                      dev_i32(out_tok), t_L, nxt, fl, Ls)
+    M.mcsd_kv_commit_paged(args, paged)
+    torch.cuda.synchronize()
+    ref_k, ref_v, ref_L, ref_nxt, ref_full = O.kv_commit(kp, vp, kt, vt, n_acc, paths, out_tok, L)
+    got_kpool, got_vpool = t_kpool.cpu().numpy(), t_vpool.cpu().numpy()
+    for layer in range(n_layers):
+        np.testing.assert_array_equal(O.gather_pages(got_kpool[layer], table, Ls), ref_k[layer])
+        np.testing.assert_array_equal(O.gather_pages(got_vpool[layer], table, Ls), ref_v[layer])
+    np.testing.assert_array_equal(t_L.cpu().numpy(), ref_L)
+    np.testing.assert_array_equal(nxt.cpu().numpy(), ref_nxt)
+    np.testing.assert_array_equal(fl.cpu().numpy() != 0, ref_full != 0)
+    assert ref_full.tolist() == [0, 0, 1, 0]
+    spare = [pg for pg in range(n_pages) if pg not in table.reshape(-1).tolist()]
+    np.testing.assert_array_equal(got_kpool[:, spare], kpool[:, spare])
+
+
+def test_kv_commit_paged_stops_at_a_table_entry_outside_the_pool():
+    rng = np.random.default_rng(12)
+    B, H_kv, d, page_size, per_seq = 2, 2, 8, 32, 2
+    Ls = per_seq * page_size
+    L = np.array([30, 10], np.int32)
+    n_acc = np.array([3, 3], np.int32)                 # sequence 0: rows 30, 31 in page 0, row 32 in page 1
+    kp, vp, kt, vt, paths, out_tok, N, gamma = make_commit_case(rng, 1, B, H_kv, d, Ls, (2, 2, 2), "fp32", L, n_acc)
+    table = np.array([[0, 99], [1, 2]], np.int32)      # sequence 0's second page is not in the pool
+    kpool = np.zeros((1, 3, H_kv, page_size, d), np.float32)
+    vpool = np.zeros_like(kpool)
+    t = lambda a: torch.from_numpy(a).to(DEV)
+    t_kpool, t_vpool, t_L = t(kpool), t(vpool), dev_i32(L)
+    nxt = torch.empty((B,), dtype=torch.int32, device=DEV)
+    fl = torch.empty((B,), dtype=torch.int32, device=DEV)
+    args, paged = M.paged_commit_args(t_kpool, t_vpool, dev_i32(table), t(kt), t(vt), dev_i32(n_acc), dev_i32(paths),
+                                      dev_i32(out_tok), t_L, nxt, fl, Ls)
+    M.mcsd_kv_commit_paged(args, paged)
+    torch.cuda.synchronize()
+    assert t_L.cpu().numpy().tolist() == [32, 13] and fl.cpu().numpy().tolist() == [64, 0]
+    got = t_kpool.cpu().numpy()
+    np.testing.assert_array_equal(got[0, 0, :, 30], kt[0, 0, :, paths[0, 0]])
+    np.testing.assert_array_equal(got[0, 0, :, 31], kt[0, 0, :, paths[0, 1]])
+    np.testing.assert_array_equal(got[0, 1, :, 10:13], kt[0, 1][:, paths[1]])
+    assert not got[0, 2].any()
