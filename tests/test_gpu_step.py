@@ -115,3 +115,19 @@ def test_step_can_be_captured_in_a_hip_graph_and_replayed():
         got = v.results()
         for k in ("n_accepted", "accepted_path", "out_tokens", "acc_child", "endpoint", "flags"):
             np.testing.assert_array_equal(got[k], ref[k], err_msg=f"{k} replay {rep}")
+
+
+def test_million_token_prefix_sampled_against_oracle():
+    """One sequence with a 1,000,003-token prefix (256 MB of K per head): offsets far beyond the
+    bench workloads, hundreds of segments per unit, a ragged last prefix tile."""
+    w = W.WORKLOADS["c2"].with_(B=1, H_q=2, H_kv=1, prefix=(1000003, 1000003), kconfig=(3, 2))
+    ai = W.gen_attn_inputs(w)
+    call = D.make_attn_call(ai)
+    M.mcsd_tree_attn(call.args)
+    torch.cuda.synchronize()
+    got = call.out_numpy()
+    sel = np.array([[0, 0, 0], [0, 8, 1], [0, 4, 0]], np.int32)
+    ref = O.tree_attn(ai.q, ai.k_prefix, ai.v_prefix, ai.prefix_len, ai.k_tree, ai.v_tree, ai.parent, ai.scale,
+                      O.BF16, sel=sel, n_threads=3)
+    assert np.abs(got[sel[:, 0], sel[:, 1], sel[:, 2]] - ref).max() <= 2e-2
+    assert np.isfinite(got).all()
