@@ -163,3 +163,14 @@ def test_naive_sampling_variant_tiny_and_full_vocab():
     vi = W.gen_verify_inputs(w)
     vi.variant = W.NAIVE
     check(vi, "c4-naive")
+
+
+@pytest.mark.parametrize("B", [65, 200, 1024, 1500])
+def test_many_sequences_mixed_temperatures(B):
+    """Batch sizes on both sides of the ranking paths (one wavefront up to 64 sequences, the whole
+    workgroup up to its thread count, none beyond), argmax and sampled sequences interleaved."""
+    w = W.WORKLOADS["c2"].with_(B=B, V=512, kconfig=(3, 2), variant=W.WITHOUT_REPLACEMENT)
+    rng = np.random.default_rng(B)
+    temps = np.where(rng.random(B) < 0.4, 0.0, rng.choice([0.5, 1.0, 1.7], B)).astype(np.float32)
+    vi = W.gen_verify_inputs(w, rng, temperature=temps)
+    check(vi, f"B{B}")
