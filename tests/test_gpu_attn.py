@@ -184,3 +184,19 @@ def test_tree_attention_equals_replicated_candidate_sequences(name):
             got = r[b * n_leaves + li]
             want = a[b, path]
             assert np.abs(got - want).max() <= tol, (b, li)
+
+
+def test_many_short_sequences():
+    """300 sequences (more (sequence, segment) pairs than a workgroup ranks: plain dispatch order)."""
+    w = W.WORKLOADS["c2"].with_(B=300, H_q=4, H_kv=2, prefix=(0, 700), kconfig=(3, 2))
+    ai = W.gen_attn_inputs(w)
+    call = D.make_attn_call(ai)
+    M.mcsd_tree_attn(call.args)
+    torch.cuda.synchronize()
+    got = call.out_numpy()
+    rng = np.random.default_rng(4)
+    sel = np.stack([rng.integers(0, ai.B, 200), rng.integers(0, ai.N, 200), rng.integers(0, ai.H_q, 200)], axis=1).astype(np.int32)
+    sel[0, 0] = int(np.argmin(ai.prefix_len)); sel[1, 0] = int(np.argmax(ai.prefix_len))
+    ref = O.tree_attn(ai.q, ai.k_prefix, ai.v_prefix, ai.prefix_len, ai.k_tree, ai.v_tree, ai.parent, ai.scale,
+                      O.BF16, sel=sel, n_threads=8)
+    assert np.abs(got[sel[:, 0], sel[:, 1], sel[:, 2]] - ref).max() <= 2e-2
