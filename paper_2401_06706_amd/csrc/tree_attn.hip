@@ -26,6 +26,8 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "mcsd_internal.h"
 
 namespace mcsd {
@@ -130,10 +132,20 @@ __device__ __forceinline__ void build_ancestor_masks(const int32_t *parent, int 
 //   V  global -> registers (a lane reads 8 key rows x 16 contiguous bytes, neighbouring
 //      lanes neighbouring bytes; one tile ahead), in-lane 8x8 transpose of the 16-bit
 //      elements, registers -> the same LDS area -> operand (exchange inside 16-lane groups).
-template <int RH, int KS, bool PAGED>
+//
+// COOP (one key stream, several row groups): the waves of the workgroup share every K/V tile.
+// Each wave loads a quarter of the tile and stores it to a double-buffered LDS tile that all
+// waves read their operands from after one workgroup barrier per tile; K in the operand order
+// above, V in its natural order (row pitch 288 bytes) and read with the transposing LDS load,
+// which hands a lane the four keys of one d column that the PV operand needs.  Per wave and
+// tile that is a quarter of the global loads and LDS stores of the private scheme and no
+// in-register transpose, which matters where the matrix cores are the limit (many query rows
+// per KV head).
+template <int RH, int KS, bool PAGED, bool COOP = false>
 __global__ __launch_bounds__(RH * KS * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void tree_attn_mfma_kernel(AttnParams p)
 {
+    static_assert(!COOP || (KS == 1 && RH == 4), "the shared-tile scheme splits a tile over four waves of one key stream");
     constexpr int MT = 2;                   // 16-row MFMA tiles per wave
     constexpr int NW = RH * KS;
     constexpr int NT = NW * 64;
@@ -178,6 +190,20 @@ void tree_attn_mfma_kernel(AttnParams p)
     //   V load s (0..7): row (s < 4 ? 0 : 16) + 4 lj + (s & 3), granule lc
     const uint32_t k_lane_off = lane * 16;
     const uint32_t v_lane_off = lj * 1024 + lc * 16;
+    // COOP: wave w loads K rows and V rows 8 w .. 8 w + 7 (load j = 0, 1: row 8 w + 4 j + lj, granule lc).
+    //   A buffer is 2048 words of K (operand order) followed by 32 V rows of 72 words.
+    constexpr int COOP_BUF_WORDS = 2048 + KT * 72;
+    static_assert(!COOP || 2 * COOP_BUF_WORDS <= NW * AREA_WORDS, "the two tile buffers live in the epilogue areas");
+    uint32_t coop_kst[2], coop_vst[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int i = 2 * wave + j;                 // K load index of the private scheme
+        coop_kst[j] = 4 * ((lc >> 2) * 64 + (lc & 3) * 16 + ((4 * (i & 3) + lj) ^ lc) + (i >> 2) * 256);
+        coop_vst[j] = 2048 + (4 * i + lj) * 72 + lc * 4;
+    }
+    //   transposing read for (sub, nt): the 16 lanes of a group point at keys 16 sub + 4 lj + (lc >> 2),
+    //   d columns 16 nt + 4 (lc & 3) .. + 3; lane lc receives column 16 nt + lc of keys 16 sub + 4 lj + 0..3
+    const uint32_t coop_vld = 2048 + (4 * lj + (lc >> 2)) * 72 + (lc & 3) * 2;     // + sub 16 x 72 + nt 8 words
     const float c2 = p.scale_log2;      // >= 0 (checked by the host)
     const uint16_t *qb = static_cast<const uint16_t *>(p.q);
 
@@ -322,26 +348,159 @@ void tree_attn_mfma_kernel(AttnParams p)
                 vcur[s] = __builtin_amdgcn_raw_buffer_load_b128(rs, v_lane_off + ((s < 4) ? 0 : 4096) + (s & 3) * 256, r.off, 0);
         };
 
+        // COOP: this wave's quarter of both tiles (two K and two V requests)
+        auto load_kv_coop = [&](const TileRef &r, const int st) {
+            __amdgpu_buffer_rsrc_t rk = r.tree ? rs_ktre : rs_kpre;
+            __amdgpu_buffer_rsrc_t rv = r.tree ? rs_vtre : rs_vpre;
+            if (PAGED && r.paged) {
+                rk = make_rsrc(static_cast<const char *>(p.k_prefix) + r.page_off, (uint32_t)r.nvalid * (D * 2));
+                rv = make_rsrc(static_cast<const char *>(p.v_prefix) + r.page_off, (uint32_t)r.nvalid * (D * 2));
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                kraw[2 * st + j] = __builtin_amdgcn_raw_buffer_load_b128(rk, k_lane_off + (2 * wave + j) * 1024, r.off, 0);
+                vcur[2 * st + j] = __builtin_amdgcn_raw_buffer_load_b128(rv, k_lane_off + (2 * wave + j) * 1024, r.off, 0);
+            }
+        };
+
         int t = t_begin + ks;
-        load_k(tile_ref(t));
-        load_v(tile_ref(t));
+        if (COOP) {
+            // the first tile goes to its LDS buffer here, every later one inside the step before it;
+            // requests run two to three tiles ahead of their use
+            load_kv_coop(tile_ref(t), 0);
+            load_kv_coop(tile_ref(t + 1), 1);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                *reinterpret_cast<u32x4 *>(s_big + coop_kst[j]) = kraw[j];
+                *reinterpret_cast<u32x4 *>(s_big + coop_vst[j]) = vcur[j];
+            }
+            load_kv_coop(tile_ref(t + 2), 0);
+        } else {
+            load_k(tile_ref(t));
+            load_v(tile_ref(t));
+        }
+        const bool wave_active = !COOP || row0 + WROWS * rh < p.M;     // a wave whose rows all lie past M only helps to load
         // the masks are needed from the first tree tile on; built while the first loads are in flight
         if (t_end > tilesP) {
             build_ancestor_masks(p.parent + (p.parent_per_seq ? (size_t)b * p.N : 0), p.N, s_anc, s_parent);
             __syncthreads();
         }
-        for (; t < t_end; t += KS) {
+        auto tile_step = [&](const int t, auto stage) __attribute__((always_inline)) {
+            constexpr int ST = decltype(stage)::value;      // COOP: register stage and LDS buffer of this tile
             const TileRef cur = tile_ref(t);
             // Both K and V run one tile ahead of their use: K(t) goes from its load registers to LDS
             // (operand order) and K(t + KS) is requested into the same registers; V(t + KS) is
             // requested further down, as soon as V(t) has left its registers.
+            if (COOP) {
+                // Tile t is in buffer t & 1 once every wave has passed this barrier; tile t + 1 goes
+                // from its registers to the other buffer while the matrix cores work on QK, and
+                // tile t + 3 is requested into the registers that frees.  The other buffer is free:
+                // it held tile t - 1, whose last read precedes every wave's arrival here.  One
+                // barrier per tile, and no wave waits for memory or for its LDS stores at it.
+                const uint32_t *cb = s_big + ST * COOP_BUF_WORDS;
+                uint32_t *nb = s_big + (ST ^ 1) * COOP_BUF_WORDS;
+                __syncthreads();
+                // The wave's two 16-row tiles are taken through the tile one after the other, in the
+                // order QK(0) QK(1) softmax(0) PV(0) softmax(1) PV(1): the matrix cores work on
+                // QK(1) and PV(0) while the vector ALU does the softmax of the other row tile.
+                typedef short v4i16 __attribute__((ext_vector_type(4)));
+                typedef v4i16 __attribute__((address_space(3))) *lds_v4i16_ptr;
+                f32x4 sacc[2][MT];
+                if (wave_active) {
+                    bf16x8 kop[4][2];
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-                *reinterpret_cast<u32x4 *>(area + 4 * (kst_pos[i & 3] + (i >> 2) * 256)) = kraw[i];
-            load_k(tile_ref(t + KS));
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    for (int kk = 0; kk < 4; ++kk) {
+                        kop[kk][0] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(cb + 4 * kld_pos[kk]));
+                        kop[kk][1] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(cb + 4 * (kld_pos[kk] + 256)));
+                    }
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        sacc[0][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                        sacc[1][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int kk = 0; kk < 4; ++kk) {
+                            sacc[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[kk][0], qreg[mt][kk], sacc[0][mt], 0, 0, 0);
+                            sacc[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[kk][1], qreg[mt][kk], sacc[1][mt], 0, 0, 0);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    *reinterpret_cast<u32x4 *>(nb + coop_kst[j]) = kraw[2 * (ST ^ 1) + j];
+                    *reinterpret_cast<u32x4 *>(nb + coop_vst[j]) = vcur[2 * (ST ^ 1) + j];
+                }
+                load_kv_coop(tile_ref(t + 3), ST ^ 1);
+                if (!wave_active) return;
+                // V^T operands by transposing LDS reads, requested now: they arrive during the first softmax
+                bf16x8 vop[8];
+#pragma unroll
+                for (int nt = 0; nt < 8; ++nt) {
+                    const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_ptr)(cb + coop_vld + nt * 8));
+                    const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_ptr)(cb + coop_vld + 16 * 72 + nt * 8));
+                    vop[nt] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                }
+                const bool masked = cur.nvalid < KT || cur.tree;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    uint32_t vis = 0xffffffffu;
+                    if (masked) {
+                        const int node_m = min(row0 + WROWS * rh + 16 * mt + lc, p.M - 1) / p.G;
+                        if (cur.tree) vis = s_anc[node_m][cur.tt];
+                        if (cur.nvalid < KT) vis &= (1u << cur.nvalid) - 1u;
+#pragma unroll
+                        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                if (!((vis >> (16 * sub + 4 * lj + i)) & 1u)) sacc[sub][mt][i] = -INFINITY;
+                    }
+                    // online softmax with a lazily raised running max (scaled, base-2 domain)
+                    const float m0 = fmaxf(fmaxf(sacc[0][mt][0], sacc[0][mt][1]), fmaxf(sacc[0][mt][2], sacc[0][mt][3]));
+                    const float m1 = fmaxf(fmaxf(sacc[1][mt][0], sacc[1][mt][1]), fmaxf(sacc[1][mt][2], sacc[1][mt][3]));
+                    const float mr = fmaxf(m0, m1);
+                    const float lmax = (mr == -INFINITY) ? -INFINITY : mr * c2;
+                    if (__any(lmax > m_used[mt] + RESCALE_GAP)) {
+                        float rm = lmax;
+                        rm = fmaxf(rm, __shfl_xor(rm, 16));
+                        rm = fmaxf(rm, __shfl_xor(rm, 32));
+                        const float m_new = fmaxf(m_used[mt], rm);
+                        const float alpha = fast_exp2(m_used[mt] - m_new);
+                        m_used[mt] = m_new;
+                        l_part[mt] *= alpha;
+#pragma unroll
+                        for (int nt = 0; nt < 8; ++nt) oacc[nt][mt] *= alpha;
+                    }
+                    float pv[8];
+#pragma unroll
+                    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) pv[4 * sub + i] = fast_exp2(fmaf(sacc[sub][mt][i], c2, -m_used[mt]));
+                    if (masked) {
+                        // also covers scale == 0, where a masked score can not be told apart by its value
+#pragma unroll
+                        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                if (!((vis >> (16 * sub + 4 * lj + i)) & 1u)) pv[4 * sub + i] = 0.f;
+                    }
+                    l_part[mt] += ((pv[0] + pv[1]) + (pv[2] + pv[3])) + ((pv[4] + pv[5]) + (pv[6] + pv[7]));
+                    const u32x4 pk = {pack_bf16(pv[0], pv[1]), pack_bf16(pv[2], pv[3]), pack_bf16(pv[4], pv[5]), pack_bf16(pv[6], pv[7])};
+                    const bf16x8 pop = __builtin_bit_cast(bf16x8, pk);
+                    // O^T[d][row] += sum_key V[key][d] P[row][key]
+#pragma unroll
+                    for (int nt = 0; nt < 8; ++nt)
+                        oacc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[nt], pop, oacc[nt][mt], 0, 0, 0);
+                }
+                return;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    *reinterpret_cast<u32x4 *>(area + 4 * (kst_pos[i & 3] + (i >> 2) * 256)) = kraw[i];
+                load_k(tile_ref(t + KS));
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
 
             // S^T[key][row] = sum_d K[key][d] Q[row][d]   (raw, the softmax scale is applied in the exponent)
             f32x4 sacc[2][MT];
@@ -467,6 +626,19 @@ void tree_attn_mfma_kernel(AttnParams p)
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
+        };
+        if (COOP) {
+            // Tiles alternate between the two register stages / LDS buffers.  The pair loop has no
+            // branch around its second half: with one, the wait for a stage's data at the top of
+            // the loop would have to cover the path on which no younger loads are in flight, that
+            // is, wait for everything.  An odd last tile is handled after the loop.
+            for (; t + 1 < t_end; t += 2) {
+                tile_step(t, std::integral_constant<int, 0>());
+                tile_step(t + 1, std::integral_constant<int, 1>());
+            }
+            if (t < t_end) tile_step(t, std::integral_constant<int, 0>());
+        } else {
+            for (; t < t_end; t += KS) tile_step(t, std::integral_constant<int, 0>());
         }
 
         // ---- epilogue: merge the key streams.  (m, l) per row through LDS; O in two halves of d:
@@ -742,17 +914,16 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
         return true;
     }
     // Kernel variant (4 waves, two workgroups per CU): 0 = 32 rows x 4 key streams for
-    // rows_per_kv <= 32, 1 = 2 x 32 rows x 2 key streams otherwise (row tiles of 64).
-    pl.row_tile = pl.rows_per_kv <= 32 ? 32 : 64;
-    pl.variant = pl.rows_per_kv <= 32 ? 0 : 1;
+    // rows_per_kv <= 32, 1 = 2 x 32 rows x 2 key streams up to 64 rows, 2 = 4 x 32 rows on one
+    // key stream with tiles shared through LDS beyond that (several row tiles per KV head:
+    // the matrix cores are the limit there, and the shared tiles cut the per-wave staging work).
+    pl.variant = pl.rows_per_kv <= 32 ? 0 : (pl.rows_per_kv <= 64 ? 1 : 2);
     {
         const int forced_variant = env_int("MCSD_ATTN_VARIANT", 0);     // 1-based, 0 / unset = automatic
-        if (forced_variant >= 1 && forced_variant <= 2) {
-            pl.variant = forced_variant - 1;
-            pl.row_tile = pl.variant == 0 ? 32 : 64;
-        }
+        if (forced_variant >= 1 && forced_variant <= 3) pl.variant = forced_variant - 1;
     }
-    const int key_streams = pl.variant == 1 ? 2 : 4;
+    pl.row_tile = 32 << pl.variant;
+    const int key_streams = 4 >> pl.variant;
     pl.n_row_tiles = (pl.rows_per_kv + pl.row_tile - 1) / pl.row_tile;
     pl.tiles_prefix_max = (d.L_stride + KT - 1) / KT;
     pl.tiles_tree = (d.N + KT - 1) / KT;
@@ -765,11 +936,11 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
 
     // Workgroups per launch if every sequence had the maximum length (the CUs hold 512 at a time).
     // More, shorter segments balance the end of the launch better but every segment of a split
-    // unit costs one fp32 partial written and read back.  Where the kernel is HBM-bound (one row
-    // tile per KV head) that traffic competes with the cache stream and 1024 measured best; where
-    // the matrix cores are the limit (several row tiles share each key stream) the partials are
-    // free and 2048 measured best.
-    const long target_wgs = env_int("MCSD_ATTN_TARGET_WGS", pl.n_row_tiles == 1 ? 1024 : 2048);
+    // unit costs one fp32 partial written and read back; 1024 measured best both where the
+    // kernel is HBM-bound (that traffic competes with the cache stream) and where the matrix
+    // cores are the limit (768 .. 1536 within 2 %; beyond that the merge kernel grows faster
+    // than the attention kernel shrinks).
+    const long target_wgs = env_int("MCSD_ATTN_TARGET_WGS", 1024);
     long chunk = (total_max * units + target_wgs - 1) / target_wgs;
     chunk = ((chunk + key_streams - 1) / key_streams) * key_streams;
     if (chunk < min_run) chunk = min_run;
@@ -832,10 +1003,12 @@ int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const
         timing_begin(K_ATTN_MFMA, stream);
         if (paged) {
             if (plan.variant == 0) hipLaunchKernelGGL((tree_attn_mfma_kernel<1, 4, true>), grid, dim3(256), 0, stream, p);
-            else hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, true>), grid, dim3(256), 0, stream, p);
+            else if (plan.variant == 1) hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, true>), grid, dim3(256), 0, stream, p);
+            else hipLaunchKernelGGL((tree_attn_mfma_kernel<4, 1, true, true>), grid, dim3(256), 0, stream, p);
         } else {
             if (plan.variant == 0) hipLaunchKernelGGL((tree_attn_mfma_kernel<1, 4, false>), grid, dim3(256), 0, stream, p);
-            else hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, false>), grid, dim3(256), 0, stream, p);
+            else if (plan.variant == 1) hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, false>), grid, dim3(256), 0, stream, p);
+            else hipLaunchKernelGGL((tree_attn_mfma_kernel<4, 1, false, true>), grid, dim3(256), 0, stream, p);
         }
         timing_end(K_ATTN_MFMA, stream);
         e = hipGetLastError();

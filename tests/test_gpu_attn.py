@@ -133,6 +133,28 @@ def test_split_factors_agree(monkeypatch):
     assert np.abs(outs[0] - outs[-1]).max() <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("variant", [1, 2, 3])
+@pytest.mark.parametrize("H_q,H_kv,kconfig", [(2, 2, (3, 2)), (8, 2, (4, 2)), (8, 1, (4, 2, 2)), (32, 4, (4, 2, 2))])
+def test_every_kernel_variant_on_every_row_count(monkeypatch, variant, H_q, H_kv, kconfig):
+    """The three matrix-core kernels (32 rows x 4 key streams, 64 x 2, 128 rows sharing one key
+    stream) forced in turn on 9, 48, 224 and 224 rows per KV head: fewer rows than one wave's
+    share, ragged last row tiles, several row tiles; ragged prefixes with poisoned padding,
+    one segment per unit and several."""
+    monkeypatch.setenv("MCSD_ATTN_VARIANT", str(variant))
+    ai = W.gen_attn_inputs(wl(H_q=H_q, H_kv=H_kv, kconfig=kconfig, prefix=(3, 700), B=3), np.random.default_rng(100 + H_q),
+                           L_stride=720)
+    nan16 = np.uint16(0x7FC0)
+    for b in range(ai.B):
+        ai.k_prefix[b, :, ai.prefix_len[b]:] = nan16
+        ai.v_prefix[b, :, ai.prefix_len[b]:] = nan16
+    ref = oracle_rows(ai)
+    for chunk in (6, 1000):
+        monkeypatch.setenv("MCSD_ATTN_CHUNK_TILES", str(chunk))
+        got = run_gpu(ai)
+        assert np.isfinite(got).all()
+        assert np.abs(got - ref).max() <= TOL["bf16"], (variant, chunk)
+
+
 def test_parent_per_sequence_and_determinism():
     ai = W.gen_attn_inputs(wl(prefix=(50, 90), B=3), np.random.default_rng(17))
     a, _ = check_full(ai, "shared parent")
