@@ -307,7 +307,8 @@ void tree_attn_mfma_kernel(AttnParams p)
         // tile unconditional, so the wait for one tile's data never has to cover the loads issued
         // after it (a load under a branch makes the compiler wait for everything outstanding).
         constexpr int OFF_NOWHERE = 0x7fff0000;
-        auto tile_ref = [&](int t) {
+        // (paged cache: blk = the block-table entry of the page the tile starts in)
+        auto tile_ref_blk = [&](int t, int blk, int row_in_page) {
             TileRef r;
             r.page_off = 0; r.paged = false;
             if (t >= t_end) {
@@ -315,13 +316,10 @@ void tree_attn_mfma_kernel(AttnParams p)
             } else if (t < tilesP) {
                 r.off = t * TILE_BYTES; r.nvalid = min(KT, L - t * KT); r.tree = false; r.tt = 0;
                 if (PAGED) {
-                    const int row = t * KT;
-                    const int page = row / p.page_size;
-                    const int blk = p.block_table[(size_t)b * p.max_pages + page];
                     if ((unsigned)blk < (unsigned)p.n_pages) {
                         r.paged = true;
                         r.off = 0;
-                        r.page_off = (((size_t)blk * p.H_kv + g) * (size_t)p.page_size + (size_t)(row % p.page_size)) * (D * 2);
+                        r.page_off = (((size_t)blk * p.H_kv + g) * (size_t)p.page_size + (size_t)row_in_page) * (D * 2);
                     } else {
                         r.off = OFF_NOWHERE;       // an entry outside the pool reads as zero keys, never as memory
                     }
@@ -331,6 +329,17 @@ void tree_attn_mfma_kernel(AttnParams p)
                 r.off = r.tt * TILE_BYTES; r.nvalid = min(KT, p.N - r.tt * KT); r.tree = true;
             }
             return r;
+        };
+        // The block table is only read by this kernel.  Through a pointer to the constant address
+        // space its (wave-uniform) entries are fetched with scalar loads wherever the read stands;
+        // through the plain pointer the compiler falls back to a vector load behind every barrier
+        // or asm statement, and the wait for that load covers all K/V requests in flight.
+        typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;
+        const const_i32_ptr block_table_c = (const_i32_ptr)(uintptr_t)p.block_table;
+        auto tile_ref = [&](int t) {
+            int blk = -1;
+            if (PAGED && t < t_end && t < tilesP) blk = block_table_c[(size_t)b * p.max_pages + (t * KT) / p.page_size];
+            return tile_ref_blk(t, blk, PAGED ? (t * KT) % p.page_size : 0);
         };
         u32x4 kraw[8];
         auto load_k = [&](const TileRef &r) {
@@ -348,6 +357,19 @@ void tree_attn_mfma_kernel(AttnParams p)
                 vcur[s] = __builtin_amdgcn_raw_buffer_load_b128(rs, v_lane_off + ((s < 4) ? 0 : 4096) + (s & 3) * 256, r.off, 0);
         };
 
+        // Paged cache, COOP: the block-table entry of a tile is read one step before the tile is
+        // requested, ahead of the workgroup barrier.  Scalar loads share the LDS counter and
+        // return out of order, so using one right after issuing it would drain every LDS read in
+        // flight; at the barrier that wait is made anyway.  The page and the row inside it of the
+        // tile that is looked up next advance by one tile per step (no division in the loop).
+        int ahead_page = 0, ahead_row = 0;          // of the tile whose entry is read next
+        int blk_ahead = -1, row_ahead = 0;          // entry and row-in-page read last
+        auto table_lookup_next = [&](int tt) {      // tt = index of that tile
+            row_ahead = ahead_row;
+            blk_ahead = (PAGED && tt < tilesP && tt < t_end) ? (int)block_table_c[(size_t)b * p.max_pages + ahead_page] : -1;
+            ahead_row += KT;
+            if (ahead_row >= p.page_size) { ahead_row = 0; ++ahead_page; }
+        };
         // COOP: this wave's quarter of both tiles (two K and two V requests)
         auto load_kv_coop = [&](const TileRef &r, const int st) {
             __amdgpu_buffer_rsrc_t rk = r.tree ? rs_ktre : rs_kpre;
@@ -364,6 +386,13 @@ void tree_attn_mfma_kernel(AttnParams p)
         };
 
         int t = t_begin + ks;
+        // (read before the first K/V requests, as inside the loop: the wait at the loop top is the
+        // longer of the two paths into it)
+        if (COOP && PAGED) {
+            ahead_page = ((t + 3) * KT) / p.page_size;
+            ahead_row = ((t + 3) * KT) % p.page_size;
+            table_lookup_next(t + 3);
+        }
         if (COOP) {
             // the first tile goes to its LDS buffer here, every later one inside the step before it;
             // requests run two to three tiles ahead of their use
@@ -399,6 +428,8 @@ void tree_attn_mfma_kernel(AttnParams p)
                 // barrier per tile, and no wave waits for memory or for its LDS stores at it.
                 const uint32_t *cb = s_big + ST * COOP_BUF_WORDS;
                 uint32_t *nb = s_big + (ST ^ 1) * COOP_BUF_WORDS;
+                const int blk_next = blk_ahead, row_next = row_ahead;
+                if (PAGED) table_lookup_next(t + 4);
                 __syncthreads();
                 // The wave's two 16-row tiles are taken through the tile one after the other, in the
                 // order QK(0) QK(1) softmax(0) PV(0) softmax(1) PV(1): the matrix cores work on
@@ -429,7 +460,7 @@ void tree_attn_mfma_kernel(AttnParams p)
                     *reinterpret_cast<u32x4 *>(nb + coop_kst[j]) = kraw[2 * (ST ^ 1) + j];
                     *reinterpret_cast<u32x4 *>(nb + coop_vst[j]) = vcur[2 * (ST ^ 1) + j];
                 }
-                load_kv_coop(tile_ref(t + 3), ST ^ 1);
+                load_kv_coop(tile_ref_blk(t + 3, blk_next, row_next), ST ^ 1);
                 if (!wave_active) return;
                 // V^T operands by transposing LDS reads, requested now: they arrive during the first softmax
                 bf16x8 vop[8];

@@ -50,6 +50,22 @@ def test_paged_batched_ragged_against_oracle_on_gathered_cache():
     assert np.abs(paged_call.out_numpy() - ref).max() <= 2e-2
 
 
+@pytest.mark.parametrize("page_size", [32, 96, 256])
+def test_paged_many_rows_per_kv_head_against_oracle(page_size):
+    """224 query rows per KV head (the kernel whose waves share each K/V tile and look the block
+    table up one step ahead), ragged prefixes, pages of one tile, three tiles (not a power of two)
+    and eight tiles; several segments per sequence and one."""
+    w = W.WORKLOADS["c4"].with_(B=3, H_q=16, H_kv=2, kconfig=(4, 2, 2), prefix=(5, 1500))
+    ai = W.gen_attn_inputs(w, np.random.default_rng(page_size), L_stride=1536)
+    tree, paged_call, table = run_both(ai, page_size, seed=page_size)
+    assert torch.equal(tree.out.view(torch.int16), paged_call.out.view(torch.int16))
+    kpool = paged_call.tensors["k_pool"].view(torch.int16).cpu().numpy().view(np.uint16)
+    vpool = paged_call.tensors["v_pool"].view(torch.int16).cpu().numpy().view(np.uint16)
+    kc, vc = O.gather_pages(kpool, table, ai.L_stride), O.gather_pages(vpool, table, ai.L_stride)
+    ref = O.tree_attn(ai.q, kc, vc, ai.prefix_len, ai.k_tree, ai.v_tree, ai.parent, ai.scale, O.BF16, n_threads=8)
+    assert np.abs(paged_call.out_numpy() - ref).max() <= 2e-2
+
+
 def test_pages_that_hold_no_valid_rows_are_never_read():
     # prefix 40 of capacity 256 with 32-token pages: only pages 0 and 1 of each sequence matter;
     # the other table entries point far outside the pool
