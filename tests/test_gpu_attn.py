@@ -139,10 +139,11 @@ def test_every_kernel_variant_on_every_row_count(monkeypatch, variant, H_q, H_kv
     """The three matrix-core kernels (32 rows x 4 key streams, 64 x 2, 128 rows sharing one key
     stream) forced in turn on 9, 48, 224 and 224 rows per KV head: fewer rows than one wave's
     share, ragged last row tiles, several row tiles; ragged prefixes with poisoned padding,
-    one segment per unit and several."""
+    one segment per unit and several; an empty prefix (tree keys only) among them."""
     monkeypatch.setenv("MCSD_ATTN_VARIANT", str(variant))
     ai = W.gen_attn_inputs(wl(H_q=H_q, H_kv=H_kv, kconfig=kconfig, prefix=(3, 700), B=3), np.random.default_rng(100 + H_q),
                            L_stride=720)
+    ai.prefix_len[:] = [0, 33, 700]         # no prefix at all, one tile and one key, many tiles
     nan16 = np.uint16(0x7FC0)
     for b in range(ai.B):
         ai.k_prefix[b, :, ai.prefix_len[b]:] = nan16
