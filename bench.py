@@ -318,7 +318,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build measures one GPU only (got --gpus {args.gpus}); the path shards by "
-              "sequence / KV head without any exchange, see DESIGN.md", file=sys.stderr)
+              "sequence / KV head without any exchange", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2401_06706_amd import binding as M
