@@ -321,7 +321,8 @@ int32_t mcsd_verify_step(const mcsd_attn_desc *ad, const mcsd_attn_bufs *ab, con
     rc = check_verify(vd, vb);
     if (rc != MCSD_OK) return rc;
     // The merge of the attention partials and the walk are the two small tail kernels of the step;
-    // when the attention is split they go out as one launch after the verification rows.
+    // when the attention is split they go out as one launch after the verification rows, and when
+    // it is not, the walk rides on the attention launch, which then follows the verification rows.
     if (plan.use_mfma && plan.n_chunks_max > 1) {
         rc = launch_tree_attn(*ad, *ab, plan, (hipStream_t)stream, nullptr, ATTN_PHASE_MAIN);
         if (rc != MCSD_OK) return rc;
@@ -329,6 +330,13 @@ int32_t mcsd_verify_step(const mcsd_attn_desc *ad, const mcsd_attn_bufs *ab, con
         if (rc != MCSD_OK) return rc;
         const WalkParams w = make_walk_params(*vd, *vb);
         return launch_tree_attn(*ad, *ab, plan, (hipStream_t)stream, nullptr, ATTN_PHASE_COMBINE, &w);
+    }
+    if (plan.use_mfma) {
+        // no merge launch: the verification rows go first and the attention launch carries the walk
+        rc = launch_verify(*vd, *vb, (hipStream_t)stream, false);
+        if (rc != MCSD_OK) return rc;
+        const WalkParams w = make_walk_params(*vd, *vb);
+        return launch_tree_attn(*ad, *ab, plan, (hipStream_t)stream, nullptr, ATTN_PHASE_MAIN, &w);
     }
     rc = launch_tree_attn(*ad, *ab, plan, (hipStream_t)stream);
     if (rc != MCSD_OK) return rc;

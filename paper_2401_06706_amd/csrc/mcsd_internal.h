@@ -66,8 +66,9 @@ struct AttnPlan {
 
 bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan);
 // phases: the attention kernel, and the merge of the split partials (needed iff
-// plan.n_chunks_max > 1).  The merge launch can carry the walk of a verification that ran
-// before it on the same stream (tail_walk), which saves a step one kernel launch.
+// plan.n_chunks_max > 1).  The last launch of the attention (the merge, or the matrix-core
+// kernel itself when nothing is split) can carry the walk of a verification that ran before
+// it on the same stream (tail_walk), which saves a step one kernel launch.
 enum { ATTN_PHASE_MAIN = 1, ATTN_PHASE_COMBINE = 2, ATTN_PHASE_ALL = 3 };
 int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const AttnPlan &plan,
                          hipStream_t stream, const mcsd_paged_kv *paged = nullptr, int phases = ATTN_PHASE_ALL,

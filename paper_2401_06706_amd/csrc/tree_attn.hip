@@ -143,9 +143,19 @@ __device__ __forceinline__ void build_ancestor_masks(const int32_t *parent, int 
 // per KV head).
 template <int RH, int KS, bool PAGED, bool COOP = false>
 __global__ __launch_bounds__(RH * KS * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void tree_attn_mfma_kernel(AttnParams p)
+void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
 {
     static_assert(!COOP || (KS == 1 && RH == 4), "the shared-tile scheme splits a tile over four waves of one key stream");
+    // Rows of workgroups appended to the grid along y carry the walk of a verification that ran
+    // before this launch on the same stream (one thread per sequence), when the caller asked for
+    // that: a step whose attention needs no merge launch then has no launch for the walk either.
+    if ((int)blockIdx.y >= p.n_chunks_max * p.n_row_tiles) {
+        if (blockIdx.x == 0 && blockIdx.z == 0) {
+            const int wb = ((int)blockIdx.y - p.n_chunks_max * p.n_row_tiles) * (RH * KS * 64) + (int)threadIdx.x;
+            if (wb < w.B) walk_sequence(w, wb);
+        }
+        return;
+    }
     constexpr int MT = 2;                   // 16-row MFMA tiles per wave
     constexpr int NW = RH * KS;
     constexpr int NT = NW * 64;
@@ -987,7 +997,7 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
     } else {
         pl.ws_bytes = 0;
     }
-    if ((long)pl.n_chunks_max * pl.n_row_tiles > 65535L || d.B > 65535) return false;
+    if ((long)pl.n_chunks_max * pl.n_row_tiles + 256L > 65535L || d.B > 65535) return false;     // (+ rows that may carry a walk)
     *plan = pl;
     return true;
 }
@@ -1030,16 +1040,20 @@ int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const
         p.part_l = p.part_m + rows;
     }
     if (phases & ATTN_PHASE_MAIN) {
-        const dim3 grid(d.H_kv, plan.n_chunks_max * plan.n_row_tiles, d.B);
+        // an unsplit attention has no merge launch to carry the walk: it rides on this one
+        WalkParams mw = {};
+        int walk_rows = 0;
+        if (tail_walk && plan.n_chunks_max == 1) { mw = *tail_walk; walk_rows = (mw.B + 255) / 256; }
+        const dim3 grid(d.H_kv, plan.n_chunks_max * plan.n_row_tiles + walk_rows, d.B);
         timing_begin(K_ATTN_MFMA, stream);
         if (paged) {
-            if (plan.variant == 0) hipLaunchKernelGGL((tree_attn_mfma_kernel<1, 4, true>), grid, dim3(256), 0, stream, p);
-            else if (plan.variant == 1) hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, true>), grid, dim3(256), 0, stream, p);
-            else hipLaunchKernelGGL((tree_attn_mfma_kernel<4, 1, true, true>), grid, dim3(256), 0, stream, p);
+            if (plan.variant == 0) hipLaunchKernelGGL((tree_attn_mfma_kernel<1, 4, true>), grid, dim3(256), 0, stream, p, mw);
+            else if (plan.variant == 1) hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, true>), grid, dim3(256), 0, stream, p, mw);
+            else hipLaunchKernelGGL((tree_attn_mfma_kernel<4, 1, true, true>), grid, dim3(256), 0, stream, p, mw);
         } else {
-            if (plan.variant == 0) hipLaunchKernelGGL((tree_attn_mfma_kernel<1, 4, false>), grid, dim3(256), 0, stream, p);
-            else if (plan.variant == 1) hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, false>), grid, dim3(256), 0, stream, p);
-            else hipLaunchKernelGGL((tree_attn_mfma_kernel<4, 1, false, true>), grid, dim3(256), 0, stream, p);
+            if (plan.variant == 0) hipLaunchKernelGGL((tree_attn_mfma_kernel<1, 4, false>), grid, dim3(256), 0, stream, p, mw);
+            else if (plan.variant == 1) hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, false>), grid, dim3(256), 0, stream, p, mw);
+            else hipLaunchKernelGGL((tree_attn_mfma_kernel<4, 1, false, true>), grid, dim3(256), 0, stream, p, mw);
         }
         timing_end(K_ATTN_MFMA, stream);
         e = hipGetLastError();

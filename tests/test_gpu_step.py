@@ -32,6 +32,27 @@ def test_verify_step_matches_separate_calls_and_oracle():
     compare_verify(vi, r1, run_oracle(vi, want_residual=True), check_residual=True, label="step")
 
 
+@pytest.mark.parametrize("B", [1, 300])
+def test_verify_step_with_unsplit_attention_equals_separate_calls(B):
+    """Short prefixes: the attention is not split, so the step has no merge launch and the walk
+    rides on the attention launch (more than 256 sequences: more than one row of walk blocks)."""
+    w = W.WORKLOADS["c2"].with_(B=B, H_q=2, H_kv=2, prefix=(0, 90), V=512, kconfig=(3, 2, 1), n_greedy=B // 3)
+    ai, vi = W.gen_attn_inputs(w), W.gen_verify_inputs(w)
+    a1, v1 = D.make_attn_call(ai), D.make_verify_call(vi)
+    M.mcsd_verify_step(a1.args, v1.args)
+    torch.cuda.synchronize()
+    a2, v2 = D.make_attn_call(ai), D.make_verify_call(vi)
+    M.mcsd_tree_attn(a2.args)
+    M.mcsd_verify_sample(v2.args)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(a1.out_numpy(), a2.out_numpy())
+    r1, r2 = v1.results(), v2.results()
+    for k in r1:
+        np.testing.assert_array_equal(r1[k], r2[k], err_msg=k)
+    assert (r1["n_accepted"] >= 0).all()           # written by the walk (the buffers start at -7)
+    compare_verify(vi, r1, run_oracle(vi), label=f"unsplit step B={B}")
+
+
 def test_verify_step_rejects_bad_half_without_running_the_other():
     w = W.WORKLOADS["c1"]
     ai, vi = W.gen_attn_inputs(w), W.gen_verify_inputs(w)
@@ -61,14 +82,23 @@ def test_kernel_timing_counts_launches():
     assert all(ms > 0 for ms, n in t.values() if n)
     M.mcsd_verify_step(a.args, v.args)             # timing off again: nothing recorded
     assert M.mcsd_kernel_timing_read()["verify_rows"][1] == 3
-    # an attention that is not split keeps the separate walk launch
+    # an attention that is not split has no merge launch; the walk then rides on the attention launch
     w1 = W.WORKLOADS["c2"].with_(prefix=(64, 64))
     a1, v1 = D.make_attn_call(W.gen_attn_inputs(w1)), D.make_verify_call(W.gen_verify_inputs(w1))
     M.mcsd_kernel_timing(True)
     M.mcsd_verify_step(a1.args, v1.args)
     t1 = M.mcsd_kernel_timing_read()
     M.mcsd_kernel_timing(False)
-    assert t1["walk"][1] == 1 and t1["tree_attn_combine"][1] == 0
+    assert t1["walk"][1] == 0 and t1["tree_attn_combine"][1] == 0
+    assert t1["tree_attn_mfma"][1] == 1 and t1["verify_rows"][1] == 1
+    # the fp32 path (no matrix-core kernel) keeps the walk launch of its own
+    w2 = W.WORKLOADS["c1"]
+    a2, v2 = D.make_attn_call(W.gen_attn_inputs(w2)), D.make_verify_call(W.gen_verify_inputs(w2))
+    M.mcsd_kernel_timing(True)
+    M.mcsd_verify_step(a2.args, v2.args)
+    t2 = M.mcsd_kernel_timing_read()
+    M.mcsd_kernel_timing(False)
+    assert t2["walk"][1] == 1 and t2["tree_attn_generic"][1] == 1
 
 
 def test_long_prefix_sampled_against_oracle():
