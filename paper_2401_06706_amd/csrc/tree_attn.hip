@@ -788,25 +788,35 @@ __global__ __launch_bounds__(256) void tree_attn_combine_kernel(AttnParams p, in
     const size_t base = (((size_t)b * p.H_kv + g) * p.n_chunks_max) * (size_t)p.R + r;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     float ls = 0.f;
-    if (n_chunks <= 4) {
-        // the usual case: every load is issued before the first use, one memory round trip
-        float mc[4], lc[4];
-        f32x4 oc[4];
+    // Up to eight chunks (the usual case) every load is issued before the first use: one memory
+    // round trip instead of one per chunk.  Slots past n_chunks re-read chunk 0 (a cache hit) with
+    // weight zero, so the loads stay unconditional; two sizes keep that waste below a factor of two.
+    auto merge_upfront = [&](auto maxc) __attribute__((always_inline)) {
+        constexpr int MAXC = decltype(maxc)::value;
+        float mc[MAXC], lc[MAXC];
+        f32x4 oc[MAXC];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
+        for (int c = 0; c < MAXC; ++c) {
             const bool on = c < n_chunks;
             const size_t u = base + (size_t)(on ? c : 0) * p.R;
             mc[c] = on ? p.part_m[u] : M_INIT;
             lc[c] = on ? p.part_l[u] : 0.f;
             oc[c] = *reinterpret_cast<const f32x4 *>(p.part_o + u * D + 4 * d4);
         }
-        const float ms = fmaxf(fmaxf(mc[0], mc[1]), fmaxf(mc[2], mc[3]));
+        float ms = mc[0];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
+        for (int c = 1; c < MAXC; ++c) ms = fmaxf(ms, mc[c]);
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) {
             const float fsc = (c < n_chunks) ? exp2f(mc[c] - ms) : 0.f;
             ls += fsc * lc[c];
             acc += fsc * oc[c];
         }
+    };
+    if (n_chunks <= 4) {
+        merge_upfront(std::integral_constant<int, 4>());
+    } else if (n_chunks <= 8) {
+        merge_upfront(std::integral_constant<int, 8>());
     } else {
         float ms = M_INIT;
         for (int c = 0; c < n_chunks; ++c) ms = fmaxf(ms, p.part_m[base + (size_t)c * p.R]);
