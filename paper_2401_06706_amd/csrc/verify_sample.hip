@@ -202,11 +202,14 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
         int bi = 0x7fffffff;
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
-            int e = 4 * (t + VT * i);
+            // A thread meets its elements in ascending token order and the row was padded with
+            // -inf past V when it was loaded: a strict comparison keeps the first of equal
+            // values, and no bounds check is needed.
+            const int e = 4 * (t + VT * i);
             const float v[4] = {a[i].x, a[i].y, a[i].z, a[i].w};
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-                if (e + c < V && (v[c] > bv || (v[c] == bv && e + c < bi))) { bv = v[c]; bi = e + c; }
+                if (v[c] > bv) { bv = v[c]; bi = e + c; }
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
