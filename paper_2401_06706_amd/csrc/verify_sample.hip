@@ -197,7 +197,9 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     }
 
     if (T == 0.f) {
-        // argmax sampling: lowest id on ties
+        // argmax sampling: lowest id on ties.  Thread c fetches the token of child c now, so that
+        // the comparison after the scan does not wait for memory.
+        const int my_tok = (t < k) ? p.cand_tok[(size_t)b * N + s_kids[t]] : -1;
         float bv = -INFINITY;
         int bi = 0x7fffffff;
 #pragma unroll
@@ -211,22 +213,20 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
             for (int c = 0; c < 4; ++c)
                 if (v[c] > bv) { bv = v[c]; bi = e + c; }
         }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            float ov = __shfl_xor(bv, o);
-            int oi = __shfl_xor(bi, o);
-            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-        }
+        wave_argmax(bv, bi);
         if (lane == 0) { s_bestv[wave] = bv; s_besti[wave] = bi; }
+        if (t == 0) s_int[0] = 0x7fffffff;
         __syncthreads();
         bv = s_bestv[0]; bi = s_besti[0];
         for (int w = 1; w < NWAVES; ++w)
             if (s_bestv[w] > bv || (s_bestv[w] == bv && s_besti[w] < bi)) { bv = s_bestv[w]; bi = s_besti[w]; }
         if (bi == 0x7fffffff) bi = 0;
+        // the first child (ascending node id) that proposed the argmax is accepted
+        if (t < k && my_tok == bi) atomicMin(&s_int[0], t);
+        __syncthreads();
         if (t == 0) {
-            int acc = -1;
-            for (int i = 0; i < k && acc < 0; ++i)
-                if (p.cand_tok[(size_t)b * N + s_kids[i]] == bi) acc = s_kids[i];
+            const int c = s_int[0];
+            const int acc = (c < k) ? s_kids[c] : -1;
             p.acc_child[rix] = acc;
             p.endpoint[rix] = acc < 0 ? bi : -1;
             p.flags[rix] = s_flags;

@@ -44,6 +44,27 @@ __device__ __forceinline__ float wave_max(float v)      // valid in lane 63
     return v;
 }
 
+__device__ __forceinline__ int wave_min(int v)           // valid in lane 63
+{
+    v = min(v, __builtin_amdgcn_update_dpp(v, v, DPP_QUAD_1032, 0xf, 0xf, false));
+    v = min(v, __builtin_amdgcn_update_dpp(v, v, DPP_QUAD_2301, 0xf, 0xf, false));
+    v = min(v, __builtin_amdgcn_update_dpp(v, v, DPP_ROW_HALF_MIRROR, 0xf, 0xf, false));
+    v = min(v, __builtin_amdgcn_update_dpp(v, v, DPP_ROW_MIRROR, 0xf, 0xf, false));
+    v = min(v, __builtin_amdgcn_update_dpp(v, v, DPP_ROW_BCAST15, 0xa, 0xf, false));
+    v = min(v, __builtin_amdgcn_update_dpp(v, v, DPP_ROW_BCAST31, 0xc, 0xf, false));
+    return v;
+}
+
+// Largest value of the wavefront and the lowest index among the lanes that hold it, in every
+// lane: two DPP reductions and two lane reads instead of six rounds of cross-lane shuffles.
+__device__ __forceinline__ void wave_argmax(float &bv, int &bi)
+{
+    const float m = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wave_max(bv)), 63));
+    const int i = wave_min(bv == m ? bi : 0x7fffffff);
+    bv = m;
+    bi = __builtin_amdgcn_readlane(i, 63);
+}
+
 __device__ __forceinline__ double wave_sum(double v)    // valid in lane 63
 {
     v += dpp_d<DPP_QUAD_1032, 0xf>(0.0, v);
