@@ -39,7 +39,7 @@ __global__ __launch_bounds__(VT) void draft_rows_kernel(DraftParams p)
     const int N = p.N, V = p.V;
 
     __shared__ double s_red[NWAVES];
-    __shared__ double s_seg[NWAVES * ITEMS];
+    __shared__ double s_seg[4 * NWAVES * ITEMS];
     __shared__ double s_tot[ITEMS];
     __shared__ float s_redf[NWAVES];
     __shared__ unsigned long long s_mask[2];

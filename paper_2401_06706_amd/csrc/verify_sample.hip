@@ -79,7 +79,7 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
 
     __shared__ double s_red[NWAVES];
     __shared__ double s_red2[NWAVES];
-    __shared__ double s_seg[NWAVES * ITEMS + ITEMS];
+    __shared__ double s_seg[4 * NWAVES * ITEMS + ITEMS];
     __shared__ float s_redf[NWAVES];
     __shared__ float s_redf2[NWAVES];
     __shared__ unsigned long long s_mask[2];

@@ -7,6 +7,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "mcsd.h"
 
 namespace mcsd {
@@ -31,7 +33,8 @@ __device__ __forceinline__ double dpp_d(double old, double v)
 }
 
 constexpr int DPP_QUAD_1032 = 0xB1, DPP_QUAD_2301 = 0x4E, DPP_ROW_HALF_MIRROR = 0x141, DPP_ROW_MIRROR = 0x140,
-              DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143;
+              DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143,
+              DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, DPP_ROW_SHR8 = 0x118;
 
 __device__ __forceinline__ float wave_max(float v)      // valid in lane 63
 {
@@ -74,6 +77,55 @@ __device__ __forceinline__ double wave_sum(double v)    // valid in lane 63
     v += dpp_d<DPP_ROW_BCAST15, 0xa>(0.0, v);
     v += dpp_d<DPP_ROW_BCAST31, 0xc>(0.0, v);
     return v;
+}
+
+// Inclusive running sum over the lanes of the wavefront: shifts inside the rows of 16 lanes
+// (a lane without a source adds zero), then the totals of the rows before it.
+__device__ __forceinline__ double wave_scan_inclusive(double v)
+{
+    v += dpp_d<DPP_ROW_SHR1, 0xf>(0.0, v);
+    v += dpp_d<DPP_ROW_SHR2, 0xf>(0.0, v);
+    v += dpp_d<DPP_ROW_SHR4, 0xf>(0.0, v);
+    v += dpp_d<DPP_ROW_SHR8, 0xf>(0.0, v);
+    v += dpp_d<DPP_ROW_BCAST15, 0xa>(0.0, v);
+    v += dpp_d<DPP_ROW_BCAST31, 0xc>(0.0, v);
+    return v;
+}
+
+// ITEMS values per lane -> for every row of 16 lanes, the 16-lane total of each of the ITEMS
+// values, spread over the lanes of that row: lane l ends up with the total of value number
+// `which`.  Each of the first log2(ITEMS) steps halves the values a lane carries: the partner
+// (whose lane number differs in the step's bit) gets the half this lane gives up, and this lane
+// adds the partner's copy of the half it keeps.  15 exchanges for 16 values instead of 16 x 4.
+template <int ITEMS>
+__device__ __forceinline__ double row_totals_scattered(double (&x)[ITEMS], int lane, int &which)
+{
+    static_assert(ITEMS == 1 || ITEMS == 2 || ITEMS == 4 || ITEMS == 8 || ITEMS == 16, "power of two up to 16");
+    which = 0;
+    auto step = [&](auto ctrl_c, auto n_c, int bit) __attribute__((always_inline)) {
+        constexpr int CTRL = decltype(ctrl_c)::value;
+        constexpr int N = decltype(n_c)::value;          // values carried before this step
+        if constexpr (N > 1) {
+            const bool keep_hi = (lane >> bit) & 1;
+#pragma unroll
+            for (int j = 0; j < N / 2; ++j) {
+                const double mine = keep_hi ? x[j + N / 2] : x[j];
+                const double give = keep_hi ? x[j] : x[j + N / 2];
+                x[j] = mine + dpp_d<CTRL, 0xf>(0.0, give);
+            }
+            if (keep_hi) which += N / 2;
+        } else {
+            x[0] += dpp_d<CTRL, 0xf>(0.0, x[0]);
+        }
+    };
+    // Widest exchange first: the row mirror (lane i <-> 15 - i) flips bit 3, and every later
+    // exchange (mirror inside 8 lanes, lanes 2 apart, neighbours) leaves the bits of the earlier
+    // steps alone, so the two partners of a step always carry the same subset of the values.
+    step(std::integral_constant<int, DPP_ROW_MIRROR>(), std::integral_constant<int, ITEMS>(), 3);
+    step(std::integral_constant<int, DPP_ROW_HALF_MIRROR>(), std::integral_constant<int, (ITEMS > 1 ? ITEMS / 2 : 1)>(), 2);
+    step(std::integral_constant<int, DPP_QUAD_2301>(), std::integral_constant<int, (ITEMS > 2 ? ITEMS / 4 : 1)>(), 1);
+    step(std::integral_constant<int, DPP_QUAD_1032>(), std::integral_constant<int, (ITEMS > 4 ? ITEMS / 8 : 1)>(), 0);
+    return x[0];
 }
 
 // Every thread returns the same value (fixed summation order over the waves).
@@ -222,24 +274,25 @@ __device__ __forceinline__ void store_row_scaled(float *dst, int V, const float4
 // the segment that holds the crossing.  fp64 throughout.
 //
 // cdf_segments prepares level (1): s_tot[i] = the total of segment i (four-token sums of the
-// threads, added up per wave and then over the waves in a fixed order).  cdf_search does the
-// rest and may be called repeatedly on the same prepared state; a caller that removes a token
-// between searches keeps s_tot and A in step itself.
+// threads, added up per row of 16 lanes and then over the rows and waves in a fixed order).
+// cdf_search does the rest and may be called repeatedly on the same prepared state; a caller
+// that removes a token between searches keeps s_tot and A in step itself.
+// s_seg holds 4 (VT / 64) ITEMS doubles.
 template <int ITEMS, int VT>
 __device__ __forceinline__ void cdf_segments(const float4 (&a)[ITEMS], double *s_seg, double *s_tot)
 {
-    constexpr int NWAVES = VT / 64;
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    constexpr int NROWS = VT / 16;
+    const int t = threadIdx.x, lane = t & 63;
+    double x[ITEMS];
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-        const double w = wave_sum(sum4(a[i]));
-        if (lane == 63) s_seg[wave * ITEMS + i] = w;
-    }
+    for (int i = 0; i < ITEMS; ++i) x[i] = sum4(a[i]);
+    int which;
+    const double w = row_totals_scattered<ITEMS>(x, lane, which);
+    s_seg[(t >> 4) * ITEMS + which] = w;     // (with fewer than 16 values several lanes of a row store the same total)
     __syncthreads();
     if (t < ITEMS) {
         double tot = 0.0;
-#pragma unroll
-        for (int w = 0; w < NWAVES; ++w) tot += s_seg[w * ITEMS + t];
+        for (int r = 0; r < NROWS; ++r) tot += s_seg[r * ITEMS + t];
         s_tot[t] = tot;
     }
     __syncthreads();
@@ -268,12 +321,7 @@ __device__ __forceinline__ int cdf_search(const float4 (&a)[ITEMS], double A, do
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i)
             if (i == istar) mine = a[i];
-        double incl = sum4(mine);
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            double n = __shfl_up(incl, o);
-            if (lane >= o) incl += n;
-        }
+        const double incl = wave_scan_inclusive(sum4(mine));
         if (lane == 63) s_red[wave] = incl;
         __syncthreads();
         double woff = base;
@@ -323,12 +371,12 @@ __device__ __forceinline__ int cdf_search(const float4 (&a)[ITEMS], double A, do
     return token;
 }
 
-// One-shot form: s_seg holds (VT / 64) * ITEMS + ITEMS doubles.
+// One-shot form: s_seg holds 4 (VT / 64) ITEMS + ITEMS doubles.
 template <int ITEMS, int VT>
 __device__ __forceinline__ int inverse_cdf(const float4 (&a)[ITEMS], double A, double u, double eps,
                                            double *s_red, double *s_seg, int *s_int, uint32_t *flag_bits)
 {
-    double *s_tot = s_seg + (VT / 64) * ITEMS;
+    double *s_tot = s_seg + 4 * (VT / 64) * ITEMS;
     cdf_segments<ITEMS, VT>(a, s_seg, s_tot);
     return cdf_search<ITEMS, VT>(a, A, u, eps, s_red, s_tot, s_int, flag_bits);
 }
