@@ -239,6 +239,20 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
         return;
     }
 
+    // Thread c follows candidate c: its token, its uniform and the two logits of that token are
+    // requested now, so that the first accept decision does not wait for three dependent trips
+    // to memory after the exponentials.
+    int my_tok = -1;
+    float my_u = 0.f, my_zp = 0.f, my_zq = 0.f;
+    if (k > 0 && !naive && t < k) {
+        const int node = s_kids[t];
+        my_tok = p.cand_tok[(size_t)b * N + node];
+        my_u = p.u_accept[(size_t)b * N + node];
+        if (my_tok >= 0 && my_tok < V) {
+            my_zp = zp_row[my_tok];
+            my_zq = zq_row[my_tok];
+        }
+    }
     const float invT = 1.0f / T;
     const float c2 = invT * LOG2E_F;
     float mp = row_max<ITEMS>(a), mq = row_max<ITEMS>(eq);
@@ -253,18 +267,11 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     int accepted = -1;
     if (k > 0 && !naive) {
         // fp64 track of the candidate tokens: thread c follows candidate c
-        int my_tok = -1;
         double my_a = 0.0, my_q = 0.0;
-        float my_u = 0.f;
-        if (t < k) {
-            const int node = s_kids[t];
-            my_tok = p.cand_tok[(size_t)b * N + node];
-            my_u = p.u_accept[(size_t)b * N + node];
-            if (my_tok >= 0 && my_tok < V) {
-                // same constants as the vector pass (float c2), evaluated exactly
-                my_a = exp2_neg(((double)zp_row[my_tok] - (double)mp) * (double)c2);
-                my_q = exp2_neg(((double)zq_row[my_tok] - (double)mq) * (double)c2);
-            }
+        if (t < k && my_tok >= 0 && my_tok < V) {
+            // same constants as the vector pass (float c2), evaluated exactly
+            my_a = exp2_neg(((double)my_zp - (double)mp) * (double)c2);
+            my_q = exp2_neg(((double)my_zq - (double)mq) * (double)c2);
         }
         // Z_q: mass of the draft tokens not yet removed.  After a removal it is summed
         // again over the resident row rather than updated by subtraction, so that it
