@@ -95,7 +95,20 @@ __global__ __launch_bounds__(VT) void draft_rows_kernel(DraftParams p)
     }
 
     if (T == 0.f) {
+        // largest value of the workgroup and the lowest token id that holds it, in every thread
+        auto block_argmax = [&](float &bv, int &bi) __attribute__((always_inline)) {
+            wave_argmax(bv, bi);
+            if (lane == 0) { s_bestv[wave] = bv; s_besti[wave] = bi; }
+            __syncthreads();
+            bv = s_bestv[0]; bi = s_besti[0];
+            for (int w = 1; w < NWAVES; ++w)
+                if (s_bestv[w] > bv || (s_bestv[w] == bv && s_besti[w] < bi)) { bv = s_bestv[w]; bi = s_besti[w]; }
+            __syncthreads();
+        };
         for (int i = 0; i < k; ++i) {
+            // A thread meets its elements in ascending token order, so a strict comparison keeps
+            // the lowest id among equal values; it never picks a logit of -inf (nor the -inf
+            // padding past V), which is only right while something finite is left ...
             float bv = -INFINITY;
             int bi = 0x7fffffff;
 #pragma unroll
@@ -104,20 +117,23 @@ __global__ __launch_bounds__(VT) void draft_rows_kernel(DraftParams p)
                 const float v[4] = {a[j].x, a[j].y, a[j].z, a[j].w};
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
-                    if (e + c < V && (v[c] > bv || (v[c] == bv && e + c < bi))) { bv = v[c]; bi = e + c; }
+                    if (v[c] > bv) { bv = v[c]; bi = e + c; }
             }
+            block_argmax(bv, bi);
+            if (bi == 0x7fffffff) {
+                // ... otherwise (every thread sees the same result) the scan is repeated with
+                // -inf allowed to win, inside the row only
+                bv = -INFINITY;
 #pragma unroll
-            for (int o = 32; o > 0; o >>= 1) {
-                const float ov = __shfl_xor(bv, o);
-                const int oi = __shfl_xor(bi, o);
-                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+                for (int j = 0; j < ITEMS; ++j) {
+                    const int e = 4 * (t + VT * j);
+                    const float v[4] = {a[j].x, a[j].y, a[j].z, a[j].w};
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (e + c < V && (v[c] > bv || (v[c] == bv && e + c < bi))) { bv = v[c]; bi = e + c; }
+                }
+                block_argmax(bv, bi);
             }
-            if (lane == 0) { s_bestv[wave] = bv; s_besti[wave] = bi; }
-            __syncthreads();
-            bv = s_bestv[0]; bi = s_besti[0];
-            for (int w = 1; w < NWAVES; ++w)
-                if (s_bestv[w] > bv || (s_bestv[w] == bv && s_besti[w] < bi)) { bv = s_bestv[w]; bi = s_besti[w]; }
-            __syncthreads();
             // nothing comparable left (only NaN logits remain): reported, token 0 handed out
             const bool none = (bi == 0x7fffffff);
             if (none) bi = 0;
