@@ -9,10 +9,12 @@
 //
 // Work decomposition (bf16, d = 128: tree_attn_mfma_kernel)
 //   keys of a sequence = ceil(L/32) prefix tiles followed by ceil(N/32) tree tiles
-//   unit      = (sequence b, KV head g, tile of 32/64 query rows)
+//   unit      = (sequence b, KV head g, tile of 32/64/128 query rows)
 //   segment   = a run of consecutive key tiles of a unit, processed by one workgroup
 //               (4 waves): wave (rh, ks) owns 32 rows and every KS-th tile of the run and
-//               runs an independent online softmax with no workgroup barrier in the loop.
+//               runs an independent online softmax with no workgroup barrier in the loop
+//               (32- and 64-row tiles), or four waves of 32 rows walk one key stream together
+//               and share every tile through LDS (128-row tiles, more than 64 rows per KV head).
 //   The T tiles of a unit are cut into round(T / chunk_tiles) equal segments (at least one):
 //   grid (KV head, segment x row tile, sequence).  The (sequence, segment) pairs are handed
 //   out longest first.  A segment that covers its whole unit writes the output rows itself;
