@@ -76,6 +76,15 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *ptr, uin
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(ptr), 0, bytes, 0x00020000);
 }
 
+// max(a, b, c) as the one hardware instruction: fmaxf() on values the compiler knows nothing
+// about (MFMA results) costs an extra NaN-quieting v_max_f32 x, x per operand.
+__device__ __forceinline__ float max3_raw(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 __device__ __forceinline__ float fast_exp2(float x)
 {
     return __builtin_amdgcn_exp2f(x);      // v_exp_f32; results below the normal range flush to 0
@@ -498,9 +507,9 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
                                 if (!((vis >> (16 * sub + 4 * lj + i)) & 1u)) sacc[sub][mt][i] = -INFINITY;
                     }
                     // online softmax with a lazily raised running max (scaled, base-2 domain)
-                    const float m0 = fmaxf(fmaxf(sacc[0][mt][0], sacc[0][mt][1]), fmaxf(sacc[0][mt][2], sacc[0][mt][3]));
-                    const float m1 = fmaxf(fmaxf(sacc[1][mt][0], sacc[1][mt][1]), fmaxf(sacc[1][mt][2], sacc[1][mt][3]));
-                    const float mr = fmaxf(m0, m1);
+                    const float m0 = max3_raw(sacc[0][mt][0], sacc[0][mt][1], sacc[0][mt][2]);
+                    const float m1 = max3_raw(sacc[0][mt][3], sacc[1][mt][0], sacc[1][mt][1]);
+                    const float mr = max3_raw(max3_raw(m0, m1, sacc[1][mt][2]), sacc[1][mt][3], sacc[1][mt][3]);
                     const float lmax = (mr == -INFINITY) ? -INFINITY : mr * c2;
                     if (__any(lmax > m_used[mt] + RESCALE_GAP)) {
                         float rm = lmax;
@@ -592,9 +601,9 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
             float lmax[MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                float m0 = fmaxf(fmaxf(sacc[0][mt][0], sacc[0][mt][1]), fmaxf(sacc[0][mt][2], sacc[0][mt][3]));
-                float m1 = fmaxf(fmaxf(sacc[1][mt][0], sacc[1][mt][1]), fmaxf(sacc[1][mt][2], sacc[1][mt][3]));
-                const float mr = fmaxf(m0, m1);
+                const float m0 = max3_raw(sacc[0][mt][0], sacc[0][mt][1], sacc[0][mt][2]);
+                const float m1 = max3_raw(sacc[0][mt][3], sacc[1][mt][0], sacc[1][mt][1]);
+                const float mr = max3_raw(max3_raw(m0, m1, sacc[1][mt][2]), sacc[1][mt][3], sacc[1][mt][3]);
                 lmax[mt] = (mr == -INFINITY) ? -INFINITY : mr * c2;
                 raise |= lmax[mt] > m_used[mt] + RESCALE_GAP;
             }
