@@ -1,5 +1,5 @@
 """Randomly drawn (seeded) shapes within the documented limits: tree attention (contiguous and
-paged) and verification against the oracle.  The draws cover what the hand-picked cases may
+paged) and verification against the oracle, and the fused step against the separate calls.  The draws cover what the hand-picked cases may
 miss: odd head ratios, trees of every size, prefixes around tile and page edges, every kernel
 variant the launch plan picks by itself."""
 import numpy as np
@@ -69,3 +69,11 @@ def test_random_shape(seed):
     M.mcsd_verify_sample(vcall.args)
     torch.cuda.synchronize()
     compare_verify(vi, vcall.results(), run_oracle(vi), label=f"random {seed}")
+    # the fused step (whichever launch carries the walk for this shape) gives the same bits
+    a2, v2 = D.make_attn_call(ai), D.make_verify_call(vi, want_ratio=True)
+    M.mcsd_verify_step(a2.args, v2.args)
+    torch.cuda.synchronize()
+    assert torch.equal(call.out.view(torch.int16), a2.out.view(torch.int16))
+    r1, r2 = vcall.results(), v2.results()
+    for k in r1:
+        np.testing.assert_array_equal(r1[k], r2[k], err_msg=f"step vs separate calls: {k}")
