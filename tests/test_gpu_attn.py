@@ -1,8 +1,9 @@
 """GPU parity of mcsd_tree_attn (through the C ABI) against the CPU oracle.
 
-Tolerances: 2e-2 abs for bf16 storage (inputs are N(0,1); outputs are convex
-combinations of V rows, so |out| <= max|V| ~ 5 and a bf16 output ulp is up to
-1.6e-2), 1e-5 abs for fp32.
+Every comparison goes through tests.parity.assert_attn_close: the stated absolute tolerance
+(2e-2 for bf16 storage, 1e-5 for fp32) AND a bar scaled to the reference (largest error against
+max|ref|, RMS error against RMS(ref)), because long-prefix outputs are far smaller than 2e-2.
+The five named workloads are compared in full, every row of every sequence and head.
 """
 import numpy as np
 import pytest
@@ -12,15 +13,14 @@ from oracle import mcsd_oracle as O
 from paper_2401_06706_amd import binding as M
 from paper_2401_06706_amd import device as D
 from paper_2401_06706_amd import workloads as W
+from tests.parity import ATTN_REL, assert_attn_close
 
 pytestmark = pytest.mark.gpu
-
-TOL = {"fp32": 1e-5, "bf16": 2e-2}
 
 
 def oracle_rows(ai, sel=None):
     return O.tree_attn(ai.q, ai.k_prefix, ai.v_prefix, ai.prefix_len, ai.k_tree, ai.v_tree, ai.parent,
-                       ai.scale, O.FP32 if ai.dtype == "fp32" else O.BF16, sel=sel, n_threads=8)
+                       ai.scale, O.FP32 if ai.dtype == "fp32" else O.BF16, sel=sel, n_threads=16)
 
 
 def run_gpu(ai, parent_per_seq=False):
@@ -35,31 +35,8 @@ def check_full(ai, label, parent_per_seq=False):
           flush=True)
     got = run_gpu(ai, parent_per_seq)
     ref = oracle_rows(ai)
-    err = np.abs(got - ref)
-    print(f"[attn] {label}: max abs err {err.max():.3e}", flush=True)
-    assert np.isfinite(got).all()
-    assert err.max() <= TOL[ai.dtype], f"{label}: max abs err {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)}"
+    assert_attn_close(got, ref, ai.dtype, label)
     return got, ref
-
-
-def check_sampled(ai, label, n_sel=96, seed=0):
-    print(f"[attn] {label}: B={ai.B} N={ai.N} H={ai.H_q}/{ai.H_kv} d={ai.d} {ai.dtype} sampled {n_sel} rows", flush=True)
-    got = run_gpu(ai)
-    rng = np.random.default_rng(seed)
-    sel = np.stack([rng.integers(0, ai.B, n_sel), rng.integers(0, ai.N, n_sel), rng.integers(0, ai.H_q, n_sel)],
-                   axis=1).astype(np.int32)
-    # always include the first and last row of the first and last sequence / head
-    sel[0] = (0, 0, 0); sel[1] = (ai.B - 1, ai.N - 1, ai.H_q - 1); sel[2] = (0, ai.N - 1, 0)
-    ref = oracle_rows(ai, sel)
-    g = got[sel[:, 0], sel[:, 1], sel[:, 2]]
-    err = np.abs(g - ref)
-    print(f"[attn] {label}: max abs err over sample {err.max():.3e}", flush=True)
-    assert np.isfinite(got).all()
-    assert err.max() <= TOL[ai.dtype], f"{label}: {err.max():.3e}"
-    # property that holds at any size: every output is a convex combination of V rows
-    vmax = max(np.abs(W.bf16_bits_to_f32(ai.v_prefix)).max(), np.abs(W.bf16_bits_to_f32(ai.v_tree)).max()) \
-        if ai.dtype == "bf16" else max(np.abs(ai.v_prefix).max(), np.abs(ai.v_tree).max())
-    assert np.abs(got).max() <= vmax * 1.01
 
 
 def wl(**kw):
@@ -77,16 +54,22 @@ def test_c2_full():
     check_full(W.gen_attn_inputs(W.WORKLOADS["c2"]), "c2")
 
 
-def test_c3_sampled():
-    check_sampled(W.gen_attn_inputs(W.WORKLOADS["c3"]), "c3", n_sel=256)
+def test_c3_full():
+    check_full(W.gen_attn_inputs(W.WORKLOADS["c3"]), "c3")
 
 
-def test_c4_sampled_ragged_batch():
-    check_sampled(W.gen_attn_inputs(W.WORKLOADS["c4"]), "c4", n_sel=192)
+def test_c4_full_ragged_batch():
+    """All 16 x 60 x 32 rows of the batched workload (the launch configuration the bench times)."""
+    ai = W.gen_attn_inputs(W.WORKLOADS["c4"])
+    got, _ = check_full(ai, "c4")
+    # property that holds at any size: every output is a convex combination of V rows
+    vmax = max(np.abs(W.bf16_bits_to_f32(ai.v_prefix)).max(), np.abs(W.bf16_bits_to_f32(ai.v_tree)).max())
+    assert np.abs(got).max() <= vmax * 1.01
 
 
-def test_c5_sampled_gqa_long_prefix():
-    check_sampled(W.gen_attn_inputs(W.WORKLOADS["c5"]), "c5", n_sel=64)
+def test_c5_full_gqa_long_prefix():
+    """All 4 x 84 x 64 rows at the 16384-token prefix: every row tile, wave and key segment."""
+    check_full(W.gen_attn_inputs(W.WORKLOADS["c5"]), "c5")
 
 
 @pytest.mark.parametrize("L", [0, 1, 31, 32, 33, 63, 64, 65, 127, 129, 300])
@@ -128,9 +111,9 @@ def test_split_factors_agree(monkeypatch):
     for chunk in (4, 8, 20, 1000):
         monkeypatch.setenv("MCSD_ATTN_CHUNK_TILES", str(chunk))
         got = run_gpu(ai)
-        assert np.abs(got - ref).max() <= TOL["bf16"], chunk
+        assert_attn_close(got, ref, "bf16", f"chunk_tiles={chunk}")
         outs.append(got)
-    assert np.abs(outs[0] - outs[-1]).max() <= TOL["bf16"]
+    assert_attn_close(outs[0], outs[-1], "bf16", "4-tile segments against one segment")
 
 
 @pytest.mark.parametrize("variant", [1, 2, 3])
@@ -152,8 +135,7 @@ def test_every_kernel_variant_on_every_row_count(monkeypatch, variant, H_q, H_kv
     for chunk in (6, 1000):
         monkeypatch.setenv("MCSD_ATTN_CHUNK_TILES", str(chunk))
         got = run_gpu(ai)
-        assert np.isfinite(got).all()
-        assert np.abs(got - ref).max() <= TOL["bf16"], (variant, chunk)
+        assert_attn_close(got, ref, "bf16", f"variant {variant} chunk_tiles={chunk}")
 
 
 def test_parent_per_sequence_and_determinism():
@@ -201,12 +183,12 @@ def test_tree_attention_equals_replicated_candidate_sequences(name):
     a = tree.out.float().cpu().numpy()                                   # [B][N][H][d]
     r = rep.out.float().cpu().numpy()                                    # [B*leaves][depth][H][d]
     n_leaves = len(rep.paths)
-    tol = 1e-5 if ai.dtype == "fp32" else 2e-2
     for b in range(ai.B):
         for li, path in enumerate(rep.paths):
             got = r[b * n_leaves + li]
             want = a[b, path]
-            assert np.abs(got - want).max() <= tol, (b, li)
+            # both sides are rounded outputs of the same kernel: twice the bar against the oracle
+            assert np.abs(got - want).max() <= 2 * ATTN_REL[ai.dtype] * np.abs(want).max(), (b, li)
 
 
 def test_many_short_sequences():
@@ -221,5 +203,5 @@ def test_many_short_sequences():
     sel = np.stack([rng.integers(0, ai.B, 200), rng.integers(0, ai.N, 200), rng.integers(0, ai.H_q, 200)], axis=1).astype(np.int32)
     sel[0, 0] = int(np.argmin(ai.prefix_len)); sel[1, 0] = int(np.argmax(ai.prefix_len))
     ref = O.tree_attn(ai.q, ai.k_prefix, ai.v_prefix, ai.prefix_len, ai.k_tree, ai.v_tree, ai.parent, ai.scale,
-                      O.BF16, sel=sel, n_threads=8)
-    assert np.abs(got[sel[:, 0], sel[:, 1], sel[:, 2]] - ref).max() <= 2e-2
+                      O.BF16, sel=sel, n_threads=16)
+    assert_attn_close(got[sel[:, 0], sel[:, 1], sel[:, 2]], ref, "bf16", "300 sequences (sampled rows)")

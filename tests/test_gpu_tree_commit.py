@@ -9,6 +9,7 @@ from oracle import mcsd_oracle as O
 from paper_2401_06706_amd import binding as M
 from paper_2401_06706_amd import device as D
 from paper_2401_06706_amd import workloads as W
+from tests.parity import assert_attn_close
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -194,7 +195,7 @@ def test_decode_loop_three_steps_matches_oracle_loop():
         np.testing.assert_array_equal(cand.numpy(), r_cand)
         ref_attn = O.tree_attn(x["q"], kp, vp, L, x["kt"], x["vt"], rp, 1.0 / np.sqrt(d), O.BF16, n_threads=8)
         got_attn = W.bf16_bits_to_f32(out.view(torch.int16).numpy().view(np.uint16))
-        assert np.abs(got_attn - ref_attn).max() <= 2e-2, f"step {s}"
+        assert_attn_close(got_attn, ref_attn, "bf16", f"decode loop step {s}")
         rv = O.verify(x["zp"], x["zq"], rq, rp, r_cand, x["u_acc"], x["u_end"], temp, variant, gamma_max=gamma, n_threads=8)
         on_path_rows = [[0] + [1 + int(c) for c in rv.accepted_path[b] if c >= 0] for b in range(B)]
         for b in range(B):
