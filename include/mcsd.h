@@ -135,6 +135,22 @@ typedef struct {
 size_t mcsd_attn_workspace_bytes(const mcsd_attn_desc *desc);
 int32_t mcsd_tree_attn(const mcsd_attn_desc *desc, const mcsd_attn_bufs *bufs, void *stream);
 
+/* The same operation for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * split partials go to a buffer of MCSD_STATIC_SCRATCH_BYTES that is part of the library's
+ * device image (one copy per GPU, held until the process ends) instead of bufs->workspace,
+ * which is ignored together with bufs->workspace_bytes.  Inputs, outputs, stream semantics and
+ * results (bit for bit) are those of mcsd_tree_attn.  The call allocates nothing and calls no
+ * allocating routine.  A shape whose partials need more than MCSD_STATIC_SCRATCH_BYTES
+ * (mcsd_attn_workspace_bytes tells) is refused with MCSD_E_WORKSPACE before anything is enqueued.
+ * The first call on a device looks the buffer's address up (module set-up; make it outside
+ * graph capture); `stream` must belong to the device that is current at the call.  All calls
+ * on one GPU share the one buffer: calls that may overlap on a GPU (different streams, or
+ * different host threads on unordered streams) race and must be ordered by the caller.
+ * Nothing in the buffer has to survive from one call to the next. */
+#define MCSD_STATIC_SCRATCH_BYTES ((size_t)96 << 20)
+int32_t mcsd_tree_attn_static(const mcsd_attn_desc *desc, const mcsd_attn_bufs *bufs, void *stream);
+
 /* Paged prefix cache.  The same operation, but the prefix keys and values live in a pool of
  * fixed-size pages shared by all sequences (the usual serving layout): bufs->k_prefix and
  * bufs->v_prefix point to pools [n_pages][H_kv][page_size][d], and logical prefix row r of

@@ -25,7 +25,7 @@ FLAG_NEAR_TIE_ACCEPT, FLAG_NEAR_TIE_ENDPOINT, FLAG_BAD_TOKEN = 1, 2, 4
 FLAG_ZERO_DRAFT_PROB, FLAG_ZERO_RESIDUAL, FLAG_NONFINITE, FLAG_BAD_TREE = 8, 16, 32, 64
 
 EXPORTS = ["mcsd_last_error", "mcsd_version", "mcsd_tree_validate", "mcsd_attn_workspace_bytes",
-           "mcsd_tree_attn", "mcsd_tree_attn_paged", "mcsd_verify_workspace_bytes", "mcsd_verify_sample", "mcsd_verify_step",
+           "mcsd_tree_attn", "mcsd_tree_attn_static", "mcsd_tree_attn_paged", "mcsd_verify_workspace_bytes", "mcsd_verify_sample", "mcsd_verify_step",
            "mcsd_draft_sample", "mcsd_tree_size", "mcsd_tree_build", "mcsd_kv_commit", "mcsd_kv_commit_paged",
            "mcsd_kernel_timing", "mcsd_kernel_count", "mcsd_kernel_name", "mcsd_kernel_timing_read"]
 
@@ -111,6 +111,8 @@ def lib() -> C.CDLL:
         L.mcsd_verify_workspace_bytes.restype = C.c_size_t
         L.mcsd_tree_attn.argtypes = [C.POINTER(AttnDesc), C.POINTER(AttnBufs), C.c_void_p]
         L.mcsd_tree_attn.restype = C.c_int32
+        L.mcsd_tree_attn_static.argtypes = [C.POINTER(AttnDesc), C.POINTER(AttnBufs), C.c_void_p]
+        L.mcsd_tree_attn_static.restype = C.c_int32
         L.mcsd_tree_attn_paged.argtypes = [C.POINTER(AttnDesc), C.POINTER(AttnBufs), C.POINTER(PagedKV), C.c_void_p]
         L.mcsd_tree_attn_paged.restype = C.c_int32
         L.mcsd_verify_sample.argtypes = [C.POINTER(VerifyDesc), C.POINTER(VerifyBufs), C.c_void_p]
@@ -225,6 +227,14 @@ def attn_args(q, k_prefix, v_prefix, prefix_len, k_tree, v_tree, parent, out, sc
 
 def mcsd_tree_attn(args: AttnArgs, stream=None) -> None:
     _check(lib().mcsd_tree_attn(C.byref(args.desc), C.byref(args.bufs), _stream(stream)))
+
+
+STATIC_SCRATCH_BYTES = 96 << 20
+
+
+def mcsd_tree_attn_static(args: AttnArgs, stream=None) -> None:
+    """mcsd_tree_attn without a workspace: the library's own static device buffer holds the partials."""
+    _check(lib().mcsd_tree_attn_static(C.byref(args.desc), C.byref(args.bufs), _stream(stream)))
 
 
 def paged_attn_args(q, k_pool, v_pool, block_table, prefix_len, k_tree, v_tree, parent, out, scale, L_stride: int,

@@ -210,6 +210,61 @@ int32_t mcsd_tree_attn(const mcsd_attn_desc *desc, const mcsd_attn_bufs *bufs, v
     return launch_tree_attn(*desc, *bufs, plan, (hipStream_t)stream);
 }
 
+// ---------------------------------------------------------- allocation-free attention
+// The scratch of mcsd_tree_attn_static lives in the device image of this library: no
+// allocation at any call.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the device address it returns (one per GPU) is what kernels get.
+static __device__ __align__(256) unsigned char scratch[MCSD_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES];     // device address of `scratch` on each GPU, looked up once
+
+int32_t static_scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { set_error("attn(static): hipGetDevice failed: %s", hipGetErrorString(e)); return MCSD_E_HIP; }
+    if (dev < 0 || dev >= MAX_DEVICES) { set_error("attn(static): device %d outside 0..%d", dev, MAX_DEVICES - 1); return MCSD_E_UNSUPPORTED; }
+    std::lock_guard<std::mutex> lk(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            set_error("attn(static): hipGetSymbolAddress failed on device %d: %s", dev, hipGetErrorString(e));
+            return MCSD_E_HIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return MCSD_OK;
+}
+}  // namespace
+
+int32_t mcsd_tree_attn_static(const mcsd_attn_desc *desc, const mcsd_attn_bufs *bufs, void *stream)
+{
+    AttnPlan plan;
+    if (!bufs) { set_error("attn bufs is NULL"); return MCSD_E_NULL; }
+    int32_t rc = check_attn(desc, nullptr, &plan);       // the descriptor alone fixes the scratch size
+    if (rc != MCSD_OK) return rc;
+    if (plan.ws_bytes > MCSD_STATIC_SCRATCH_BYTES) {
+        set_error("attn(static): this shape needs %zu bytes of scratch, the static buffer holds %zu; use mcsd_tree_attn with a workspace",
+                  plan.ws_bytes, (size_t)MCSD_STATIC_SCRATCH_BYTES);
+        return MCSD_E_WORKSPACE;
+    }
+    if (bufs->struct_size != sizeof(mcsd_attn_bufs)) { set_error("attn bufs struct_size %u != %zu", bufs->struct_size, sizeof(mcsd_attn_bufs)); return MCSD_E_SHAPE; }
+    mcsd_attn_bufs b = *bufs;
+    void *ptr = nullptr;
+    rc = static_scratch_of_current_device(&ptr);
+    if (rc != MCSD_OK) return rc;
+    b.workspace = ptr;
+    b.workspace_bytes = MCSD_STATIC_SCRATCH_BYTES;
+    rc = check_attn(desc, &b, &plan);
+    if (rc != MCSD_OK) return rc;
+    return launch_tree_attn(*desc, b, plan, (hipStream_t)stream);
+}
+
 int32_t mcsd_tree_attn_paged(const mcsd_attn_desc *desc, const mcsd_attn_bufs *bufs, const mcsd_paged_kv *paged,
                              void *stream)
 {

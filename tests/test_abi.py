@@ -253,3 +253,19 @@ def test_paged_descriptor_errors(lib):
     assert lib.mcsd_tree_attn_paged(C.byref(d), None, C.byref(pk), None) == -1
     pk.struct_size = 3
     assert lib.mcsd_tree_attn_paged(C.byref(d), C.byref(bufs), C.byref(pk), None) == -2
+
+
+def test_static_scratch_entry_point_refuses_oversized_shapes_before_touching_the_device(lib):
+    """mcsd_tree_attn_static holds MCSD_STATIC_SCRATCH_BYTES of scratch; a shape whose split partials
+    need more is refused by return code (the pointers here are never dereferenced)."""
+    hdr = open(HEADER).read()
+    m = re.search(r"#define MCSD_STATIC_SCRATCH_BYTES \(\(size_t\)(\d+) << (\d+)\)", hdr)
+    assert m and (int(m.group(1)) << int(m.group(2))) == M.STATIC_SCRATCH_BYTES
+    d = M.attn_desc(16, 84, 64, 8, 128, M.DTYPE_BF16, 16384, 0.088)
+    assert M.mcsd_attn_workspace_bytes(d) > M.STATIC_SCRATCH_BYTES
+    b = M.AttnBufs(C.sizeof(M.AttnBufs), 256, 256, 256, 256, 256, 256, 256, 256, None, 0)
+    assert lib.mcsd_tree_attn_static(C.byref(d), C.byref(b), None) == -5
+    assert b"static buffer holds" in lib.mcsd_last_error()
+    assert lib.mcsd_tree_attn_static(C.byref(d), None, None) == -1
+    d.N = 0
+    assert lib.mcsd_tree_attn_static(C.byref(d), C.byref(b), None) == -4
