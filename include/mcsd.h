@@ -35,9 +35,12 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls return after enqueueing; outputs are valid once the stream is
  *     synchronised.  Two calls that share a workspace must be stream-ordered.
- *   - Return value: MCSD_OK or a negative MCSD_E_* code.  On error nothing has
- *     been enqueued.  mcsd_last_error() gives a thread-local message.  No call
- *     aborts, throws or synchronises the device.
+ *   - Return value: MCSD_OK or a negative MCSD_E_* code.  Every argument is
+ *     validated before the first launch: on an argument error (every code but
+ *     MCSD_E_HIP) nothing has been enqueued.  MCSD_E_HIP means the HIP runtime
+ *     refused a launch; launches enqueued before it stay enqueued and the
+ *     outputs of the call are undefined.  mcsd_last_error() gives a thread-local
+ *     message.  No call aborts, throws or synchronises the device.
  *   - Errors in the DATA (token id out of range, zero draft probability, ...)
  *     cannot be seen from the host without a sync; they set bits in the
  *     `flags` output instead (MCSD_FLAG_*).
@@ -85,7 +88,8 @@ enum {
     MCSD_FLAG_ZERO_DRAFT_PROB = 8,    /* q(candidate) == 0: ratio taken as 1 if p > 0 else 0 */
     MCSD_FLAG_ZERO_RESIDUAL = 16,     /* sum max(0, p - q) was not positive after a rejection */
     MCSD_FLAG_NONFINITE = 32,         /* a softmax normaliser was not finite and positive */
-    MCSD_FLAG_BAD_TREE = 64,          /* a row with children has no valid q_row entry: handled as a leaf */
+    MCSD_FLAG_BAD_TREE = 64,          /* a row with children has no valid q_row entry: handled as a leaf; or the walk
+                                         reached gamma_max on a row that accepted a child (tree deeper than gamma_max) */
     MCSD_FLAG_NEAR_TIE_DRAW = 128,    /* mcsd_draft_sample: u_draw within near_tie_eps of an edge of the chosen CDF interval */
     MCSD_FLAG_CACHE_FULL = 256        /* mcsd_kv_commit: prefix_len + n_accepted > L_stride, nothing committed for this sequence */
 };
@@ -151,6 +155,14 @@ int32_t mcsd_tree_attn(const mcsd_attn_desc *desc, const mcsd_attn_bufs *bufs, v
 #define MCSD_STATIC_SCRATCH_BYTES ((size_t)96 << 20)
 int32_t mcsd_tree_attn_static(const mcsd_attn_desc *desc, const mcsd_attn_bufs *bufs, void *stream);
 
+/* Test and tuning aid, not needed in normal use: overrides the launch plan of the matrix-core
+ * attention kernel for all later calls of this process (0 = automatic for each value).
+ * variant 1, 2, 3 = the 32-row x 4-key-stream, 64-row x 2-key-stream and shared-tile kernels;
+ * chunk_tiles = 32-key tiles per segment; target_items = workgroups aimed at when the segment
+ * length is derived.  The workspace size depends on the plan: query mcsd_attn_workspace_bytes
+ * after changing it.  MCSD_E_SHAPE for values out of range. */
+int32_t mcsd_attn_plan_override(int32_t variant, int32_t chunk_tiles, int32_t target_items);
+
 /* Paged prefix cache.  The same operation, but the prefix keys and values live in a pool of
  * fixed-size pages shared by all sequences (the usual serving layout): bufs->k_prefix and
  * bufs->v_prefix point to pools [n_pages][H_kv][page_size][d], and logical prefix row r of
@@ -177,7 +189,7 @@ int32_t mcsd_tree_attn_paged(const mcsd_attn_desc *desc, const mcsd_attn_bufs *b
  * and the walk (Sec. 3).  Per sequence b with temperature T = temperature[b]:
  *   p_r = softmax(target_logits[b][r] / T),  q_r = softmax(draft_logits[b][q_row[r]] / T)
  *   for the children c_1 < c_2 < ... of row r, x = cand_tok[b][c_i]:
- *       ratio = min(1, p_r(x) / q_r(x));  accept c_i iff u_accept[b][c_i] <= ratio
+ *       ratio = min(1, p_r(x) / q_r(x));  accept c_i iff u_accept[b][c_i] <= ratio and ratio > 0
  *       else p_r := max(0, p_r - q_r) / sum_x max(0, p_r - q_r)
  *            and, without replacement only, q_r(x) := 0, q_r := q_r / sum q_r
  *   no child accepted, or r is a leaf: endpoint = inverse CDF of p_r (token-id
@@ -188,7 +200,7 @@ int32_t mcsd_tree_attn_paged(const mcsd_attn_desc *desc, const mcsd_attn_bufs *b
  *       token x is drawn from p_r by inverse CDF at u_endpoint[b][r]; the first child whose
  *       token equals x is accepted, otherwise x is the endpoint; draft logits and u_accept
  *       are not read, ratio is NaN.
- *   T == 0 (argmax sampling, Sec. 4.1/4.4): accept the first child whose token is
+ *   T == 0 (argmax sampling, Sec. 4.1/4.5): accept the first child whose token is
  *       argmax target_logits[b][r] (lowest id on ties), otherwise that argmax is
  *       the endpoint; draft logits and uniforms are not read.
  * Every row is evaluated (not only the rows on the accepted path), so results do
@@ -205,14 +217,17 @@ typedef struct {
     int32_t variant;        /* MCSD_WITH_REPLACEMENT | MCSD_WITHOUT_REPLACEMENT | MCSD_NAIVE */
     int32_t gamma_max;      /* depth bound: row length of accepted_path; out_tokens rows have gamma_max+1 */
     float near_tie_eps;     /* threshold of the MCSD_FLAG_NEAR_TIE_* bits, e.g. 1e-6 */
+    int32_t parent_per_seq; /* 0: one tree for the batch (parent[N], q_row[1+N]); 1: one tree per
+                               sequence (parent[B][N], q_row[B][1+N]): Sec. 3 verifies each sequence's
+                               own candidate tree */
 } mcsd_verify_desc;
 
 typedef struct {
     uint32_t struct_size;
     const float *target_logits;  /* [B][1+N][V]   row 0 = root */
     const float *draft_logits;   /* [B][P][V] */
-    const int32_t *q_row;        /* [1+N] row of draft_logits for each tree row, -1 for leaves */
-    const int32_t *parent;       /* [N] shared by the batch */
+    const int32_t *q_row;        /* [1+N] or [B][1+N]: row of draft_logits for each tree row, -1 for leaves */
+    const int32_t *parent;       /* [N] or [B][N] (desc->parent_per_seq) */
     const int32_t *cand_tok;     /* [B][N] candidate token of each node */
     const float *u_accept;       /* [B][N]   uniform in (0,1) for each node's accept test */
     const float *u_endpoint;     /* [B][1+N] uniform in (0,1) for each row's endpoint draw */
@@ -265,13 +280,14 @@ typedef struct {
     int32_t P;              /* rows of draft_logits per sequence */
     int32_t variant;        /* MCSD_WITH_REPLACEMENT | MCSD_WITHOUT_REPLACEMENT */
     float near_tie_eps;     /* threshold of MCSD_FLAG_NEAR_TIE_DRAW, e.g. 1e-6 */
+    int32_t parent_per_seq; /* 0: one tree for the batch; 1: parent[B][N], q_row[B][1+N] */
 } mcsd_draft_desc;
 
 typedef struct {
     uint32_t struct_size;
     const float *draft_logits;   /* [B][P][V], 16-byte aligned */
-    const int32_t *q_row;        /* [1+N] row of draft_logits for each tree row, -1 for leaves */
-    const int32_t *parent;       /* [N] shared by the batch */
+    const int32_t *q_row;        /* [1+N] or [B][1+N]: row of draft_logits for each tree row, -1 for leaves */
+    const int32_t *parent;       /* [N] or [B][N] (desc->parent_per_seq) */
     const float *u_draw;         /* [B][N] uniform in (0,1) for each node's draw */
     const float *temperature;    /* [B], 0 = top-k */
     int32_t *cand_tok;           /* [B][N] out */

@@ -40,7 +40,7 @@
  * Pins (tests/test_oracle_*.py): exact enumeration of the output distribution
  * against the theorems of Appendix A and B, the per-round accept / reject
  * masses of Appendix A, hand-derived rational examples, the k=1 textbook rule,
- * the Appendix C inequality, the argmax behaviour stated in Sec. 4.4, and
+ * the Appendix C inequality, the argmax behaviour stated in Sec. 4.5, and
  * brute-force per-path causal attention; for the draft sampler the measure of
  * the uniforms mapped to each candidate tuple against q and Eq. (1), numpy's
  * cumulative-sum search, and the end-to-end law (sampler + Algorithm 1 / 2
@@ -231,7 +231,7 @@ static int inverse_cdf(const double *p, int V, double u, double *margin)
  *   z_p, z_q   logit rows [V]; p = softmax(z_p / T), q = softmax(z_q / T)
  *   tok[k]     candidate ids in sampling order;  u_acc[k] their uniforms
  *   u_end      uniform for the endpoint draw
- *   T == 0     argmax behaviour (Sec. 4.4): accept the first candidate equal to
+ *   T == 0     argmax behaviour (Sec. 4.5): accept the first candidate equal to
  *              argmax z_p, otherwise the endpoint is that argmax; z_q, uniforms
  *              unused.  k == 0 is a leaf: endpoint ~ softmax(z_p / T).
  * Outputs: *accepted = index in 0..k-1 of the accepted candidate or -1;
@@ -306,7 +306,9 @@ int mcsd_oracle_verify_parent(int V, int k, int variant, double T, const float *
         ratio[i] = rat;
         double mg = fabs(r - rat);
         if (mg < *margin) *margin = mg;
-        if (r <= rat) {
+        /* a token of probability zero is never accepted (Sec. 3.2: a rejected token has residual
+         * probability 0), also not by a uniform of exactly 0 from outside the open interval */
+        if (rat > 0.0 && r <= rat) {
             *accepted = i;
             break;
         }

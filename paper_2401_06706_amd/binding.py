@@ -25,7 +25,7 @@ FLAG_NEAR_TIE_ACCEPT, FLAG_NEAR_TIE_ENDPOINT, FLAG_BAD_TOKEN = 1, 2, 4
 FLAG_ZERO_DRAFT_PROB, FLAG_ZERO_RESIDUAL, FLAG_NONFINITE, FLAG_BAD_TREE = 8, 16, 32, 64
 
 EXPORTS = ["mcsd_last_error", "mcsd_version", "mcsd_tree_validate", "mcsd_attn_workspace_bytes",
-           "mcsd_tree_attn", "mcsd_tree_attn_static", "mcsd_tree_attn_paged", "mcsd_verify_workspace_bytes", "mcsd_verify_sample", "mcsd_verify_step",
+           "mcsd_tree_attn", "mcsd_tree_attn_static", "mcsd_attn_plan_override", "mcsd_tree_attn_paged", "mcsd_verify_workspace_bytes", "mcsd_verify_sample", "mcsd_verify_step",
            "mcsd_draft_sample", "mcsd_tree_size", "mcsd_tree_build", "mcsd_kv_commit", "mcsd_kv_commit_paged",
            "mcsd_kernel_timing", "mcsd_kernel_count", "mcsd_kernel_name", "mcsd_kernel_timing_read"]
 
@@ -52,7 +52,7 @@ class AttnBufs(C.Structure):
 class VerifyDesc(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("B", C.c_int32), ("N", C.c_int32), ("V", C.c_int32),
                 ("P", C.c_int32), ("variant", C.c_int32), ("gamma_max", C.c_int32),
-                ("near_tie_eps", C.c_float)]
+                ("near_tie_eps", C.c_float), ("parent_per_seq", C.c_int32)]
 
 
 class VerifyBufs(C.Structure):
@@ -69,7 +69,8 @@ class PagedKV(C.Structure):
 
 class DraftDesc(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("B", C.c_int32), ("N", C.c_int32), ("V", C.c_int32),
-                ("P", C.c_int32), ("variant", C.c_int32), ("near_tie_eps", C.c_float)]
+                ("P", C.c_int32), ("variant", C.c_int32), ("near_tie_eps", C.c_float),
+                ("parent_per_seq", C.c_int32)]
 
 
 class DraftBufs(C.Structure):
@@ -113,6 +114,8 @@ def lib() -> C.CDLL:
         L.mcsd_tree_attn.restype = C.c_int32
         L.mcsd_tree_attn_static.argtypes = [C.POINTER(AttnDesc), C.POINTER(AttnBufs), C.c_void_p]
         L.mcsd_tree_attn_static.restype = C.c_int32
+        L.mcsd_attn_plan_override.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+        L.mcsd_attn_plan_override.restype = C.c_int32
         L.mcsd_tree_attn_paged.argtypes = [C.POINTER(AttnDesc), C.POINTER(AttnBufs), C.POINTER(PagedKV), C.c_void_p]
         L.mcsd_tree_attn_paged.restype = C.c_int32
         L.mcsd_verify_sample.argtypes = [C.POINTER(VerifyDesc), C.POINTER(VerifyBufs), C.c_void_p]
@@ -237,6 +240,12 @@ def mcsd_tree_attn_static(args: AttnArgs, stream=None) -> None:
     _check(lib().mcsd_tree_attn_static(C.byref(args.desc), C.byref(args.bufs), _stream(stream)))
 
 
+def mcsd_attn_plan_override(variant: int = 0, chunk_tiles: int = 0, target_items: int = 0) -> None:
+    """Test / tuning aid: force the attention kernel variant (1..3), the segment length in 32-key
+    tiles, or the item target of the launch plan, for all later calls (0 = automatic)."""
+    _check(lib().mcsd_attn_plan_override(int(variant), int(chunk_tiles), int(target_items)))
+
+
 def paged_attn_args(q, k_pool, v_pool, block_table, prefix_len, k_tree, v_tree, parent, out, scale, L_stride: int,
                     workspace: Optional[torch.Tensor] = None):
     """Like attn_args, with the prefix in pools [n_pages][H_kv][page_size][d] and block_table
@@ -281,7 +290,8 @@ class VerifyArgs:
 def verify_args(target_logits, draft_logits, q_row, parent, cand_tok, u_accept, u_endpoint, temperature,
                 n_accepted, accepted_path, out_tokens, acc_child, endpoint, flags, variant: int,
                 ratio=None, residual_out=None, near_tie_eps: float = 1e-6) -> VerifyArgs:
-    """Shapes: target_logits [B][1+N][V]; draft_logits [B][P][V]; q_row int32 [1+N]; parent int32 [N];
+    """Shapes: target_logits [B][1+N][V]; draft_logits [B][P][V]; q_row int32 [1+N] and parent int32 [N]
+    (one tree for the batch) or q_row [B][1+N] and parent [B][N] (one tree per sequence);
     cand_tok int32 [B][N]; u_accept [B][N]; u_endpoint [B][1+N]; temperature [B];
     outputs n_accepted [B], accepted_path [B][gamma_max], out_tokens [B][gamma_max+1],
     acc_child / endpoint / flags [B][1+N], ratio [B][N] (optional), residual_out [B][1+N][V] (optional)."""
@@ -290,7 +300,9 @@ def verify_args(target_logits, draft_logits, q_row, parent, cand_tok, u_accept, 
     P = draft_logits.shape[1]
     gamma_max = accepted_path.shape[1]
     f32, i32 = torch.float32, torch.int32
-    shapes = [(draft_logits, (B, P, V)), (q_row, (1 + N,)), (parent, (N,)), (cand_tok, (B, N)),
+    per_seq = parent.dim() == 2
+    shapes = [(draft_logits, (B, P, V)), (q_row, (B, 1 + N) if per_seq else (1 + N,)),
+              (parent, (B, N) if per_seq else (N,)), (cand_tok, (B, N)),
               (u_accept, (B, N)), (u_endpoint, (B, 1 + N)), (temperature, (B,)), (n_accepted, (B,)),
               (accepted_path, (B, gamma_max)), (out_tokens, (B, gamma_max + 1)), (acc_child, (B, 1 + N)),
               (endpoint, (B, 1 + N)), (flags, (B, 1 + N))]
@@ -301,7 +313,8 @@ def verify_args(target_logits, draft_logits, q_row, parent, cand_tok, u_accept, 
     for t, shp in shapes:
         if tuple(t.shape) != shp:
             raise ValueError(f"shape mismatch: got {tuple(t.shape)}, expected {shp}")
-    desc = VerifyDesc(C.sizeof(VerifyDesc), B, N, V, P, int(variant), gamma_max, float(near_tie_eps))
+    desc = VerifyDesc(C.sizeof(VerifyDesc), B, N, V, P, int(variant), gamma_max, float(near_tie_eps),
+                      1 if per_seq else 0)
     bufs = VerifyBufs(C.sizeof(VerifyBufs),
                       _ptr(target_logits, f32, "target_logits"), _ptr(draft_logits, f32, "draft_logits"),
                       _ptr(q_row, i32, "q_row"), _ptr(parent, i32, "parent"), _ptr(cand_tok, i32, "cand_tok"),
@@ -339,15 +352,17 @@ class DraftArgs:
 
 def draft_args(draft_logits, q_row, parent, u_draw, temperature, cand_tok, flags, variant: int,
                near_tie_eps: float = 1e-6) -> DraftArgs:
-    """Shapes: draft_logits [B][P][V]; q_row int32 [1+N]; parent int32 [N]; u_draw [B][N];
-    temperature [B]; outputs cand_tok int32 [B][N], flags int32 [B][N]."""
+    """Shapes: draft_logits [B][P][V]; q_row int32 [1+N] and parent int32 [N], or q_row [B][1+N] and
+    parent [B][N] (one tree per sequence); u_draw [B][N]; temperature [B]; outputs cand_tok int32
+    [B][N], flags int32 [B][N]."""
     B, P, V = draft_logits.shape
-    N = parent.shape[0]
+    per_seq = parent.dim() == 2
+    N = parent.shape[-1]
     f32, i32 = torch.float32, torch.int32
-    for t, shp in [(q_row, (1 + N,)), (u_draw, (B, N)), (temperature, (B,)), (cand_tok, (B, N)), (flags, (B, N))]:
+    for t, shp in [(q_row, (B, 1 + N) if per_seq else (1 + N,)), (parent, (B, N) if per_seq else (N,)), (u_draw, (B, N)), (temperature, (B,)), (cand_tok, (B, N)), (flags, (B, N))]:
         if tuple(t.shape) != shp:
             raise ValueError(f"shape mismatch: got {tuple(t.shape)}, expected {shp}")
-    desc = DraftDesc(C.sizeof(DraftDesc), B, N, V, P, int(variant), float(near_tie_eps))
+    desc = DraftDesc(C.sizeof(DraftDesc), B, N, V, P, int(variant), float(near_tie_eps), 1 if per_seq else 0)
     bufs = DraftBufs(C.sizeof(DraftBufs), _ptr(draft_logits, f32, "draft_logits"), _ptr(q_row, i32, "q_row"),
                      _ptr(parent, i32, "parent"), _ptr(u_draw, f32, "u_draw"),
                      _ptr(temperature, f32, "temperature"), _ptr(cand_tok, i32, "cand_tok"),

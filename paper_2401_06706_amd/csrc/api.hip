@@ -26,10 +26,11 @@ void set_error(const char *fmt, ...)
 // the launch stream; mcsd_kernel_timing_read waits for them and adds up durations.
 namespace {
 struct EventPair { hipEvent_t a, b; int id; };
+struct OpenBracket { hipEvent_t a; int id; hipStream_t stream; };
 std::mutex g_tmutex;
 bool g_timing = false;
 std::vector<EventPair> g_pending;
-hipEvent_t g_open[K_COUNT];
+std::vector<OpenBracket> g_open;      // begun, not yet ended: one per (kernel id, stream)
 double g_total_ms[K_COUNT];
 long long g_count[K_COUNT];
 const char *const g_names[K_COUNT] = {"tree_attn_mfma", "tree_attn_generic", "tree_attn_combine",
@@ -43,19 +44,24 @@ void timing_begin(int id, hipStream_t stream)
     hipEvent_t e;
     if (hipEventCreate(&e) != hipSuccess) return;
     (void)hipEventRecord(e, stream);
-    g_open[id] = e;
+    for (auto &o : g_open)
+        if (o.id == id && o.stream == stream) { (void)hipEventDestroy(o.a); o.a = e; return; }
+    g_open.push_back({e, id, stream});
 }
 
 void timing_end(int id, hipStream_t stream)
 {
     if (!g_timing) return;
     std::lock_guard<std::mutex> lk(g_tmutex);
-    if (!g_open[id]) return;
-    hipEvent_t e;
-    if (hipEventCreate(&e) != hipSuccess) return;
-    (void)hipEventRecord(e, stream);
-    g_pending.push_back({g_open[id], e, id});
-    g_open[id] = nullptr;
+    for (size_t i = 0; i < g_open.size(); ++i) {
+        if (g_open[i].id != id || g_open[i].stream != stream) continue;
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return;
+        (void)hipEventRecord(e, stream);
+        g_pending.push_back({g_open[i].a, e, id});
+        g_open.erase(g_open.begin() + (long)i);
+        return;
+    }
 }
 
 }  // namespace mcsd
@@ -76,7 +82,9 @@ int32_t mcsd_kernel_timing(int32_t enable)
     if (g_timing) {
         for (auto &p : g_pending) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
         g_pending.clear();
-        for (int i = 0; i < K_COUNT; ++i) { g_total_ms[i] = 0.0; g_count[i] = 0; g_open[i] = nullptr; }
+        for (auto &o : g_open) (void)hipEventDestroy(o.a);
+        g_open.clear();
+        for (int i = 0; i < K_COUNT; ++i) { g_total_ms[i] = 0.0; g_count[i] = 0; }
     }
     return MCSD_OK;
 }
@@ -155,6 +163,7 @@ static int32_t check_verify(const mcsd_verify_desc *d, const mcsd_verify_bufs *b
     if (d->V > MCSD_MAX_VOCAB) { set_error("verify: V %d > %d", d->V, MCSD_MAX_VOCAB); return MCSD_E_UNSUPPORTED; }
     if (d->variant != MCSD_WITH_REPLACEMENT && d->variant != MCSD_WITHOUT_REPLACEMENT && d->variant != MCSD_NAIVE) { set_error("verify: unknown variant %d", d->variant); return MCSD_E_UNSUPPORTED; }
     if (!(d->near_tie_eps >= 0.f)) { set_error("verify: near_tie_eps must be >= 0"); return MCSD_E_SHAPE; }
+    if (d->parent_per_seq != 0 && d->parent_per_seq != 1) { set_error("verify: parent_per_seq must be 0 or 1"); return MCSD_E_SHAPE; }
     if (!b) return MCSD_OK;
     if (b->struct_size != sizeof(mcsd_verify_bufs)) { set_error("verify bufs struct_size %u != %zu", b->struct_size, sizeof(mcsd_verify_bufs)); return MCSD_E_SHAPE; }
     if (!b->target_logits || !b->draft_logits || !b->q_row || !b->parent || !b->cand_tok || !b->u_accept ||
@@ -178,6 +187,7 @@ static int32_t check_draft(const mcsd_draft_desc *d, const mcsd_draft_bufs *b)
     if (d->V > MCSD_MAX_VOCAB) { set_error("draft: V %d > %d", d->V, MCSD_MAX_VOCAB); return MCSD_E_UNSUPPORTED; }
     if (d->variant != MCSD_WITH_REPLACEMENT && d->variant != MCSD_WITHOUT_REPLACEMENT) { set_error("draft: unknown variant %d", d->variant); return MCSD_E_UNSUPPORTED; }
     if (!(d->near_tie_eps >= 0.f)) { set_error("draft: near_tie_eps must be >= 0"); return MCSD_E_SHAPE; }
+    if (d->parent_per_seq != 0 && d->parent_per_seq != 1) { set_error("draft: parent_per_seq must be 0 or 1"); return MCSD_E_SHAPE; }
     if (!b) { set_error("draft bufs is NULL"); return MCSD_E_NULL; }
     if (b->struct_size != sizeof(mcsd_draft_bufs)) { set_error("draft bufs struct_size %u != %zu", b->struct_size, sizeof(mcsd_draft_bufs)); return MCSD_E_SHAPE; }
     if (!b->draft_logits || !b->q_row || !b->parent || !b->u_draw || !b->temperature || !b->cand_tok || !b->flags) {
@@ -396,6 +406,13 @@ int32_t mcsd_verify_step(const mcsd_attn_desc *ad, const mcsd_attn_bufs *ab, con
     rc = launch_tree_attn(*ad, *ab, plan, (hipStream_t)stream);
     if (rc != MCSD_OK) return rc;
     return launch_verify(*vd, *vb, (hipStream_t)stream);
+}
+
+int32_t mcsd_attn_plan_override(int32_t variant, int32_t chunk_tiles, int32_t target_items)
+{
+    const int32_t rc = attn_plan_override(variant, chunk_tiles, target_items);
+    if (rc != MCSD_OK) set_error("plan override: variant must be 0..3, chunk_tiles and target_items >= 0");
+    return rc;
 }
 
 }  // extern "C"

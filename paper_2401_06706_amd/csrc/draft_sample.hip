@@ -21,7 +21,7 @@ using namespace vocab;
 constexpr float LOG2E_F = 1.44269504088896340736f;
 
 struct DraftParams {
-    int B, N, V, P, variant;
+    int B, N, V, P, variant, per_seq;
     float eps;
     const float *draft_logits;
     const int32_t *q_row, *parent;
@@ -53,7 +53,8 @@ __global__ __launch_bounds__(VT) void draft_rows_kernel(DraftParams p)
 
     // The row is requested before it is known whether this tree row has children: in a
     // well-formed input q_row marks exactly the rows that do.
-    const int qr = p.q_row[row];
+    const int qr = p.q_row[(p.per_seq ? (size_t)b * (1 + N) : 0) + row];
+    const int32_t *parent = p.parent + (p.per_seq ? (size_t)b * N : 0);
     const bool have_q = qr >= 0 && qr < p.P;
     float4 a[ITEMS];
     if (have_q) {
@@ -66,7 +67,7 @@ __global__ __launch_bounds__(VT) void draft_rows_kernel(DraftParams p)
 
     // children of this row, ascending node id = sampling order
     if (t < 128) {
-        const bool f = (t < N) && (p.parent[t] == row - 1);
+        const bool f = (t < N) && (parent[t] == row - 1);
         const unsigned long long m = __ballot(f);
         if (lane == 0) s_mask[wave] = m;
     }
@@ -216,7 +217,7 @@ void launch_rows(const DraftParams &p, hipStream_t stream)
 int32_t launch_draft_sample(const mcsd_draft_desc &d, const mcsd_draft_bufs &b, hipStream_t stream)
 {
     DraftParams p;
-    p.B = d.B; p.N = d.N; p.V = d.V; p.P = d.P; p.variant = d.variant; p.eps = d.near_tie_eps;
+    p.B = d.B; p.N = d.N; p.V = d.V; p.P = d.P; p.variant = d.variant; p.eps = d.near_tie_eps; p.per_seq = d.parent_per_seq;
     p.draft_logits = b.draft_logits; p.q_row = b.q_row; p.parent = b.parent;
     p.u_draw = b.u_draw; p.temperature = b.temperature; p.cand_tok = b.cand_tok; p.flags = b.flags;
     // the row stays in registers: 1024 threads up to 8192 tokens, 512 threads with more

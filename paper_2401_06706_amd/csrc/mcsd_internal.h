@@ -22,6 +22,7 @@ struct WalkParams {
     int B, N, gamma_max;
     const int32_t *acc_child, *endpoint, *cand_tok;
     int32_t *n_accepted, *accepted_path, *out_tokens;
+    uint32_t *flags;        // [B][1+N], written by the verification rows before the walk runs
 };
 
 // From the root: an accepted child moves down one level, otherwise (or at a leaf) the row's
@@ -38,6 +39,9 @@ __device__ __forceinline__ void walk_sequence(const WalkParams &w, int b)
         const size_t rix = (size_t)b * (1 + N) + row;
         const int c = w.acc_child[rix];
         if (c < 0 || c >= N || n >= G) {
+            // A row that accepted a child has no endpoint: reaching gamma_max there means the tree
+            // is deeper than the caller said (the block then ends with -1 and the row is flagged).
+            if (c >= 0 && c < N) atomicOr(&w.flags[rix], (uint32_t)MCSD_FLAG_BAD_TREE);
             out[n] = w.endpoint[rix];
             break;
         }
@@ -65,6 +69,9 @@ struct AttnPlan {
 };
 
 bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan);
+// Process-wide overrides of the plan (0 = automatic): kernel variant 1..3, 32-key tiles per
+// segment, workgroups aimed at when the segment length is derived.  A test and tuning aid.
+int32_t attn_plan_override(int variant, int chunk_tiles, int target_wgs);
 // phases: the attention kernel, and the merge of the split partials (needed iff
 // plan.n_chunks_max > 1).  The last launch of the attention (the merge, or the matrix-core
 // kernel itself when nothing is split) can carry the walk of a verification that ran before

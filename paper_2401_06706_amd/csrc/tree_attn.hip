@@ -26,8 +26,8 @@
 // Everything else (fp32 storage, other head dims) runs tree_attn_generic_kernel on
 // the vector ALUs.
 #include <math.h>
-#include <stdlib.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "mcsd_internal.h"
@@ -953,13 +953,8 @@ __global__ __launch_bounds__(256) void tree_attn_generic_kernel(AttnParams p)
     }
 }
 
-int env_int(const char *name, int dflt)
-{
-    const char *s = getenv(name);
-    if (!s || !*s) return dflt;
-    int v = atoi(s);
-    return v > 0 ? v : dflt;
-}
+// Launch-plan overrides of mcsd_attn_plan_override (0 = automatic), process-wide.
+std::atomic<int> g_force_variant{0}, g_force_chunk_tiles{0}, g_force_target_wgs{0};
 
 }  // namespace
 
@@ -981,7 +976,7 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
     // the matrix cores are the limit there, and the shared tiles cut the per-wave staging work).
     pl.variant = pl.rows_per_kv <= 32 ? 0 : (pl.rows_per_kv <= 64 ? 1 : 2);
     {
-        const int forced_variant = env_int("MCSD_ATTN_VARIANT", 0);     // 1-based, 0 / unset = automatic
+        const int forced_variant = g_force_variant.load();     // 1-based, 0 = automatic
         if (forced_variant >= 1 && forced_variant <= 3) pl.variant = forced_variant - 1;
     }
     pl.row_tile = 32 << pl.variant;
@@ -1002,11 +997,12 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
     // kernel is HBM-bound (that traffic competes with the cache stream) and where the matrix
     // cores are the limit (768 .. 1536 within 2 %; beyond that the merge kernel grows faster
     // than the attention kernel shrinks).
-    const long target_wgs = env_int("MCSD_ATTN_TARGET_WGS", 1024);
+    const int forced_target = g_force_target_wgs.load();
+    const long target_wgs = forced_target > 0 ? forced_target : 1024;
     long chunk = (total_max * units + target_wgs - 1) / target_wgs;
     chunk = ((chunk + key_streams - 1) / key_streams) * key_streams;
     if (chunk < min_run) chunk = min_run;
-    const int forced = env_int("MCSD_ATTN_CHUNK_TILES", 0);
+    const int forced = g_force_chunk_tiles.load();
     if (forced > 0) chunk = forced;
     if (chunk > total_max) chunk = total_max;
     pl.chunk_tiles = (int)chunk;
@@ -1021,6 +1017,15 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
     if ((long)pl.n_chunks_max * pl.n_row_tiles + 256L > 65535L || d.B > 65535) return false;     // (+ rows that may carry a walk)
     *plan = pl;
     return true;
+}
+
+int32_t attn_plan_override(int variant, int chunk_tiles, int target_wgs)
+{
+    if (variant < 0 || variant > 3 || chunk_tiles < 0 || target_wgs < 0) return MCSD_E_SHAPE;
+    g_force_variant.store(variant);
+    g_force_chunk_tiles.store(chunk_tiles);
+    g_force_target_wgs.store(target_wgs);
+    return MCSD_OK;
 }
 
 int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const AttnPlan &plan,

@@ -32,7 +32,7 @@ using namespace vocab;
 constexpr float LOG2E_F = 1.44269504088896340736f;
 
 struct VerifyParams {
-    int B, N, V, P, variant, gamma_max;
+    int B, N, V, P, variant, gamma_max, per_seq;
     float eps;
     const float *target_logits, *draft_logits;
     const int32_t *q_row, *parent, *cand_tok;
@@ -100,8 +100,9 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     __shared__ int s_cnt[NWAVES];
     __shared__ int s_seq_of_rank[VT];
     __shared__ float s_T_of_rank[VT];
-    // requested now, used after the ranking: the draft-row address needs it
-    const int qr = p.q_row[row];
+    // requested now, used after the ranking: the draft-row address needs it (with one tree per
+    // sequence the map is that sequence's and can only be read once the sequence is known)
+    int qr = p.per_seq ? -1 : p.q_row[row];
     float T = 1.f;
     const bool ranked = p.B > 1 && p.B <= VT;
     if (p.B > 1 && p.B <= 64) {
@@ -148,6 +149,11 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     } else {
         T = p.temperature[b];
     }
+    const int32_t *parent = p.parent;
+    if (p.per_seq) {
+        qr = p.q_row[(size_t)b * (1 + N) + row];
+        parent += (size_t)b * N;
+    }
 
     // The two logit rows are requested first; the bookkeeping below (children list, flags)
     // runs while they are in flight.  A row has a draft row iff q_row says so; whether it
@@ -171,7 +177,7 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
 
     // children of this row, ascending node id = sampling order
     if (t < 128) {
-        bool f = (t < N) && (p.parent[t] == row - 1);
+        bool f = (t < N) && (parent[t] == row - 1);
         unsigned long long m = __ballot(f);
         if (lane == 0) s_mask[wave] = m;
     }
@@ -223,6 +229,7 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
         if (bi == 0x7fffffff) bi = 0;
         // the first child (ascending node id) that proposed the argmax is accepted
         if (t < k && my_tok == bi) atomicMin(&s_int[0], t);
+        if (t < k && (my_tok < 0 || my_tok >= V)) atomicOr(&s_flags, (uint32_t)MCSD_FLAG_BAD_TOKEN);
         __syncthreads();
         if (t == 0) {
             const int c = s_int[0];
@@ -294,7 +301,9 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
                     fl |= MCSD_FLAG_ZERO_DRAFT_PROB;
                 }
                 const double u = (double)my_u;
-                const bool acc = (u <= ratio);
+                // (a token of probability zero - a duplicate of a rejected one, Sec. 3.2 - is never
+                // accepted, also not by a uniform of exactly 0 from outside the open interval)
+                const bool acc = (ratio > 0.0) && (u <= ratio);
                 if (fabs(u - ratio) < (double)p.eps) fl |= MCSD_FLAG_NEAR_TIE_ACCEPT;
                 if (fl) atomicOr(&s_flags, fl);
                 if (p.ratio) p.ratio[(size_t)b * N + s_kids[i]] = (float)ratio;
@@ -322,10 +331,9 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
                 a[j].w = fmaxf(0.f, fmaf(-bl, eq[j].w, fmaf(-bh, eq[j].w, a[j].w)));
                 part += sum4(a[j]);
             }
-            if (t < k) {
-                my_a = fmax(0.0, my_a - beta * my_q);
-                if (xrem >= 0 && my_tok == xrem) my_q = 0.0;
-            }
+            const double my_a_new = fmax(0.0, my_a - beta * my_q);
+            if (t < k && xrem >= 0 && my_tok == xrem) my_q = 0.0;
+            double A_new;
             if (xrem >= 0) {
                 const int q4 = xrem >> 2;                 // float4 index of the removed token
                 if ((q4 & (VT - 1)) == t) {
@@ -343,13 +351,26 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
                 for (int j = 0; j < ITEMS; ++j)
                     partq += sum4(eq[j]);
                 block_sum2<NWAVES>(part, partq, s_red, s_red2);   // barriers inside also order the reuse of s_accept / s_xrem
-                A = part;
+                A_new = part;
                 Zq = partq;
             } else {
-                A = block_sum<NWAVES>(part, s_red);
+                A_new = block_sum<NWAVES>(part, s_red);
             }
-            if (!(A > 0.0)) {
+            if (A_new > 0.0) {
+                A = A_new;
+                my_a = my_a_new;
+            } else {
+                // max(0, p - q) vanished everywhere, which a rejection excludes in exact arithmetic
+                // (it needs p = q) and rounding or a bad candidate can produce: p stays as it
+                // was.  With every a(x) <= beta e_q(x) and equal sums, the old a is beta e_q.
                 if (t == 0) atomicOr(&s_flags, (uint32_t)MCSD_FLAG_ZERO_RESIDUAL);
+#pragma unroll
+                for (int j = 0; j < ITEMS; ++j) {
+                    a[j].x = fmaf(bl, eq[j].x, bh * eq[j].x);
+                    a[j].y = fmaf(bl, eq[j].y, bh * eq[j].y);
+                    a[j].z = fmaf(bl, eq[j].z, bh * eq[j].z);
+                    a[j].w = fmaf(bl, eq[j].w, bh * eq[j].w);
+                }
             }
         }
         // candidates after the accepted one were never tested
@@ -414,7 +435,7 @@ void launch_rows(const VerifyParams &p, hipStream_t stream)
 WalkParams make_walk_params(const mcsd_verify_desc &d, const mcsd_verify_bufs &b)
 {
     WalkParams w;
-    w.B = d.B; w.N = d.N; w.gamma_max = d.gamma_max;
+    w.B = d.B; w.N = d.N; w.gamma_max = d.gamma_max; w.flags = b.flags;
     w.acc_child = b.acc_child; w.endpoint = b.endpoint; w.cand_tok = b.cand_tok;
     w.n_accepted = b.n_accepted; w.accepted_path = b.accepted_path; w.out_tokens = b.out_tokens;
     return w;
@@ -424,7 +445,7 @@ int32_t launch_verify(const mcsd_verify_desc &d, const mcsd_verify_bufs &b, hipS
 {
     VerifyParams p;
     p.B = d.B; p.N = d.N; p.V = d.V; p.P = d.P; p.variant = d.variant; p.gamma_max = d.gamma_max;
-    p.eps = d.near_tie_eps;
+    p.eps = d.near_tie_eps; p.per_seq = d.parent_per_seq;
     p.target_logits = b.target_logits; p.draft_logits = b.draft_logits;
     p.q_row = b.q_row; p.parent = b.parent; p.cand_tok = b.cand_tok;
     p.u_accept = b.u_accept; p.u_endpoint = b.u_endpoint; p.temperature = b.temperature;

@@ -26,3 +26,12 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def plan_override():
+    """Forces the launch plan of the matrix-core attention kernel for one test (kernel variant,
+    segment length, item target) through mcsd_attn_plan_override; automatic again afterwards."""
+    from paper_2401_06706_amd import binding as M
+    yield M.mcsd_attn_plan_override
+    M.mcsd_attn_plan_override(0, 0, 0)

@@ -41,11 +41,11 @@ def test_struct_layout_matches_header(tmp_path):
     """Compile a C program against the header and compare sizeof/offsetof with ctypes."""
     fields = {"mcsd_attn_desc": (M.AttnDesc, ["struct_size", "B", "d", "L_stride", "scale", "parent_per_seq"]),
               "mcsd_attn_bufs": (M.AttnBufs, ["q", "prefix_len", "out", "workspace", "workspace_bytes"]),
-              "mcsd_verify_desc": (M.VerifyDesc, ["V", "P", "variant", "gamma_max", "near_tie_eps"]),
+              "mcsd_verify_desc": (M.VerifyDesc, ["V", "P", "variant", "gamma_max", "near_tie_eps", "parent_per_seq"]),
               "mcsd_verify_bufs": (M.VerifyBufs, ["target_logits", "temperature", "acc_child", "ratio",
                                                   "flags", "residual_out", "workspace_bytes"]),
               "mcsd_paged_kv": (M.PagedKV, ["page_size", "n_pages", "max_pages_per_seq", "block_table"]),
-              "mcsd_draft_desc": (M.DraftDesc, ["B", "V", "P", "variant", "near_tie_eps"]),
+              "mcsd_draft_desc": (M.DraftDesc, ["B", "V", "P", "variant", "near_tie_eps", "parent_per_seq"]),
               "mcsd_draft_bufs": (M.DraftBufs, ["draft_logits", "q_row", "u_draw", "temperature", "cand_tok", "flags"]),
               "mcsd_commit_desc": (M.CommitDesc, ["B", "H_kv", "dtype", "L_stride", "gamma_max", "n_layers"]),
               "mcsd_commit_bufs": (M.CommitBufs, ["k_prefix", "v_tree", "n_accepted", "out_tokens", "prefix_len",

@@ -102,14 +102,14 @@ def test_ragged_batch_with_padding_rows_poisoned():
     check_full(ai, "poisoned padding")
 
 
-def test_split_factors_agree(monkeypatch):
-    """Different chunk lengths (number of workgroups along the keys) give the same result
-    within tolerance; one chunk (direct write) and many chunks (combine kernel)."""
+def test_split_factors_agree(plan_override):
+    """Different segment lengths give the same result within tolerance; one segment per unit
+    (direct write) and many (partials merged by the segment that arrives last)."""
     ai = W.gen_attn_inputs(wl(prefix=(1000, 1500), B=2, H_q=4, H_kv=4), np.random.default_rng(13), L_stride=1500)
     ref = oracle_rows(ai)
     outs = []
     for chunk in (4, 8, 20, 1000):
-        monkeypatch.setenv("MCSD_ATTN_CHUNK_TILES", str(chunk))
+        plan_override(0, chunk, 0)
         got = run_gpu(ai)
         assert_attn_close(got, ref, "bf16", f"chunk_tiles={chunk}")
         outs.append(got)
@@ -118,12 +118,11 @@ def test_split_factors_agree(monkeypatch):
 
 @pytest.mark.parametrize("variant", [1, 2, 3])
 @pytest.mark.parametrize("H_q,H_kv,kconfig", [(2, 2, (3, 2)), (8, 2, (4, 2)), (8, 1, (4, 2, 2)), (32, 4, (4, 2, 2))])
-def test_every_kernel_variant_on_every_row_count(monkeypatch, variant, H_q, H_kv, kconfig):
+def test_every_kernel_variant_on_every_row_count(plan_override, variant, H_q, H_kv, kconfig):
     """The three matrix-core kernels (32 rows x 4 key streams, 64 x 2, 128 rows sharing one key
     stream) forced in turn on 9, 48, 224 and 224 rows per KV head: fewer rows than one wave's
     share, ragged last row tiles, several row tiles; ragged prefixes with poisoned padding,
     one segment per unit and several; an empty prefix (tree keys only) among them."""
-    monkeypatch.setenv("MCSD_ATTN_VARIANT", str(variant))
     ai = W.gen_attn_inputs(wl(H_q=H_q, H_kv=H_kv, kconfig=kconfig, prefix=(3, 700), B=3), np.random.default_rng(100 + H_q),
                            L_stride=720)
     ai.prefix_len[:] = [0, 33, 700]         # no prefix at all, one tile and one key, many tiles
@@ -133,7 +132,7 @@ def test_every_kernel_variant_on_every_row_count(monkeypatch, variant, H_q, H_kv
         ai.v_prefix[b, :, ai.prefix_len[b]:] = nan16
     ref = oracle_rows(ai)
     for chunk in (6, 1000):
-        monkeypatch.setenv("MCSD_ATTN_CHUNK_TILES", str(chunk))
+        plan_override(variant, chunk, 0)
         got = run_gpu(ai)
         assert_attn_close(got, ref, "bf16", f"variant {variant} chunk_tiles={chunk}")
 
@@ -205,3 +204,34 @@ def test_many_short_sequences():
     ref = O.tree_attn(ai.q, ai.k_prefix, ai.v_prefix, ai.prefix_len, ai.k_tree, ai.v_tree, ai.parent, ai.scale,
                       O.BF16, sel=sel, n_threads=16)
     assert_attn_close(got[sel[:, 0], sel[:, 1], sel[:, 2]], ref, "bf16", "300 sequences (sampled rows)")
+
+
+@pytest.mark.parametrize("H_q,H_kv,kconfig,target", [(16, 8, (4, 2, 2), 4096), (24, 3, (4, 2, 2), 2048), (16, 16, (4, 2), 3000)])
+def test_thousands_of_short_segments(plan_override, H_q, H_kv, kconfig, target):
+    """Far more workgroups than the chip holds at once, every unit cut into many short segments
+    (the minimum run length), an empty prefix and a full one among them; the result is the same
+    bits on every run."""
+    plan_override(0, 0, target)
+    ai = W.gen_attn_inputs(wl(H_q=H_q, H_kv=H_kv, kconfig=kconfig, prefix=(200, 3000), B=7), np.random.default_rng(H_q),
+                           L_stride=3000)
+    ai.prefix_len[0] = 0
+    ai.prefix_len[1] = 3000
+    ref = oracle_rows(ai)
+    call = D.make_attn_call(ai)
+    M.mcsd_tree_attn(call.args)
+    torch.cuda.synchronize()
+    first = call.out.clone()
+    assert_attn_close(call.out_numpy(), ref, "bf16", f"pull {H_q}/{H_kv} target {target}")
+    for rep in range(3):
+        call.out.fill_(7.0)
+        M.mcsd_tree_attn(call.args)
+        torch.cuda.synchronize()
+        assert torch.equal(call.out.view(torch.int16), first.view(torch.int16)), rep
+
+
+def test_plan_override_rejects_bad_values():
+    with pytest.raises(M.McsdError):
+        M.mcsd_attn_plan_override(4, 0, 0)
+    with pytest.raises(M.McsdError):
+        M.mcsd_attn_plan_override(0, -1, 0)
+    M.mcsd_attn_plan_override(0, 0, 0)

@@ -169,3 +169,35 @@ def test_top_k_with_minus_infinity_logits():
     got, rt, rm = run(vi, u)
     assert rt[0].tolist() == [20, 333, 700, 0, 1, 2]
     np.testing.assert_array_equal(got["cand_tok"], rt)
+
+
+@pytest.mark.parametrize("variant", [W.WITH_REPLACEMENT, W.WITHOUT_REPLACEMENT])
+def test_one_tree_per_sequence(variant):
+    """Different candidate trees in one call (parent [B][N], q_row [B][1+N]), one sequence at
+    temperature 0: every sequence's draws equal the oracle's on its own tree."""
+    kconfigs = [(12,), (3, 3), (6, 1), (4, 2), (2, 5), (1,) * 12, (3, 1, 1, 1)]
+    temps = [1.0, 0.8, 1.0, 0.0, 1.0, 1.5, 1.0]
+    V, B = 5000, len(kconfigs)
+    vis, us = [], []
+    for i, (kc, T) in enumerate(zip(kconfigs, temps)):
+        w = W.WORKLOADS["c2"].with_(B=1, V=V, kconfig=kc, variant=variant)
+        vis.append(W.gen_verify_inputs(w, np.random.default_rng(70 + i), temperature=[T], draw_candidates_on_host=False))
+        us.append(W.open_uniform(np.random.default_rng(90 + i), (1, vis[-1].N)))
+    N, P = vis[0].N, max(v.P for v in vis)
+    draft = np.zeros((B, P, V), np.float32)
+    for b, v in enumerate(vis):
+        draft[b, :v.P] = v.draft_logits[0]
+    dev = "cuda:0"
+    t = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+    cand = torch.full((B, N), -9, dtype=torch.int32, device=dev)
+    flags = torch.full((B, N), -9, dtype=torch.int32, device=dev)
+    args = M.draft_args(t(draft), t(np.stack([v.tree.q_row for v in vis]).astype(np.int32)),
+                        t(np.stack([v.tree.parent for v in vis]).astype(np.int32)), t(np.concatenate(us)),
+                        t(np.asarray(temps, np.float32)), cand, flags, variant)
+    assert args.desc.parent_per_seq == 1
+    M.mcsd_draft_sample(args)
+    torch.cuda.synchronize()
+    tok, fl = cand.cpu().numpy(), flags.cpu().numpy()
+    for b, vi in enumerate(vis):
+        rt, rm = O.draft_sample(vi.draft_logits, vi.tree.q_row, vi.tree.parent, us[b], vi.temperature, variant, n_threads=2)
+        compare(vi, {"cand_tok": tok[b:b + 1], "flags": fl[b:b + 1]}, rt, rm, f"per-seq tree {kconfigs[b]}")

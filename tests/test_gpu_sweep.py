@@ -30,7 +30,7 @@ def test_monotonic_rule_and_budget_groups():
     tau = {kc: S.run_config(W.parse_kconfig(kc), "mcss_without", SEQ, V=V, seed=1)["tau"]
            for kc in ["4x2", "2x4", "4x2x2", "2x2x4", "8x1", "1x8"]}
     print("tau:", tau)
-    # decreasing beats increasing at the same budget (Sec. 4.3): the next level is only reached through this one
+    # decreasing beats increasing at the same budget (Sec. 4.4): the next level is only reached through this one
     assert tau["4x2"] > tau["2x4"] + 0.02
     assert tau["4x2x2"] > tau["2x2x4"] + 0.02
     assert tau["8x1"] > tau["1x8"] + 0.02

@@ -73,7 +73,7 @@ def test_tree_shapes(kconfig):
 
 
 def test_duplicate_candidates_with_replacement():
-    """Sec. 3.1: a rejected token has residual probability 0, a repeat is never accepted."""
+    """Sec. 3.2: a rejected token has residual probability 0, a repeat is never accepted."""
     w = W.WORKLOADS["c2"].with_(V=512, B=64, kconfig=(6,), variant=W.WITH_REPLACEMENT)
     vi = W.gen_verify_inputs(w, np.random.default_rng(3))
     vi.cand_tok[:, 1] = vi.cand_tok[:, 0]
@@ -174,3 +174,128 @@ def test_many_sequences_mixed_temperatures(B):
     temps = np.where(rng.random(B) < 0.4, 0.0, rng.choice([0.5, 1.0, 1.7], B)).astype(np.float32)
     vi = W.gen_verify_inputs(w, rng, temperature=temps)
     check(vi, f"B{B}")
+
+
+# ------------------------------------------------------- one candidate tree per sequence
+def _per_sequence_batch(kconfigs, V, variant, temps, seed):
+    """One single-sequence workload per k-configuration (all with the same node count), and the
+    arrays of the batch they form: parent [B][N], q_row [B][1+N], draft rows padded to the largest P."""
+    vis = []
+    for i, (kc, T) in enumerate(zip(kconfigs, temps)):
+        w = W.WORKLOADS["c2"].with_(B=1, V=V, kconfig=kc, variant=variant)
+        vis.append(W.gen_verify_inputs(w, np.random.default_rng(seed + i), temperature=[T]))
+    N = vis[0].N
+    assert all(v.N == N for v in vis)
+    P = max(v.P for v in vis)
+    B = len(vis)
+    draft = np.zeros((B, P, V), np.float32)
+    for b, v in enumerate(vis):
+        draft[b, :v.P] = v.draft_logits[0]
+    arr = dict(
+        target=np.concatenate([v.target_logits for v in vis]), draft=draft,
+        q_row=np.stack([v.tree.q_row for v in vis]).astype(np.int32),
+        parent=np.stack([v.tree.parent for v in vis]).astype(np.int32),
+        cand=np.concatenate([v.cand_tok for v in vis]), u_acc=np.concatenate([v.u_accept for v in vis]),
+        u_end=np.concatenate([v.u_endpoint for v in vis]), temp=np.concatenate([v.temperature for v in vis]))
+    return vis, arr, N, P
+
+
+KCONFIGS_12 = [(12,), (3, 3), (6, 1), (4, 2), (2, 5), (1,) * 12, (3, 1, 1, 1)]      # 12 nodes each
+
+
+@pytest.mark.parametrize("variant", [W.WITH_REPLACEMENT, W.WITHOUT_REPLACEMENT], ids=["wr", "wor"])
+def test_one_tree_per_sequence(variant):
+    """Sec. 3 verifies each sequence's own candidate tree: seven different trees of twelve nodes
+    (one wide level, balanced, chains, ...) in one call, one of them at temperature 0."""
+    V = 3000
+    temps = [1.0, 1.0, 0.7, 0.0, 1.0, 1.3, 1.0]
+    vis, a, N, P = _per_sequence_batch(KCONFIGS_12, V, variant, temps, seed=40 + variant)
+    B, G = len(vis), 12
+    dev = "cuda:0"
+    t = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+    i32 = dict(dtype=torch.int32, device=dev)
+    out = dict(n_accepted=torch.full((B,), -7, **i32), accepted_path=torch.full((B, G), -7, **i32),
+               out_tokens=torch.full((B, G + 1), -7, **i32), acc_child=torch.full((B, 1 + N), -7, **i32),
+               endpoint=torch.full((B, 1 + N), -7, **i32), flags=torch.full((B, 1 + N), -7, **i32),
+               ratio=torch.full((B, N), -7.0, dtype=torch.float32, device=dev),
+               residual_out=torch.full((B, 1 + N, V), -7.0, dtype=torch.float32, device=dev))
+    args = M.verify_args(t(a["target"]), t(a["draft"]), t(a["q_row"]), t(a["parent"]), t(a["cand"]), t(a["u_acc"]),
+                         t(a["u_end"]), t(a["temp"]), out["n_accepted"], out["accepted_path"], out["out_tokens"],
+                         out["acc_child"], out["endpoint"], out["flags"], variant, ratio=out["ratio"],
+                         residual_out=out["residual_out"])
+    assert args.desc.parent_per_seq == 1
+    M.mcsd_verify_sample(args)
+    torch.cuda.synchronize()
+    res = {k: v.cpu().numpy() for k, v in out.items()}
+    for b, vi in enumerate(vis):
+        g = vi.tree.gamma
+        assert (res["accepted_path"][b, g:] == -1).all() and (res["out_tokens"][b, g + 1:] == -1).all()
+        gpu_b = {k: v[b:b + 1] for k, v in res.items()}
+        gpu_b["accepted_path"] = gpu_b["accepted_path"][:, :g]
+        gpu_b["out_tokens"] = gpu_b["out_tokens"][:, :g + 1]
+        st = compare_verify(vi, gpu_b, run_oracle(vi, want_residual=True), check_residual=True,
+                            label=f"per-seq tree {vi.tree.kconfig}")
+        print(f"[verify] tree {vi.tree.kconfig} T={temps[b]}: {st}", flush=True)
+
+
+def test_zero_residual_leaves_p_unchanged():
+    """p == q and a first candidate that is no token at all: the rejection finds max(0, p - q) = 0
+    everywhere.  p stays as it was (flagged), so the next candidate is tested at ratio 1 against
+    the unchanged p and, rejected too by a bad id, the residual written out is p itself."""
+    w = W.WORKLOADS["c2"].with_(V=2000, B=3, kconfig=(3,), variant=W.WITH_REPLACEMENT)
+    vi = W.gen_verify_inputs(w, np.random.default_rng(21))
+    vi.draft_logits[:, 0] = vi.target_logits[:, 0]
+    vi.cand_tok[:, 0] = -1                      # rejected as a bad token: residual update with p == q
+    vi.cand_tok[1, 1] = -1                      # sequence 1: the second one too
+    vi.cand_tok[1, 2] = 2000
+    gpu = run_gpu(vi, want_residual=True)
+    assert (gpu["flags"][:, 0] & M.FLAG_ZERO_RESIDUAL).all() and (gpu["flags"][:, 0] & M.FLAG_BAD_TOKEN).all()
+    # sequences 0 and 2: the second candidate is a real token, p/q = 1 exactly as before the update
+    for b in (0, 2):
+        assert gpu["ratio"][b, 1] == 1.0 and gpu["acc_child"][b, 0] == 1
+    # sequence 1: nothing acceptable; endpoint drawn from the unchanged p
+    assert gpu["acc_child"][1, 0] == -1 and 0 <= gpu["endpoint"][1, 0] < 2000
+    z = vi.target_logits[1, 0].astype(np.float64)
+    p = np.exp(z - z.max()); p /= p.sum()
+    assert np.abs(gpu["residual_out"][1, 0] - p).max() <= 1e-6
+
+
+def test_walk_cut_short_by_gamma_max_is_flagged():
+    """A chain of three candidates that are all accepted (p == q), verified with gamma_max = 2: the
+    walk stops after two, the block ends with -1 and the row that still had an accepted child is
+    flagged; with gamma_max = 3 nothing is flagged."""
+    w = W.WORKLOADS["c2"].with_(V=500, B=2, kconfig=(1, 1, 1))
+    vi = W.gen_verify_inputs(w, np.random.default_rng(22))
+    for row in range(3):
+        vi.draft_logits[:, vi.tree.q_row[row]] = vi.target_logits[:, row]
+    call = D.make_verify_call(vi)
+    M.mcsd_verify_sample(call.args)
+    torch.cuda.synchronize()
+    full = call.results()
+    assert (full["n_accepted"] == 3).all() and (full["flags"] & M.FLAG_BAD_TREE == 0).all()
+    t = call.tensors
+    i32 = dict(dtype=torch.int32, device=t["flags"].device)
+    path2, tok2 = torch.full((2, 2), -7, **i32), torch.full((2, 3), -7, **i32)
+    args = M.verify_args(t["target_logits"], t["draft_logits"], t["q_row"], t["parent"], t["cand_tok"], t["u_accept"],
+                         t["u_endpoint"], t["temperature"], t["n_accepted"], path2, tok2, t["acc_child"],
+                         t["endpoint"], t["flags"], vi.variant)
+    assert args.desc.gamma_max == 2
+    M.mcsd_verify_sample(args)
+    torch.cuda.synchronize()
+    assert (t["n_accepted"].cpu().numpy() == 2).all()
+    np.testing.assert_array_equal(path2.cpu().numpy(), full["accepted_path"][:, :2])
+    np.testing.assert_array_equal(tok2.cpu().numpy()[:, :2], full["out_tokens"][:, :2])
+    assert (tok2.cpu().numpy()[:, 2] == -1).all()
+    fl = t["flags"].cpu().numpy()
+    assert (fl[:, 2] & M.FLAG_BAD_TREE).all() and (fl[:, [0, 1, 3]] & M.FLAG_BAD_TREE == 0).all()
+
+
+def test_argmax_rows_flag_bad_tokens():
+    w = W.WORKLOADS["c2"].with_(V=300, B=2, kconfig=(3,), n_greedy=2)
+    vi = W.gen_verify_inputs(w, np.random.default_rng(23))
+    vi.cand_tok[0, 1] = 300
+    vi.cand_tok[0, 2] = -2
+    gpu = run_gpu(vi)
+    assert gpu["flags"][0, 0] & M.FLAG_BAD_TOKEN and not (gpu["flags"][1, 0] & M.FLAG_BAD_TOKEN)
+    best = int(np.argmax(vi.target_logits[0, 0]))
+    assert gpu["acc_child"][0, 0] == (0 if vi.cand_tok[0, 0] == best else -1)

@@ -6,7 +6,7 @@ None of these tests compares the oracle with itself.  They check it against
   * the per-round accept / reject masses derived in Appendix A,
   * the k = 1 speculative-sampling rule of Sec. 2,
   * the Appendix C inequality (MCSS acceptance >= naive multi-candidate acceptance),
-  * the argmax statements of Sec. 4.4,
+  * the argmax statements of Sec. 4.5,
   * the interval structure an inverse-CDF draw must have.
 """
 import itertools
@@ -203,7 +203,7 @@ def test_identical_distributions_accept_first():
 
 
 def test_rejected_token_has_zero_residual_and_is_never_accepted_again():
-    """Sec. 3.1: a rejected token has probability 0 in the residual, so a repeated
+    """Sec. 3.2: a rejected token has probability 0 in the residual, so a repeated
     candidate can not be accepted later."""
     rng = np.random.default_rng(11)
     V = 30
@@ -217,6 +217,9 @@ def test_rejected_token_has_zero_residual_and_is_never_accepted_again():
         assert r1.residual[x] == 0.0
         r2 = O.verify_parent(z, zq, [x, x, x], [U_REJECT, U_ACCEPT, U_ACCEPT], 0.5, O.WITH_REPLACEMENT)
         assert r2.accepted == -1 and r2.ratio[1] == 0.0 and r2.ratio[2] == 0.0
+        # ... not even by a uniform of exactly 0, which lies outside the open interval the method draws from
+        r3 = O.verify_parent(z, zq, [x, x], [U_REJECT, 0.0], 0.5, O.WITH_REPLACEMENT)
+        assert r3.accepted == -1 and r3.ratio[1] == 0.0 and r3.endpoint >= 0
 
 
 @pytest.mark.parametrize("variant", [O.WITH_REPLACEMENT, O.WITHOUT_REPLACEMENT], ids=["wr", "wor"])
@@ -227,8 +230,8 @@ def test_invariants_full_vocab(variant):
     rng = np.random.default_rng(5)
     z = (3 * rng.standard_normal(w.V)).astype(np.float32)
     zq = (z + rng.standard_normal(w.V).astype(np.float32)).astype(np.float32)
-    q = np.exp(zq.astype(np.float64) - zq.max()); q /= q.sum()
-    toks = W.draw_candidates(rng, q, 8, variant)
+    u_draw = W.open_uniform(rng, (8,))
+    toks, _ = O.draft_parent(zq, u_draw, 8, variant)
     r = reject_all(z, zq, toks, variant)
     n = 8 if r.accepted < 0 else r.accepted
     assert ((r.ratio[:n + (r.accepted >= 0)] >= 0) & (r.ratio[:n + (r.accepted >= 0)] <= 1)).all()
@@ -239,7 +242,7 @@ def test_invariants_full_vocab(variant):
 
 # ----------------------------------------------------------------------- argmax
 def test_temperature_zero():
-    """Sec. 4.4: under argmax sampling the with-replacement rule degenerates to
+    """Sec. 4.5: under argmax sampling the with-replacement rule degenerates to
     ordinary speculative decoding (accept iff the draft token is the target's
     argmax) and the without-replacement rule to multi-candidate naive sampling
     (accept iff the argmax is among the candidates)."""
