@@ -8,8 +8,10 @@ seeded synthetic tensors resident in HBM before the timed region starts.
 
 Prints ONE JSON line.  Metric: verified draft-tree nodes per second
 (B * N / step time).  `roofline` describes the dominant kernel (tree attention)
-from per-kernel HIP-event durations taken in a second pass over the same work;
-`cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
+from per-kernel execution times (HIP events tied to each dispatch) taken in a second pass
+over the same work; `cpu_baseline` is the CPU oracle timed on a bounded sample of the same
+workload.  The default run measures the batched workload c4 (headline, bound by HBM) and adds
+the long-prompt GQA workload c5 (bound by the matrix cores) as `secondary`.
 """
 from __future__ import annotations
 
@@ -49,6 +51,8 @@ def parse_args():
                          "(--page-size), timed next to the contiguous layout; each measured on its own")
     ap.add_argument("--page-size", type=int, default=64, help="tokens per page for --stage paged_attention")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="with the default workload (c4), do not also measure c5 for the `secondary` object")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--sets", type=int, default=0, help="rotating input copies (0 = enough for >= 1 GiB)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -350,7 +354,22 @@ def main():
     if args.stage == "paged_attention":
         bench_paged_attention(args, torch, M, D, W)
         return
-    w = W.WORKLOADS[args.workload]
+    out = measure_step(args, args.workload, torch, M, D, W, with_cpu_baseline=not args.no_cpu_baseline)
+    if args.workload == "c4" and not args.no_secondary:
+        # the second long-prefix workload, bound by the matrix cores instead of HBM
+        torch.cuda.empty_cache()
+        sec = measure_step(args, "c5", torch, M, D, W, with_cpu_baseline=False)
+        out["secondary"] = {k: sec[k] for k in ("value", "unit", "ms_per_step", "dtype", "config", "step_ms_event_p10_p50_p90",
+                                                 "hot_cache_ms_per_step", "step_hbm_gbs", "step_hbm_frac", "roofline",
+                                                 "verify_roofline", "kernels", "kernels_sum_us")}
+    print(json.dumps(out))
+
+
+def measure_step(args, workload, torch, M, D, W, with_cpu_baseline):
+    """Times mcsd_verify_step on one workload: wall clock over back-to-back steps on rotating
+    input sets, then per-kernel execution times from the events of each dispatch."""
+    dev = "cuda:0"
+    w = W.WORKLOADS[workload]
     ai = W.gen_attn_inputs(w)
     vi = W.gen_verify_inputs(w)
 
@@ -379,13 +398,15 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
 
-    # second pass, same work, with every kernel launch bracketed by HIP events on its stream
+    # second pass, same work: every kernel dispatch carries its own start / stop events, so the
+    # durations are kernel execution times (as in a kernel trace) and add up to less than a step
     M.mcsd_kernel_timing(True)
     run(args.steps, args.warmup + args.steps)
     torch.cuda.synchronize()
     ktimes = M.mcsd_kernel_timing_read()
     M.mcsd_kernel_timing(False)
     kernels = {k: {"avg_us": 1e3 * ms / n, "launches": n} for k, (ms, n) in ktimes.items() if n > 0}
+    kernels_sum_us = sum(v["avg_us"] * v["launches"] for v in kernels.values()) / args.steps
 
     # third pass: one event pair per step for the spread, then the same step on ONE input set
     # (the 256 MB memory-side cache then serves part of the reads): labelled, never the headline
@@ -417,14 +438,21 @@ def main():
     else:
         roofline = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS}
-    roofline.update({"traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "algorithmic_bytes": attn_bytes,
+    roofline.update({"traffic": MEASURED_TRAFFIC_BYTES.get(workload),
+                     "traffic_source": f"profiles/step_{workload}.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, a run of its own)",
+                     "algorithmic_bytes": attn_bytes,
                      "algorithmic_flops": flops, "avg_kernel_us": dom_us,
                      "hbm_gbs": achieved, "hbm_frac": achieved / HBM_PEAK_GBS,
                      "mfma_tflops": tflops, "mfma_frac": tflops / MFMA_BF16_PEAK_TFLOPS})
     ver_us = kernels["verify_rows"]["avg_us"]
+    # path-only minimum next to the design bytes: the rows a sequential walk would touch at most
+    # (gamma + 1 target rows, and gamma draft rows for a sampled sequence)
+    g = vi.tree.gamma
+    path_rows = sum((g + 1) + (0 if T == 0.0 else g) for T in vi.temperature)
     verify_roof = {"kernel": "verify_rows", "bound": "hbm", "achieved": verify_bytes / (ver_us * 1e-6) / 1e9,
                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": verify_bytes / (ver_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                   "algorithmic_bytes": verify_bytes, "avg_kernel_us": ver_us}
+                   "algorithmic_bytes": verify_bytes, "design_bytes_every_row": verify_bytes,
+                   "path_only_bytes": int(path_rows) * vi.V * 4, "avg_kernel_us": ver_us}
 
     out = {
         "metric": "verified draft-tree nodes/sec (tree-attn + MCSD sample); achieved HBM GB/s",
@@ -444,10 +472,12 @@ def main():
         "roofline": roofline,
         "verify_roofline": verify_roof,
         "kernels": kernels,
+        "kernels_sum_us": kernels_sum_us,
     }
-    if not args.no_cpu_baseline:
+    if with_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, ai, vi, args.cpu_seconds)
-    print(json.dumps(out))
+    del sets
+    return out
 
 
 if __name__ == "__main__":

@@ -363,12 +363,13 @@ int32_t mcsd_kv_commit_paged(const mcsd_commit_desc *desc, const mcsd_commit_buf
                              void *stream);
 
 /* ------------------------------------------------------------ profiling aid
- * Not part of the verification step.  mcsd_kernel_timing(1) makes every kernel
- * launch of the calls above be bracketed by a pair of HIP events on the launch
- * stream (totals are reset); mcsd_kernel_timing(0) stops.  mcsd_kernel_timing_read
- * waits for the recorded events and returns the summed duration (ms) and the number
- * of launches of kernel `id` (0 .. mcsd_kernel_count()-1, named by mcsd_kernel_name).
- * Events are host objects; no device memory is allocated.
+ * Not part of the verification step.  mcsd_kernel_timing(1) makes every kernel launch of the
+ * calls above carry a start and a stop event tied to that one dispatch (totals are reset), so
+ * that the time between them is the kernel's own execution time, without launch latency or
+ * the gaps between kernels; mcsd_kernel_timing(0) stops.  mcsd_kernel_timing_read waits for
+ * the recorded events and returns the summed duration (ms) and the number of launches of
+ * kernel `id` (0 .. mcsd_kernel_count()-1, named by mcsd_kernel_name).  Events are host
+ * objects; no device memory is allocated.  Not for use under graph capture.
  */
 int32_t mcsd_kernel_timing(int32_t enable);
 int32_t mcsd_kernel_count(void);

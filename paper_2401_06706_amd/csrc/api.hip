@@ -22,46 +22,31 @@ void set_error(const char *fmt, ...)
 }
 
 // ------------------------------------------------------------------ event timing
-// Off by default.  When on, every kernel launch is bracketed by a pair of events on
-// the launch stream; mcsd_kernel_timing_read waits for them and adds up durations.
+// Off by default.  When on, every kernel launch carries a start and a stop event of its own
+// dispatch; mcsd_kernel_timing_read waits for them and adds up the durations.
 namespace {
 struct EventPair { hipEvent_t a, b; int id; };
-struct OpenBracket { hipEvent_t a; int id; hipStream_t stream; };
 std::mutex g_tmutex;
 bool g_timing = false;
 std::vector<EventPair> g_pending;
-std::vector<OpenBracket> g_open;      // begun, not yet ended: one per (kernel id, stream)
 double g_total_ms[K_COUNT];
 long long g_count[K_COUNT];
 const char *const g_names[K_COUNT] = {"tree_attn_mfma", "tree_attn_generic", "tree_attn_combine",
                                       "verify_rows", "walk", "draft_rows", "tree_build", "kv_copy", "kv_finish"};
 }  // namespace
 
-void timing_begin(int id, hipStream_t stream)
+bool timing_new_events(hipEvent_t *start, hipEvent_t *stop)
 {
-    if (!g_timing) return;
-    std::lock_guard<std::mutex> lk(g_tmutex);
-    hipEvent_t e;
-    if (hipEventCreate(&e) != hipSuccess) return;
-    (void)hipEventRecord(e, stream);
-    for (auto &o : g_open)
-        if (o.id == id && o.stream == stream) { (void)hipEventDestroy(o.a); o.a = e; return; }
-    g_open.push_back({e, id, stream});
+    if (!g_timing) return false;
+    if (hipEventCreate(start) != hipSuccess) return false;
+    if (hipEventCreate(stop) != hipSuccess) { (void)hipEventDestroy(*start); return false; }
+    return true;
 }
 
-void timing_end(int id, hipStream_t stream)
+void timing_commit(int id, hipEvent_t start, hipEvent_t stop)
 {
-    if (!g_timing) return;
     std::lock_guard<std::mutex> lk(g_tmutex);
-    for (size_t i = 0; i < g_open.size(); ++i) {
-        if (g_open[i].id != id || g_open[i].stream != stream) continue;
-        hipEvent_t e;
-        if (hipEventCreate(&e) != hipSuccess) return;
-        (void)hipEventRecord(e, stream);
-        g_pending.push_back({g_open[i].a, e, id});
-        g_open.erase(g_open.begin() + (long)i);
-        return;
-    }
+    g_pending.push_back({start, stop, id});
 }
 
 }  // namespace mcsd
@@ -82,8 +67,6 @@ int32_t mcsd_kernel_timing(int32_t enable)
     if (g_timing) {
         for (auto &p : g_pending) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
         g_pending.clear();
-        for (auto &o : g_open) (void)hipEventDestroy(o.a);
-        g_open.clear();
         for (int i = 0; i < K_COUNT; ++i) { g_total_ms[i] = 0.0; g_count[i] = 0; }
     }
     return MCSD_OK;

@@ -207,9 +207,9 @@ void launch_rows(const DraftParams &p, hipStream_t stream)
 {
     dim3 grid(1 + p.N, p.B), block(VT);
     if (p.V % 4 == 0)
-        hipLaunchKernelGGL((draft_rows_kernel<ITEMS, VT, true>), grid, block, 0, stream, p);
+        launch_kernel(K_DRAFT_ROWS, draft_rows_kernel<ITEMS, VT, true>, grid, block, stream, p);
     else
-        hipLaunchKernelGGL((draft_rows_kernel<ITEMS, VT, false>), grid, block, 0, stream, p);
+        launch_kernel(K_DRAFT_ROWS, draft_rows_kernel<ITEMS, VT, false>, grid, block, stream, p);
 }
 
 }  // namespace
@@ -222,12 +222,10 @@ int32_t launch_draft_sample(const mcsd_draft_desc &d, const mcsd_draft_bufs &b, 
     p.u_draw = b.u_draw; p.temperature = b.temperature; p.cand_tok = b.cand_tok; p.flags = b.flags;
     // the row stays in registers: 1024 threads up to 8192 tokens, 512 threads with more
     // registers each beyond that (a 1024-thread workgroup is capped at 128 registers per thread)
-    timing_begin(K_DRAFT_ROWS, stream);
     if (d.V <= 4096) launch_rows<1, 1024>(p, stream);
     else if (d.V <= 8192) launch_rows<2, 1024>(p, stream);
     else if (d.V <= 16384) launch_rows<8, 512>(p, stream);
     else launch_rows<16, 512>(p, stream);
-    timing_end(K_DRAFT_ROWS, stream);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         set_error("draft_rows launch failed: %s", hipGetErrorString(e));

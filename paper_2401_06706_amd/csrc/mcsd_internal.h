@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "mcsd.h"
@@ -13,9 +14,23 @@ enum KernelId { K_ATTN_MFMA = 0, K_ATTN_GENERIC = 1, K_ATTN_COMBINE = 2, K_VERIF
 
 void set_error(const char *fmt, ...);
 
-// Brackets a launch with events when timing is enabled (no-ops otherwise).
-void timing_begin(int kernel_id, hipStream_t stream);
-void timing_end(int kernel_id, hipStream_t stream);
+// Optional per-kernel timing.  When it is enabled a launch goes out through the HIP extension
+// that ties a start and a stop event to that one dispatch, so the elapsed time between them is
+// the kernel's own execution time (what a kernel trace reports), not launch latency or gaps.
+bool timing_new_events(hipEvent_t *start, hipEvent_t *stop);        // false: timing is off
+void timing_commit(int kernel_id, hipEvent_t start, hipEvent_t stop);
+
+template <typename Kernel, typename... Args>
+inline void launch_kernel(int kernel_id, Kernel kernel, dim3 grid, dim3 block, hipStream_t stream, Args... args)
+{
+    hipEvent_t e0, e1;
+    if (timing_new_events(&e0, &e1)) {
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, e0, e1, 0, args...);
+        timing_commit(kernel_id, e0, e1);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, 0, stream, args...);
+    }
+}
 
 // ---- the walk (Sec. 3), shared by verify_sample.hip and the fused tail of a step -------
 struct WalkParams {

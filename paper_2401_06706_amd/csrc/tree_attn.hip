@@ -1045,12 +1045,10 @@ int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const
     if (!plan.use_mfma) {
         if (d.H_q > 2147483647 || d.N > 65535 || d.B > 65535) { set_error("attn: grid too large"); return MCSD_E_UNSUPPORTED; }
         dim3 grid(d.H_q, d.N, d.B), block(256);
-        timing_begin(K_ATTN_GENERIC, stream);
         if (d.dtype == MCSD_DTYPE_FP32)
-            hipLaunchKernelGGL(tree_attn_generic_kernel<float>, grid, block, 0, stream, p);
+            launch_kernel(K_ATTN_GENERIC, tree_attn_generic_kernel<float>, grid, block, stream, p);
         else
-            hipLaunchKernelGGL(tree_attn_generic_kernel<uint16_t>, grid, block, 0, stream, p);
-        timing_end(K_ATTN_GENERIC, stream);
+            launch_kernel(K_ATTN_GENERIC, tree_attn_generic_kernel<uint16_t>, grid, block, stream, p);
         e = hipGetLastError();
         if (e != hipSuccess) { set_error("tree_attn_generic launch failed: %s", hipGetErrorString(e)); return MCSD_E_HIP; }
         return MCSD_OK;
@@ -1071,17 +1069,15 @@ int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const
         int walk_rows = 0;
         if (tail_walk && plan.n_chunks_max == 1) { mw = *tail_walk; walk_rows = (mw.B + 255) / 256; }
         const dim3 grid(d.H_kv, plan.n_chunks_max * plan.n_row_tiles + walk_rows, d.B);
-        timing_begin(K_ATTN_MFMA, stream);
         if (paged) {
-            if (plan.variant == 0) hipLaunchKernelGGL((tree_attn_mfma_kernel<1, 4, true>), grid, dim3(256), 0, stream, p, mw);
-            else if (plan.variant == 1) hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, true>), grid, dim3(256), 0, stream, p, mw);
-            else hipLaunchKernelGGL((tree_attn_mfma_kernel<4, 1, true, true>), grid, dim3(256), 0, stream, p, mw);
+            if (plan.variant == 0) launch_kernel(K_ATTN_MFMA, tree_attn_mfma_kernel<1, 4, true>, grid, dim3(256), stream, p, mw);
+            else if (plan.variant == 1) launch_kernel(K_ATTN_MFMA, tree_attn_mfma_kernel<2, 2, true>, grid, dim3(256), stream, p, mw);
+            else launch_kernel(K_ATTN_MFMA, tree_attn_mfma_kernel<4, 1, true, true>, grid, dim3(256), stream, p, mw);
         } else {
-            if (plan.variant == 0) hipLaunchKernelGGL((tree_attn_mfma_kernel<1, 4, false>), grid, dim3(256), 0, stream, p, mw);
-            else if (plan.variant == 1) hipLaunchKernelGGL((tree_attn_mfma_kernel<2, 2, false>), grid, dim3(256), 0, stream, p, mw);
-            else hipLaunchKernelGGL((tree_attn_mfma_kernel<4, 1, false, true>), grid, dim3(256), 0, stream, p, mw);
+            if (plan.variant == 0) launch_kernel(K_ATTN_MFMA, tree_attn_mfma_kernel<1, 4, false>, grid, dim3(256), stream, p, mw);
+            else if (plan.variant == 1) launch_kernel(K_ATTN_MFMA, tree_attn_mfma_kernel<2, 2, false>, grid, dim3(256), stream, p, mw);
+            else launch_kernel(K_ATTN_MFMA, tree_attn_mfma_kernel<4, 1, false, true>, grid, dim3(256), stream, p, mw);
         }
-        timing_end(K_ATTN_MFMA, stream);
         e = hipGetLastError();
         if (e != hipSuccess) { set_error("tree_attn_mfma launch failed: %s", hipGetErrorString(e)); return MCSD_E_HIP; }
     }
@@ -1091,9 +1087,7 @@ int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const
         int walk_blocks = 0;
         if (tail_walk) { w = *tail_walk; walk_blocks = (w.B + 255) / 256; }
         dim3 cgrid(nx + walk_blocks, d.H_kv, d.B);
-        timing_begin(K_ATTN_COMBINE, stream);
-        hipLaunchKernelGGL(tree_attn_combine_kernel, cgrid, dim3(256), 0, stream, p, nx, w);
-        timing_end(K_ATTN_COMBINE, stream);
+        launch_kernel(K_ATTN_COMBINE, tree_attn_combine_kernel, cgrid, dim3(256), stream, p, nx, w);
         e = hipGetLastError();
         if (e != hipSuccess) { set_error("tree_attn_combine launch failed: %s", hipGetErrorString(e)); return MCSD_E_HIP; }
     }

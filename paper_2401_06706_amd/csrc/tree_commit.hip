@@ -148,9 +148,7 @@ int32_t launch_tree_build(const int32_t *kconfig, int gamma, int n_nodes, int B,
     for (int i = 0; i < gamma; ++i) p.k[i] = kconfig[i];
     p.gamma = gamma; p.N = n_nodes; p.B = B; p.prefix_len = prefix_len;
     p.parent = parent; p.depth = depth; p.q_row = q_row; p.position_ids = position_ids;
-    timing_begin(K_TREE_BUILD, stream);
-    hipLaunchKernelGGL(tree_build_kernel, dim3(1), dim3(256), 0, stream, p);
-    timing_end(K_TREE_BUILD, stream);
+    launch_kernel(K_TREE_BUILD, tree_build_kernel, dim3(1), dim3(256), stream, p);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_error("tree_build launch failed: %s", hipGetErrorString(e)); return MCSD_E_HIP; }
     return MCSD_OK;
@@ -171,14 +169,10 @@ int32_t launch_kv_commit(const mcsd_commit_desc &d, const mcsd_commit_bufs &b, h
     p.k_tree = static_cast<const char *>(b.k_tree); p.v_tree = static_cast<const char *>(b.v_tree);
     p.n_accepted = b.n_accepted; p.accepted_path = b.accepted_path; p.out_tokens = b.out_tokens;
     p.prefix_len = b.prefix_len; p.next_root = b.next_root; p.flags = b.flags;
-    timing_begin(K_KV_COPY, stream);
-    hipLaunchKernelGGL(kv_copy_kernel, dim3(d.gamma_max, d.B, d.n_layers), dim3(256), 0, stream, p);
-    timing_end(K_KV_COPY, stream);
+    launch_kernel(K_KV_COPY, kv_copy_kernel, dim3(d.gamma_max, d.B, d.n_layers), dim3(256), stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_error("kv_copy launch failed: %s", hipGetErrorString(e)); return MCSD_E_HIP; }
-    timing_begin(K_KV_FINISH, stream);
-    hipLaunchKernelGGL(kv_finish_kernel, dim3((d.B + 63) / 64), dim3(64), 0, stream, p);
-    timing_end(K_KV_FINISH, stream);
+    launch_kernel(K_KV_FINISH, kv_finish_kernel, dim3((d.B + 63) / 64), dim3(64), stream, p);
     e = hipGetLastError();
     if (e != hipSuccess) { set_error("kv_finish launch failed: %s", hipGetErrorString(e)); return MCSD_E_HIP; }
     return MCSD_OK;

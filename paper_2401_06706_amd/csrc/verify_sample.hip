@@ -425,9 +425,9 @@ void launch_rows(const VerifyParams &p, hipStream_t stream)
 {
     dim3 grid(1 + p.N, p.B), block(VT);
     if (p.V % 4 == 0)
-        hipLaunchKernelGGL((verify_rows_kernel<ITEMS, VT, true>), grid, block, 0, stream, p);
+        launch_kernel(K_VERIFY_ROWS, verify_rows_kernel<ITEMS, VT, true>, grid, block, stream, p);
     else
-        hipLaunchKernelGGL((verify_rows_kernel<ITEMS, VT, false>), grid, block, 0, stream, p);
+        launch_kernel(K_VERIFY_ROWS, verify_rows_kernel<ITEMS, VT, false>, grid, block, stream, p);
 }
 
 }  // namespace
@@ -457,21 +457,17 @@ int32_t launch_verify(const mcsd_verify_desc &d, const mcsd_verify_bufs &b, hipS
     // thread; beyond that 512 threads with twice the registers each (the 128-register
     // ceiling of a 1024-thread workgroup would spill).
     const int items1024 = (d.V + 4095) / 4096;
-    timing_begin(K_VERIFY_ROWS, stream);
     if (items1024 <= 1) launch_rows<1, 1024>(p, stream);
     else if (items1024 <= 2) launch_rows<2, 1024>(p, stream);
     else if (items1024 <= 4) launch_rows<4, 1024>(p, stream);
     else launch_rows<16, 512>(p, stream);
-    timing_end(K_VERIFY_ROWS, stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         set_error("verify_rows launch failed: %s", hipGetErrorString(e));
         return MCSD_E_HIP;
     }
     if (!with_walk) return MCSD_OK;
-    timing_begin(K_WALK, stream);
-    hipLaunchKernelGGL(walk_kernel, dim3((d.B + 63) / 64), dim3(64), 0, stream, make_walk_params(d, b));
-    timing_end(K_WALK, stream);
+    launch_kernel(K_WALK, walk_kernel, dim3((d.B + 63) / 64), dim3(64), stream, make_walk_params(d, b));
     e = hipGetLastError();
     if (e != hipSuccess) {
         set_error("walk launch failed: %s", hipGetErrorString(e));
