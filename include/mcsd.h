@@ -63,7 +63,7 @@ extern "C" {
 #endif
 
 #define MCSD_MAX_NODES 128      /* tree nodes per sequence (root excluded) */
-#define MCSD_MAX_VOCAB 32768    /* both logit rows of a node stay in registers */
+#define MCSD_MAX_VOCAB 65536    /* the target row of a node stays in one workgroup's registers */
 #define MCSD_MAX_HEAD_DIM 256
 
 enum {

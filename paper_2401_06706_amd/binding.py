@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libmcsd.so")
 
 DTYPE_FP32, DTYPE_BF16 = 0, 1
 WITH_REPLACEMENT, WITHOUT_REPLACEMENT, NAIVE = 0, 1, 2
-MAX_NODES, MAX_VOCAB = 128, 32768
+MAX_NODES, MAX_VOCAB = 128, 65536
 
 FLAG_NEAR_TIE_ACCEPT, FLAG_NEAR_TIE_ENDPOINT, FLAG_BAD_TOKEN = 1, 2, 4
 FLAG_ZERO_DRAFT_PROB, FLAG_ZERO_RESIDUAL, FLAG_NONFINITE, FLAG_BAD_TREE = 8, 16, 32, 64

@@ -225,7 +225,8 @@ int32_t launch_draft_sample(const mcsd_draft_desc &d, const mcsd_draft_bufs &b, 
     if (d.V <= 4096) launch_rows<1, 1024>(p, stream);
     else if (d.V <= 8192) launch_rows<2, 1024>(p, stream);
     else if (d.V <= 16384) launch_rows<8, 512>(p, stream);
-    else launch_rows<16, 512>(p, stream);
+    else if (d.V <= 32768) launch_rows<16, 512>(p, stream);
+    else launch_rows<32, 512>(p, stream);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         set_error("draft_rows launch failed: %s", hipGetErrorString(e));

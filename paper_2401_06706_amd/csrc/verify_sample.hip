@@ -1,18 +1,23 @@
 // Multi-candidate speculative sampling on gfx950: Algorithm 1 (with replacement),
 // Algorithm 2 (without replacement), the endpoint draws and the root-to-leaf walk.
 //
-// One workgroup (1024 threads, 512 for vocabularies above 16384) owns one row of the
-// tree (the root or a node).  Both logit rows of that node are read from HBM exactly
-// once with 128-bit loads and stay in registers for all k sequential accept/reject
-// rounds; every round is one elementwise pass over the resident data plus one block
-// reduction.
+// One workgroup of 512 threads owns one row of the tree (the root or a node).  The target row
+// is read from HBM once with 128-bit loads and stays in registers as the unnormalised
+// residual a(x) for all k sequential accept/reject rounds.  The draft row is streamed: once
+// from HBM for its maximum, then again (from the caches: it was just read) for the
+// exponentials and their sum, and once more for every rejection, where the residual update
+// a := max(0, a - beta e_q) needs e_q(x) = exp((z_q(x) - max) / T), recomputed on the fly.
+// Holding one row instead of two halves the registers of a workgroup, so that two of them
+// share a compute unit and the load phase of one overlaps the arithmetic of the other.
 //
-// Instead of renormalising after each rejection the kernel carries an
-// unnormalised residual a(x) and its sum A (p-hat = a / A), and the unnormalised
-// draft weights e_q(x) with the running mass Z_q of the tokens not yet removed
-// (q-bar = e_q / Z_q).  Algorithm 1/2's update p := max(0, p - q) / sum(...) then
-// reads a := max(0, a - (A / Z_q) e_q), A := sum a, and the normaliser the paper
-// divides by (the probability of the rejection, Appendix A) is A_new / A_old.
+// Instead of renormalising after each rejection the kernel carries the unnormalised residual
+// a(x) and its sum A (p-hat = a / A), and the unnormalised draft weights e_q(x) with the
+// running mass Z_q of the tokens not yet removed (q-bar = e_q / Z_q).  Algorithm 1/2's update
+// p := max(0, p - q) / sum(...) then reads a := max(0, a - (A / Z_q) e_q), A := sum a, and the
+// normaliser the paper divides by (the probability of the rejection, Appendix A) is
+// A_new / A_old.  Algorithm 2's removal of a rejected token from q needs no pass: that token's
+// residual is already 0 and stays 0 whatever is subtracted from it later, so only Z_q changes,
+// by exactly the weight of the token.
 //
 // The handful of numbers that decide an accept test - a(x), e_q(x) at the k
 // candidate tokens - are tracked separately in fp64 by one thread per candidate,
@@ -68,8 +73,98 @@ __device__ __forceinline__ double exp2_neg(double x)
     return ldexp(r, (int)n);
 }
 
+
+// The arguments of the kernel, read again from the kernel-argument segment through a pointer the
+// compiler can not see through.  Used where an argument is needed late in the kernel: kept in
+// scalar registers from the start it would be spilled around the vocabulary passes.
+__device__ __forceinline__ VerifyParams reload_params()
+{
+    typedef const uint32_t __attribute__((address_space(4))) *kernarg_words;
+    kernarg_words pk = (kernarg_words)__builtin_amdgcn_kernarg_segment_ptr();      // the only argument
+    asm volatile("" : "+s"(pk));
+    union { VerifyParams params; uint32_t words[sizeof(VerifyParams) / 4]; } copy;
+#pragma unroll
+    for (int i = 0; i < (int)(sizeof(VerifyParams) / 4); ++i) copy.words[i] = pk[i];
+    return copy.params;
+}
+
+// A logit row is read through a buffer resource whose extent is the row: the address of float4
+// number t + VT i is one per-thread offset plus a scalar, reads past the end return zero instead
+// of leaving the array, and no per-load address registers or bounds branches are needed.
+// Elements past V are then set to -inf (only in the float4s that can reach past V at all).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t row_resource(const float *row, int V)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(row), 0, V * 4, 0x00020000);
+}
+
+template <int VT, bool ALIGNED, bool NONTEMPORAL>
+__device__ __forceinline__ float4 load_row_piece(__amdgpu_buffer_rsrc_t rs, int i, int V)
+{
+    constexpr int AUX = NONTEMPORAL ? 2 : 0;
+    const int voff = threadIdx.x * 16, soff = i * (VT * 16);
+    // the thread's first element of this piece lies past V iff 4 t >= V - 4 VT i: one per-thread
+    // value against a scalar, no per-piece index registers
+    const int e0 = 4 * threadIdx.x, lim = V - 4 * VT * i;
+    const float ninf = -INFINITY;
+    float4 r;
+    if (ALIGNED) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, AUX);
+        const bool past = e0 >= lim;
+        r = make_float4(past ? ninf : __uint_as_float(v[0]), past ? ninf : __uint_as_float(v[1]),
+                        past ? ninf : __uint_as_float(v[2]), past ? ninf : __uint_as_float(v[3]));
+    } else {
+        // (row start and length are not multiples of 16 bytes: element by element)
+        r.x = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, voff, soff, AUX));
+        r.y = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, voff + 4, soff, AUX));
+        r.z = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, voff + 8, soff, AUX));
+        r.w = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, voff + 12, soff, AUX));
+        if (e0 + 0 >= lim) r.x = ninf;
+        if (e0 + 1 >= lim) r.y = ninf;
+        if (e0 + 2 >= lim) r.z = ninf;
+        if (e0 + 3 >= lim) r.w = ninf;
+    }
+    return r;
+}
+
+// One pass over a logit row that is not held in registers: thread t meets the same elements
+// as in a resident row (float4 number t + VT i for i = 0 .. ITEMS-1, -inf past V), in chunks of
+// CH; f(i, values) is called in ascending i.  Two chunks are in flight: the next one is
+// requested before the current one is used, and the scheduler may not move requests further
+// ahead than that (it would, at the price of spills).
+template <int ITEMS, int VT, bool ALIGNED, bool NONTEMPORAL = false, typename F>
+__device__ __forceinline__ void stream_row(__amdgpu_buffer_rsrc_t rs, int V, F &&f)
+{
+    constexpr int CH = ITEMS < 2 ? ITEMS : 2;
+    float4 cur[CH], nxt[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) cur[c] = load_row_piece<VT, ALIGNED, NONTEMPORAL>(rs, c, V);
+#pragma unroll
+    for (int i0 = 0; i0 < ITEMS; i0 += CH) {
+        if (i0 + CH < ITEMS) {
+#pragma unroll
+            for (int c = 0; c < CH; ++c) nxt[c] = load_row_piece<VT, ALIGNED, NONTEMPORAL>(rs, i0 + CH + c, V);
+        }
+#pragma unroll
+        for (int c = 0; c < CH; ++c) f(i0 + c, cur[c]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int c = 0; c < CH; ++c) cur[c] = nxt[c];
+    }
+}
+
+// e_q of four logits, bit for bit what every pass (and the thread that tracks a candidate
+// token) computes: subtraction first, then the scale, then v_exp_f32.
+__device__ __forceinline__ float4 exp_weights(const float4 &z, float m, float c)
+{
+    return make_float4(__builtin_amdgcn_exp2f((z.x - m) * c), __builtin_amdgcn_exp2f((z.y - m) * c),
+                       __builtin_amdgcn_exp2f((z.z - m) * c), __builtin_amdgcn_exp2f((z.w - m) * c));
+}
+
 template <int ITEMS, int VT, bool ALIGNED>
-__global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
+__global__ __launch_bounds__(VT) __attribute__((amdgpu_waves_per_eu(ITEMS <= 16 ? 4 : 2, ITEMS <= 16 ? 4 : 2)))
+void verify_rows_kernel(VerifyParams p)
 {
     constexpr int NWAVES = VT / 64;
     const int row = blockIdx.x;
@@ -89,6 +184,7 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     __shared__ uint32_t s_flags;
     __shared__ int s_accept;       // decision of the current round
     __shared__ int s_xrem;         // token removed from q after a rejection (-1: none)
+    __shared__ float s_qrem;       // its weight e_q as the vector passes compute it
     __shared__ float s_bestv[NWAVES];
     __shared__ int s_besti[NWAVES];
 
@@ -162,18 +258,9 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     const size_t rix = (size_t)b * (1 + N) + row;
     const float *zp_row = p.target_logits + rix * (size_t)V;
     const float NaN = __int_as_float(0x7fc00000);
-    float4 a[ITEMS];
-    load_row<ITEMS, VT, ALIGNED>(zp_row, V, a);
     const bool naive = (p.variant == MCSD_NAIVE);      // the draft row is not needed: candidates are only compared
     const bool have_q = (qr >= 0 && qr < p.P) && (T != 0.f) && !naive;
     const float *zq_row = have_q ? p.draft_logits + ((size_t)b * p.P + qr) * (size_t)V : zp_row;
-    float4 eq[ITEMS];
-    if (have_q) {
-        load_row<ITEMS, VT, ALIGNED>(zq_row, V, eq);
-    } else {
-#pragma unroll
-        for (int i = 0; i < ITEMS; ++i) eq[i] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-    }
 
     // children of this row, ascending node id = sampling order
     if (t < 128) {
@@ -203,22 +290,22 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     }
 
     if (T == 0.f) {
-        // argmax sampling: lowest id on ties.  Thread c fetches the token of child c now, so that
-        // the comparison after the scan does not wait for memory.
+        // argmax sampling: lowest id on ties; the row is streamed, nothing is kept.  Thread c
+        // fetches the token of child c first, so that the comparison after the scan does not
+        // wait for memory.
         const int my_tok = (t < k) ? p.cand_tok[(size_t)b * N + s_kids[t]] : -1;
         float bv = -INFINITY;
         int bi = 0x7fffffff;
-#pragma unroll
-        for (int i = 0; i < ITEMS; ++i) {
-            // A thread meets its elements in ascending token order and the row was padded with
-            // -inf past V when it was loaded: a strict comparison keeps the first of equal
-            // values, and no bounds check is needed.
+        stream_row<ITEMS, VT, ALIGNED, true>(row_resource(zp_row, V), V, [&](int i, const float4 &z) {
+            // A thread meets its elements in ascending token order and the row is padded with
+            // -inf past V: a strict comparison keeps the first of equal values, and no bounds
+            // check is needed.
             const int e = 4 * (t + VT * i);
-            const float v[4] = {a[i].x, a[i].y, a[i].z, a[i].w};
+            const float v[4] = {z.x, z.y, z.z, z.w};
 #pragma unroll
             for (int c = 0; c < 4; ++c)
                 if (v[c] > bv) { bv = v[c]; bi = e + c; }
-        }
+        });
         wave_argmax(bv, bi);
         if (lane == 0) { s_bestv[wave] = bv; s_besti[wave] = bi; }
         if (t == 0) s_int[0] = 0x7fffffff;
@@ -246,6 +333,22 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
         return;
     }
 
+    // first trip over the draft row (from HBM): its maximum
+    float mq = -INFINITY;
+    const __amdgpu_buffer_rsrc_t rs_q = row_resource(zq_row, V);
+    if (have_q)
+        stream_row<ITEMS, VT, ALIGNED>(rs_q, V, [&](int, const float4 &z) { mq = max3_raw(max3_raw(mq, z.x, z.y), z.z, z.w); });
+    // the target row: read exactly once by this workgroup (non-temporal: it does not displace
+    // anything in L2), resident from here on.  Requested behind the draft row's first trip, so
+    // that its registers are not tied up while that trip runs; it arrives during the bookkeeping
+    // below, and the other workgroup of the compute unit computes meanwhile.
+    float4 a[ITEMS];
+    {
+        const __amdgpu_buffer_rsrc_t rs_p = row_resource(zp_row, V);
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) a[i] = load_row_piece<VT, ALIGNED, true>(rs_p, i, V);
+    }
+
     // Thread c follows candidate c: its token, its uniform and the two logits of that token are
     // requested now, so that the first accept decision does not wait for three dependent trips
     // to memory after the exponentials.
@@ -262,10 +365,12 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     }
     const float invT = 1.0f / T;
     const float c2 = invT * LOG2E_F;
-    float mp = row_max<ITEMS>(a), mq = row_max<ITEMS>(eq);
+    float mp = row_max<ITEMS>(a);
     block_max2<NWAVES>(mp, mq, s_redf, s_redf2);
     double A = row_exp<ITEMS>(a, mp, c2);                 // a = e_p, A = Z_p
-    double Zq0 = (k > 0 && !naive) ? row_exp<ITEMS>(eq, mq, c2) : 0.0;
+    double Zq0 = 0.0;
+    if (k > 0 && !naive)                                   // second trip over the draft row: sum of e_q
+        stream_row<ITEMS, VT, ALIGNED>(rs_q, V, [&](int, const float4 &z) { Zq0 += sum4(exp_weights(z, mq, c2)); });
     block_sum2<NWAVES>(A, Zq0, s_red, s_red2);
     if (!(A > 0.0) || !isfinite(A) || (k > 0 && !naive && (!(Zq0 > 0.0) || !isfinite(Zq0)))) {
         if (t == 0) atomicOr(&s_flags, (uint32_t)MCSD_FLAG_NONFINITE);
@@ -275,18 +380,22 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
     if (k > 0 && !naive) {
         // fp64 track of the candidate tokens: thread c follows candidate c
         double my_a = 0.0, my_q = 0.0;
+        float my_q32 = 0.f;                 // e_q of the token with the rounding of the vector passes
         if (t < k && my_tok >= 0 && my_tok < V) {
             // same constants as the vector pass (float c2), evaluated exactly
             my_a = exp2_neg(((double)my_zp - (double)mp) * (double)c2);
             my_q = exp2_neg(((double)my_zq - (double)mq) * (double)c2);
+            my_q32 = __builtin_amdgcn_exp2f((my_zq - mq) * c2);
         }
-        // Z_q: mass of the draft tokens not yet removed.  After a removal it is summed
-        // again over the resident row rather than updated by subtraction, so that it
-        // keeps its relative accuracy when most of the mass has been removed.
+        // Z_q: mass of the draft tokens not yet removed.  A removal takes away exactly the fp32
+        // weight that the sum over the row contained for that token (the same instructions on
+        // the same logit give the same bits), so the difference keeps its relative accuracy
+        // even when most of the mass has been removed.
         double Zq = Zq0;
 
         for (int i = 0; i < k; ++i) {
             if (t == i) {
+                const VerifyParams pl = reload_params();
                 double ratio;
                 uint32_t fl = 0u;
                 const bool valid = (my_tok >= 0 && my_tok < V);
@@ -304,12 +413,13 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
                 // (a token of probability zero - a duplicate of a rejected one, Sec. 3.2 - is never
                 // accepted, also not by a uniform of exactly 0 from outside the open interval)
                 const bool acc = (ratio > 0.0) && (u <= ratio);
-                if (fabs(u - ratio) < (double)p.eps) fl |= MCSD_FLAG_NEAR_TIE_ACCEPT;
+                if (fabs(u - ratio) < (double)pl.eps) fl |= MCSD_FLAG_NEAR_TIE_ACCEPT;
                 if (fl) atomicOr(&s_flags, fl);
-                if (p.ratio) p.ratio[(size_t)b * N + s_kids[i]] = (float)ratio;
+                if (pl.ratio) pl.ratio[(size_t)b * N + s_kids[i]] = (float)ratio;
                 s_accept = acc ? 1 : 0;
-                const bool remove = (!acc) && valid && (p.variant == MCSD_WITHOUT_REPLACEMENT);
+                const bool remove = (!acc) && valid && (pl.variant == MCSD_WITHOUT_REPLACEMENT);
                 s_xrem = remove ? my_tok : -1;
+                s_qrem = remove ? my_q32 : 0.f;
             }
             __syncthreads();
             if (s_accept) {
@@ -320,42 +430,23 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
             // two-term float product so that no common rounding of beta biases the sum
             const double beta = (Zq > 0.0) ? A / Zq : 0.0;   // nothing left in q: the residual is p itself
             const int xrem = s_xrem;
+            const double Zq_new = Zq - (double)s_qrem;
             const float bh = (float)beta;
             const float bl = (float)(beta - (double)bh);
-            double part = 0.0, partq = 0.0;
-#pragma unroll
-            for (int j = 0; j < ITEMS; ++j) {
-                a[j].x = fmaxf(0.f, fmaf(-bl, eq[j].x, fmaf(-bh, eq[j].x, a[j].x)));
-                a[j].y = fmaxf(0.f, fmaf(-bl, eq[j].y, fmaf(-bh, eq[j].y, a[j].y)));
-                a[j].z = fmaxf(0.f, fmaf(-bl, eq[j].z, fmaf(-bh, eq[j].z, a[j].z)));
-                a[j].w = fmaxf(0.f, fmaf(-bl, eq[j].w, fmaf(-bh, eq[j].w, a[j].w)));
+            double part = 0.0;
+            // one more trip over the draft row for e_q
+            stream_row<ITEMS, VT, ALIGNED>(rs_q, V, [&](int j, const float4 &z) {
+                const float4 e = exp_weights(z, mq, c2);
+                a[j].x = fmaxf(0.f, fmaf(-bl, e.x, fmaf(-bh, e.x, a[j].x)));
+                a[j].y = fmaxf(0.f, fmaf(-bl, e.y, fmaf(-bh, e.y, a[j].y)));
+                a[j].z = fmaxf(0.f, fmaf(-bl, e.z, fmaf(-bh, e.z, a[j].z)));
+                a[j].w = fmaxf(0.f, fmaf(-bl, e.w, fmaf(-bh, e.w, a[j].w)));
                 part += sum4(a[j]);
-            }
+            });
             const double my_a_new = fmax(0.0, my_a - beta * my_q);
-            if (t < k && xrem >= 0 && my_tok == xrem) my_q = 0.0;
-            double A_new;
-            if (xrem >= 0) {
-                const int q4 = xrem >> 2;                 // float4 index of the removed token
-                if ((q4 & (VT - 1)) == t) {
-                    const int j = q4 / VT, c = xrem & 3;
-#pragma unroll
-                    for (int jj = 0; jj < ITEMS; ++jj)
-                        if (jj == j) {
-                            if (c == 0) eq[jj].x = 0.f;
-                            if (c == 1) eq[jj].y = 0.f;
-                            if (c == 2) eq[jj].z = 0.f;
-                            if (c == 3) eq[jj].w = 0.f;
-                        }
-                }
-#pragma unroll
-                for (int j = 0; j < ITEMS; ++j)
-                    partq += sum4(eq[j]);
-                block_sum2<NWAVES>(part, partq, s_red, s_red2);   // barriers inside also order the reuse of s_accept / s_xrem
-                A_new = part;
-                Zq = partq;
-            } else {
-                A_new = block_sum<NWAVES>(part, s_red);
-            }
+            if (t < k && xrem >= 0 && my_tok == xrem) { my_q = 0.0; my_q32 = 0.f; }
+            const double A_new = block_sum<NWAVES>(part, s_red);     // barriers inside also order the reuse of s_accept / s_xrem / s_qrem
+            Zq = Zq_new;
             if (A_new > 0.0) {
                 A = A_new;
                 my_a = my_a_new;
@@ -364,23 +455,22 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
                 // (it needs p = q) and rounding or a bad candidate can produce: p stays as it
                 // was.  With every a(x) <= beta e_q(x) and equal sums, the old a is beta e_q.
                 if (t == 0) atomicOr(&s_flags, (uint32_t)MCSD_FLAG_ZERO_RESIDUAL);
-#pragma unroll
-                for (int j = 0; j < ITEMS; ++j) {
-                    a[j].x = fmaf(bl, eq[j].x, bh * eq[j].x);
-                    a[j].y = fmaf(bl, eq[j].y, bh * eq[j].y);
-                    a[j].z = fmaf(bl, eq[j].z, bh * eq[j].z);
-                    a[j].w = fmaf(bl, eq[j].w, bh * eq[j].w);
-                }
+                stream_row<ITEMS, VT, ALIGNED>(rs_q, V, [&](int j, const float4 &z) {
+                    const float4 e = exp_weights(z, mq, c2);
+                    a[j] = make_float4(fmaf(bl, e.x, bh * e.x), fmaf(bl, e.y, bh * e.y), fmaf(bl, e.z, bh * e.z), fmaf(bl, e.w, bh * e.w));
+                });
             }
         }
         // candidates after the accepted one were never tested
-        if (p.ratio && accepted >= 0 && t > accepted && t < k) p.ratio[(size_t)b * N + s_kids[t]] = NaN;
+        const VerifyParams pl = reload_params();
+        if (pl.ratio && accepted >= 0 && t > accepted && t < k) pl.ratio[(size_t)b * N + s_kids[t]] = NaN;
     }
 
+    const VerifyParams pe = reload_params();
     int endpoint = -1;
     if (accepted < 0) {
-        const double u = (double)p.u_endpoint[rix];
-        endpoint = inverse_cdf<ITEMS, VT>(a, A, u, (double)p.eps, s_red, s_seg, s_int, &s_flags);
+        const double u = (double)pe.u_endpoint[rix];
+        endpoint = inverse_cdf<ITEMS, VT>(a, A, u, (double)pe.eps, s_red, s_seg, s_int, &s_flags);
         if (endpoint < 0 || endpoint >= V) endpoint = V - 1;
     }
     if (naive && k > 0) {
@@ -390,27 +480,45 @@ __global__ __launch_bounds__(VT) void verify_rows_kernel(VerifyParams p)
             int acc = -1;
             uint32_t fl = 0u;
             for (int i = 0; i < k; ++i) {
-                const int tok = p.cand_tok[(size_t)b * N + s_kids[i]];
+                const int tok = pe.cand_tok[(size_t)b * N + s_kids[i]];
                 if (tok < 0 || tok >= V) fl |= MCSD_FLAG_BAD_TOKEN;
                 else if (acc < 0 && tok == endpoint) acc = i;
             }
             if (fl) atomicOr(&s_flags, fl);
             s_accept = acc;
         }
-        if (p.ratio && t < k) p.ratio[(size_t)b * N + s_kids[t]] = NaN;
+        if (pe.ratio && t < k) pe.ratio[(size_t)b * N + s_kids[t]] = NaN;
         __syncthreads();
         accepted = s_accept;
         if (accepted >= 0) endpoint = -1;
     }
-    if (p.residual_out) {
+    if (pe.residual_out) {
         const float inv = (A > 0.0) ? (float)(1.0 / A) : 0.f;
-        store_row_scaled<ITEMS, VT, ALIGNED>(p.residual_out + rix * (size_t)V, V, a, inv);
+        const __amdgpu_buffer_rsrc_t rs_out = row_resource(pe.residual_out + rix * (size_t)V, V);     // stores past the end are dropped
+        // The offset of a piece goes into the per-thread offset, not into the scalar offset
+        // field: with a scalar register there, the compiler inserts no wait between a 128-bit
+        // store and the next write to its data registers, and on this chip the store then sent
+        // the next piece's values for some lanes (seen as wrong residuals, from run to run in
+        // different places).
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const int off = t * 16 + i * (VT * 16);
+            if (ALIGNED) {
+                const u32x4 v = {__float_as_uint(a[i].x * inv), __float_as_uint(a[i].y * inv), __float_as_uint(a[i].z * inv), __float_as_uint(a[i].w * inv)};
+                __builtin_amdgcn_raw_buffer_store_b128(v, rs_out, off, 0, 0);
+            } else {
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(a[i].x * inv), rs_out, off, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(a[i].y * inv), rs_out, off + 4, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(a[i].z * inv), rs_out, off + 8, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(a[i].w * inv), rs_out, off + 12, 0, 0);
+            }
+        }
     }
     __syncthreads();
     if (t == 0) {
-        p.acc_child[rix] = accepted >= 0 ? s_kids[accepted] : -1;
-        p.endpoint[rix] = endpoint;
-        p.flags[rix] = s_flags;
+        pe.acc_child[rix] = accepted >= 0 ? s_kids[accepted] : -1;
+        pe.endpoint[rix] = endpoint;
+        pe.flags[rix] = s_flags;
     }
 }
 
@@ -453,14 +561,16 @@ int32_t launch_verify(const mcsd_verify_desc &d, const mcsd_verify_bufs &b, hipS
     p.acc_child = b.acc_child; p.endpoint = b.endpoint; p.ratio = b.ratio; p.flags = b.flags;
     p.residual_out = b.residual_out;
 
-    // Up to 16384 tokens a 1024-thread workgroup holds both rows in 2 x 16 registers per
-    // thread; beyond that 512 threads with twice the registers each (the 128-register
-    // ceiling of a 1024-thread workgroup would spill).
-    const int items1024 = (d.V + 4095) / 4096;
-    if (items1024 <= 1) launch_rows<1, 1024>(p, stream);
-    else if (items1024 <= 2) launch_rows<2, 1024>(p, stream);
-    else if (items1024 <= 4) launch_rows<4, 1024>(p, stream);
-    else launch_rows<16, 512>(p, stream);
+    // 512 threads hold the target row in ITEMS float4 registers each: 2048 ITEMS tokens.  Up to
+    // 32768 tokens the kernel stays within 128 registers (two workgroups per compute unit);
+    // twice that takes the whole register file of a thread (one workgroup per compute unit).
+    const int items = (d.V + 2047) / 2048;
+    if (items <= 1) launch_rows<1, 512>(p, stream);
+    else if (items <= 2) launch_rows<2, 512>(p, stream);
+    else if (items <= 4) launch_rows<4, 512>(p, stream);
+    else if (items <= 8) launch_rows<8, 512>(p, stream);
+    else if (items <= 16) launch_rows<16, 512>(p, stream);
+    else launch_rows<32, 512>(p, stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         set_error("verify_rows launch failed: %s", hipGetErrorString(e));

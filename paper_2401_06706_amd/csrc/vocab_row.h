@@ -293,13 +293,17 @@ template <int ITEMS, int VT>
 __device__ __forceinline__ void cdf_segments(const float4 (&a)[ITEMS], double *s_seg, double *s_tot)
 {
     constexpr int NROWS = VT / 16;
+    constexpr int SC = ITEMS < 4 ? ITEMS : 4;        // segments reduced together (bounds the registers in use)
     const int t = threadIdx.x, lane = t & 63;
-    double x[ITEMS];
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i) x[i] = sum4(a[i]);
-    int which;
-    const double w = row_totals_scattered<ITEMS>(x, lane, which);
-    s_seg[(t >> 4) * ITEMS + which] = w;     // (with fewer than 16 values several lanes of a row store the same total)
+    for (int i0 = 0; i0 < ITEMS; i0 += SC) {
+        double x[SC];
+#pragma unroll
+        for (int i = 0; i < SC; ++i) x[i] = sum4(a[i0 + i]);
+        int which;
+        const double w = row_totals_scattered<SC>(x, lane, which);
+        s_seg[(t >> 4) * ITEMS + i0 + which] = w;     // (with fewer than 16 values several lanes of a row store the same total)
+    }
     __syncthreads();
     if (t < ITEMS) {
         double tot = 0.0;

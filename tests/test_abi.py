@@ -131,7 +131,7 @@ def test_verify_descriptor_errors(lib):
     ptrs = [4096] * 16 + [None]
     bufs = M.VerifyBufs(C.sizeof(M.VerifyBufs), *ptrs, 0)
     assert M.mcsd_verify_workspace_bytes(good_verify_desc()) == 0
-    cases = [(dict(N=0), -4), (dict(N=200), -4), (dict(V=0), -2), (dict(V=40000), -3), (dict(P=9), -2),
+    cases = [(dict(N=0), -4), (dict(N=200), -4), (dict(V=0), -2), (dict(V=70000), -3), (dict(P=9), -2),
              (dict(variant=3), -3), (dict(gamma_max=0), -2), (dict(near_tie_eps=-1.0), -2),
              (dict(B=70000), -3), (dict(P=0), -2)]
     for kw, code in cases:
@@ -170,7 +170,7 @@ def test_draft_descriptor_errors(lib):
         return M.DraftDesc(C.sizeof(M.DraftDesc), a["B"], a["N"], a["V"], a["P"], a["variant"], a["near_tie_eps"])
     ptrs = [4096] * 7
     bufs = M.DraftBufs(C.sizeof(M.DraftBufs), *ptrs)
-    cases = [(dict(N=0), -4), (dict(N=200), -4), (dict(V=0), -2), (dict(V=40000), -3), (dict(P=9), -2),
+    cases = [(dict(N=0), -4), (dict(N=200), -4), (dict(V=0), -2), (dict(V=70000), -3), (dict(P=9), -2),
              (dict(variant=3), -3), (dict(near_tie_eps=-1.0), -2), (dict(B=70000), -3), (dict(P=0), -2)]
     for kw, code in cases:
         d = desc(**kw)

@@ -81,7 +81,7 @@ def test_c4_full_size_sampled_and_top_k(variant):
     assert st["flagged"] <= 0.1 * st["nodes"] and st["near_tie"] <= 0.1 * st["nodes"]
 
 
-@pytest.mark.parametrize("V", [1, 3, 64, 4095, 4096, 4097, 8190, 12345, 16384, 16388, 31999, 32768])
+@pytest.mark.parametrize("V", [1, 3, 64, 4095, 4096, 4097, 8190, 12345, 16384, 16388, 31999, 32768, 40001, 65536])
 def test_vocabulary_sizes(V):
     w = W.WORKLOADS["c2"].with_(B=2, V=V, kconfig=(2, 1) if V < 4 else (4, 2))
     if V == 1:

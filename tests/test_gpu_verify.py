@@ -54,7 +54,7 @@ def test_batched_serving_config_greedy_and_sampled():
         assert np.isnan(gpu["ratio"][:8]).all()
 
 
-@pytest.mark.parametrize("V", [1, 2, 3, 5, 63, 64, 4095, 4096, 4097, 8190, 16385, 32767, 32768])
+@pytest.mark.parametrize("V", [1, 2, 3, 5, 63, 64, 2047, 2048, 2049, 4095, 4096, 4097, 8190, 16385, 32767, 32768, 32772, 50001, 65536])
 def test_ragged_vocabulary_sizes(V):
     """Vocabulary sizes around the vector width and the per-thread item boundaries."""
     w = W.WORKLOADS["c2"].with_(V=V, B=3, kconfig=(3, 2) if V >= 3 else (1, 1), n_greedy=1,
@@ -144,7 +144,7 @@ def test_runtime_errors_are_return_codes():
     w = W.WORKLOADS["c1"]
     vi = W.gen_verify_inputs(w)
     call = D.make_verify_call(vi)
-    call.args.desc.V = 40000
+    call.args.desc.V = 70000
     with pytest.raises(M.McsdError) as e:
         M.mcsd_verify_sample(call.args)
     assert e.value.code == -3
