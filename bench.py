@@ -231,7 +231,7 @@ def bench_kv_commit(args, torch, M, D, W):
         for _ in range(reps):
             Lc = Lh.copy()
             O.tree_build(w.kconfig)
-            lib.mcsd_oracle_kv_commit(n_layers, B, N, H_kv, d, 2, Ls, G, P_(kph), P_(vph), P_(kth), P_(vth),
+            lib.mcsd_oracle_kv_commit(n_layers, B, N, H_kv, d, 2, Ls, G, 0, P_(kph), P_(vph), P_(kth), P_(vth),
                                       P_(ref.n_accepted), P_(ref.accepted_path), P_(ref.out_tokens), P_(Lc), P_(nr), P_(full))
         dt = (time.perf_counter() - t0) / reps
         out["cpu_baseline"] = {"value": 1.0 / dt, "unit": "commits/s", "cores": 1, "kind": "oracle",

@@ -44,13 +44,24 @@
  *   - Errors in the DATA (token id out of range, zero draft probability, ...)
  *     cannot be seen from the host without a sync; they set bits in the
  *     `flags` output instead (MCSD_FLAG_*).
- *   - Tree layout: nodes 0..N-1 exclude the root, which is the last context
- *     token (already in the prefix cache).  parent[i] == -1 marks a child of the
+ *   - Tree layout: nodes 0..N-1 exclude the root.  parent[i] == -1 marks a child of the
  *     root; parent[i] < i is required (any order in which parents precede
  *     children, e.g. generation order).  The children of a node are verified
  *     in ascending node id, which must be the order they were sampled in
  *     (Algorithm 2 depends on it).  "Row" r means the root for r == 0 and node
  *     r-1 otherwise.  N <= MCSD_MAX_NODES.
+ *   - The root and the caches.  By default (root_row = 0) the root is the last token of
+ *     the context and its keys and values are already in the prefix cache: it is neither a
+ *     query nor a key row of the tree block, which is the situation of one verification
+ *     step looked at alone.  In a decode loop the root of a step is the endpoint token the
+ *     previous step emitted, and the target's forward pass over "root + candidates"
+ *     produces the root's keys and values together with the candidates' (its logit row
+ *     is row 0 of target_logits).  root_row = 1 in the attention and commit descriptors
+ *     describes that: the tensors of the tree block (q, out, k_tree, v_tree) carry
+ *     1 + N rows, row 0 = the root and row 1 + i = candidate i; every candidate
+ *     attends to the prefix, the root, its ancestors and itself, the root to the prefix
+ *     and itself; the commit appends the root and then the accepted path.  parent[]
+ *     keeps its N entries and its meaning.  N + root_row <= MCSD_MAX_NODES.
  */
 #ifndef MCSD_H
 #define MCSD_H
@@ -119,11 +130,12 @@ typedef struct {
     int32_t L_stride;       /* rows allocated per (sequence, KV head) in the prefix cache; prefix_len[b] <= L_stride <= 2^22 */
     float scale;            /* softmax scale, finite and >= 0, normally 1/sqrt(d) */
     int32_t parent_per_seq; /* 0: one parent[N] shared by the batch; 1: parent[B][N] */
+    int32_t root_row;       /* 0: the root is in the prefix cache; 1: the tree block has 1+N rows, row 0 = the root */
 } mcsd_attn_desc;
 
 typedef struct {
     uint32_t struct_size;
-    const void *q;               /* [B][N][H_q][d] */
+    const void *q;               /* [B][N][H_q][d]   (N here and below: N + root_row rows) */
     const void *k_prefix;        /* [B][H_kv][L_stride][d] */
     const void *v_prefix;        /* [B][H_kv][L_stride][d] */
     const int32_t *prefix_len;   /* [B], 0 <= prefix_len[b] <= L_stride */
@@ -307,13 +319,16 @@ int32_t mcsd_draft_sample(const mcsd_draft_desc *desc, const mcsd_draft_bufs *bu
  *   parent[N], depth[N] (1-based), q_row[1+N] (draft row of every tree row with
  *   children, numbered in row order; -1 for leaves),
  *   position_ids[B][N] = prefix_len[b] + depth[i] - 1 (each candidate keeps the
- *   position it has in its own sequence; nullable, then prefix_len may be NULL too).
+ *   position it has in its own sequence; nullable, then prefix_len may be NULL too);
+ *   with root_row = 1, position_ids[B][1+N]: entry 0 = prefix_len[b] (the root, first
+ *   token after the cache), entry 1 + i = prefix_len[b] + depth[i].
  * kconfig is HOST memory (gamma <= 16 entries, each >= 1); N must not exceed
  * MCSD_MAX_NODES (MCSD_E_TREE).  mcsd_tree_size only computes N and P on the host.
  */
 int32_t mcsd_tree_size(const int32_t *kconfig_host, int32_t gamma, int32_t *n_nodes, int32_t *n_draft_rows);
 int32_t mcsd_tree_build(const int32_t *kconfig_host, int32_t gamma, int32_t B, const int32_t *prefix_len,
-                        int32_t *parent, int32_t *depth, int32_t *q_row, int32_t *position_ids, void *stream);
+                        int32_t *parent, int32_t *depth, int32_t *q_row, int32_t *position_ids, int32_t root_row,
+                        void *stream);
 
 /* mcsd_kv_commit: keys and values of generated tokens are cached for reuse (Sec. 3.3);
  * after verification the accepted candidates are generated tokens.  For sequence b with
@@ -324,6 +339,11 @@ int32_t mcsd_tree_build(const int32_t *kconfig_host, int32_t gamma, int32_t B, c
  * MCSD_FLAG_CACHE_FULL (0 otherwise); path entries outside [0, N) end the copy there and set
  * MCSD_FLAG_BAD_TREE.  n_accepted, accepted_path and out_tokens are the outputs of
  * mcsd_verify_sample.  The caches of n_layers layers lie back to back.
+ * With root_row = 1 (k_tree, v_tree have 1 + N rows, row 0 = the root, see the conventions):
+ *   k_prefix[..][L] = k_tree[..][0],  k_prefix[..][L + 1 + j] = k_tree[..][1 + accepted_path[b][j]],
+ *   prefix_len[b] = L + 1 + n;  the cache is full if L + 1 + n > L_stride.
+ * The sequence held by the cache after the commit is then: context, root, accepted tokens; the
+ * endpoint (next_root) is the root row of the next step.
  */
 typedef struct {
     uint32_t struct_size;
@@ -335,14 +355,15 @@ typedef struct {
     int32_t L_stride;       /* rows allocated per (sequence, KV head) in the prefix cache */
     int32_t gamma_max;      /* row length of accepted_path; out_tokens rows have gamma_max+1 */
     int32_t n_layers;       /* >= 1 */
+    int32_t root_row;       /* 0 | 1, as in mcsd_attn_desc */
 } mcsd_commit_desc;
 
 typedef struct {
     uint32_t struct_size;
     void *k_prefix;                 /* [n_layers][B][H_kv][L_stride][d] in/out */
     void *v_prefix;                 /* [n_layers][B][H_kv][L_stride][d] in/out */
-    const void *k_tree;             /* [n_layers][B][H_kv][N][d] */
-    const void *v_tree;             /* [n_layers][B][H_kv][N][d] */
+    const void *k_tree;             /* [n_layers][B][H_kv][N + root_row][d] */
+    const void *v_tree;             /* [n_layers][B][H_kv][N + root_row][d] */
     const int32_t *n_accepted;      /* [B] */
     const int32_t *accepted_path;   /* [B][gamma_max] */
     const int32_t *out_tokens;      /* [B][gamma_max+1] */

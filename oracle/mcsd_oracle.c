@@ -584,9 +584,13 @@ int mcsd_oracle_tree_build(const int32_t *kconfig, int gamma, int max_nodes, int
  *   out_tokens [B][gamma_max+1]; prefix_len [B] (in/out); next_root [B]; full [B]
  *   (1 where prefix_len + n_accepted would exceed L_stride: nothing is copied and
  *   prefix_len keeps its value).
+ * root_row = 1: the root of the tree (the token the previous step ended with) went through the
+ *   same forward pass as the candidates, so the tree block has 1 + N rows, row 0 the root's and
+ *   row 1 + i candidate i's; generated tokens are then the root and the accepted candidates:
+ *   the root's row is appended first, the path after it, and the prefix grows by 1 + n_accepted.
  */
 int mcsd_oracle_kv_commit(int n_layers, int B, int N, int H_kv, int d, int elem_bytes, long L_stride,
-                          int gamma_max, unsigned char *k_prefix, unsigned char *v_prefix,
+                          int gamma_max, int root_row, unsigned char *k_prefix, unsigned char *v_prefix,
                           const unsigned char *k_tree, const unsigned char *v_tree,
                           const int32_t *n_accepted, const int32_t *accepted_path,
                           const int32_t *out_tokens, int32_t *prefix_len, int32_t *next_root,
@@ -598,19 +602,28 @@ int mcsd_oracle_kv_commit(int n_layers, int B, int N, int H_kv, int d, int elem_
         if (n < 0 || n > gamma_max) return -1;
         next_root[b] = out_tokens[(size_t)b * (gamma_max + 1) + n];
         long L = prefix_len[b];
-        full[b] = (L + n > L_stride) ? 1 : 0;
+        int extra = root_row ? 1 : 0;
+        int tree_rows = N + extra;
+        full[b] = (L + extra + n > L_stride) ? 1 : 0;
         if (full[b]) continue;
         for (int layer = 0; layer < n_layers; ++layer)
-            for (int g = 0; g < H_kv; ++g)
-                for (int j = 0; j < n; ++j) {
-                    int node = accepted_path[(size_t)b * gamma_max + j];
-                    if (node < 0 || node >= N) return -2;
-                    size_t src = ((((size_t)layer * B + b) * H_kv + g) * (size_t)N + node) * row;
-                    size_t dst = ((((size_t)layer * B + b) * H_kv + g) * (size_t)L_stride + (size_t)(L + j)) * row;
+            for (int g = 0; g < H_kv; ++g) {
+                if (root_row) {
+                    size_t src = ((((size_t)layer * B + b) * H_kv + g) * (size_t)tree_rows + 0) * row;
+                    size_t dst = ((((size_t)layer * B + b) * H_kv + g) * (size_t)L_stride + (size_t)L) * row;
                     memcpy(k_prefix + dst, k_tree + src, row);
                     memcpy(v_prefix + dst, v_tree + src, row);
                 }
-        prefix_len[b] = (int32_t)(L + n);
+                for (int j = 0; j < n; ++j) {
+                    int node = accepted_path[(size_t)b * gamma_max + j];
+                    if (node < 0 || node >= N) return -2;
+                    size_t src = ((((size_t)layer * B + b) * H_kv + g) * (size_t)tree_rows + (size_t)(extra + node)) * row;
+                    size_t dst = ((((size_t)layer * B + b) * H_kv + g) * (size_t)L_stride + (size_t)(L + extra + j)) * row;
+                    memcpy(k_prefix + dst, k_tree + src, row);
+                    memcpy(v_prefix + dst, v_tree + src, row);
+                }
+            }
+        prefix_len[b] = (int32_t)(L + extra + n);
     }
     return 0;
 }

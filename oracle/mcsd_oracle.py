@@ -54,7 +54,7 @@ def lib() -> ctypes.CDLL:
         L.mcsd_oracle_tree_build.restype = c.c_int
         L.mcsd_oracle_tree_build.argtypes = [c.c_void_p, c.c_int, c.c_int] + [c.c_void_p] * 3
         L.mcsd_oracle_kv_commit.restype = c.c_int
-        L.mcsd_oracle_kv_commit.argtypes = [c.c_int] * 6 + [c.c_long, c.c_int] + [c.c_void_p] * 10
+        L.mcsd_oracle_kv_commit.argtypes = [c.c_int] * 6 + [c.c_long, c.c_int, c.c_int] + [c.c_void_p] * 10
         L.mcsd_oracle_draft_sample.argtypes = [c.c_int] * 5 + [c.c_void_p] * 7 + [c.c_int]
         _lib = L
     return _lib
@@ -225,14 +225,15 @@ def tree_build(kconfig, max_nodes: int = 128):
     return parent[:n].copy(), depth[:n].copy(), q_row[:n + 1].copy()
 
 
-def kv_commit(k_prefix, v_prefix, k_tree, v_tree, n_accepted, accepted_path, out_tokens, prefix_len):
-    """Arrays [n_layers][B][H_kv][L_stride | N][d] (any 2- or 4-byte element type).  Returns new
-    (k_prefix, v_prefix, prefix_len, next_root, full); the inputs are not modified."""
+def kv_commit(k_prefix, v_prefix, k_tree, v_tree, n_accepted, accepted_path, out_tokens, prefix_len, root_row=False):
+    """Arrays [n_layers][B][H_kv][L_stride | N][d] (any 2- or 4-byte element type); with root_row
+    the tree arrays have 1 + N rows, row 0 = the root, which is committed ahead of the path.
+    Returns new (k_prefix, v_prefix, prefix_len, next_root, full); the inputs are not modified."""
     k_prefix, v_prefix = np.array(k_prefix, copy=True, order="C"), np.array(v_prefix, copy=True, order="C")
     k_tree, v_tree = np.ascontiguousarray(k_tree), np.ascontiguousarray(v_tree)
     n_layers, B, H_kv, L_stride, d = k_prefix.shape
-    N = k_tree.shape[3]
-    assert k_tree.shape == (n_layers, B, H_kv, N, d) and v_tree.shape == k_tree.shape and v_prefix.shape == k_prefix.shape
+    N = k_tree.shape[3] - (1 if root_row else 0)
+    assert k_tree.shape == (n_layers, B, H_kv, N + (1 if root_row else 0), d) and v_tree.shape == k_tree.shape and v_prefix.shape == k_prefix.shape
     assert k_prefix.dtype == k_tree.dtype == v_prefix.dtype == v_tree.dtype
     n_accepted = np.ascontiguousarray(n_accepted, dtype=np.int32).reshape(B)
     accepted_path = np.ascontiguousarray(accepted_path, dtype=np.int32)
@@ -241,7 +242,7 @@ def kv_commit(k_prefix, v_prefix, k_tree, v_tree, n_accepted, accepted_path, out
     prefix_len = np.array(prefix_len, dtype=np.int32, copy=True).reshape(B)
     next_root = np.empty(B, dtype=np.int32)
     full = np.empty(B, dtype=np.int32)
-    rc = lib().mcsd_oracle_kv_commit(n_layers, B, N, H_kv, d, k_prefix.dtype.itemsize, L_stride, gamma_max,
+    rc = lib().mcsd_oracle_kv_commit(n_layers, B, N, H_kv, d, k_prefix.dtype.itemsize, L_stride, gamma_max, 1 if root_row else 0,
                                      _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tree), _ptr(v_tree), _ptr(n_accepted),
                                      _ptr(accepted_path), _ptr(out_tokens), _ptr(prefix_len), _ptr(next_root),
                                      _ptr(full))

@@ -39,7 +39,7 @@ class McsdError(RuntimeError):
 class AttnDesc(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("B", C.c_int32), ("N", C.c_int32), ("H_q", C.c_int32),
                 ("H_kv", C.c_int32), ("d", C.c_int32), ("dtype", C.c_int32), ("L_stride", C.c_int32),
-                ("scale", C.c_float), ("parent_per_seq", C.c_int32)]
+                ("scale", C.c_float), ("parent_per_seq", C.c_int32), ("root_row", C.c_int32)]
 
 
 class AttnBufs(C.Structure):
@@ -81,7 +81,7 @@ class DraftBufs(C.Structure):
 class CommitDesc(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("B", C.c_int32), ("N", C.c_int32), ("H_kv", C.c_int32),
                 ("d", C.c_int32), ("dtype", C.c_int32), ("L_stride", C.c_int32), ("gamma_max", C.c_int32),
-                ("n_layers", C.c_int32)]
+                ("n_layers", C.c_int32), ("root_row", C.c_int32)]
 
 
 class CommitBufs(C.Structure):
@@ -127,7 +127,7 @@ def lib() -> C.CDLL:
         L.mcsd_draft_sample.restype = C.c_int32
         L.mcsd_tree_size.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.mcsd_tree_size.restype = C.c_int32
-        L.mcsd_tree_build.argtypes = [C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 5 + [C.c_void_p]
+        L.mcsd_tree_build.argtypes = [C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 5 + [C.c_int32, C.c_void_p]
         L.mcsd_tree_build.restype = C.c_int32
         L.mcsd_kv_commit.argtypes = [C.POINTER(CommitDesc), C.POINTER(CommitBufs), C.c_void_p]
         L.mcsd_kv_commit.restype = C.c_int32
@@ -188,9 +188,9 @@ class AttnArgs:
     keep: tuple       # tensors referenced by the raw pointers
 
 
-def attn_desc(B, N, H_q, H_kv, d, dtype, L_stride, scale, parent_per_seq=False) -> AttnDesc:
+def attn_desc(B, N, H_q, H_kv, d, dtype, L_stride, scale, parent_per_seq=False, root_row=False) -> AttnDesc:
     return AttnDesc(C.sizeof(AttnDesc), B, N, H_q, H_kv, d, dtype, L_stride, float(scale),
-                    1 if parent_per_seq else 0)
+                    1 if parent_per_seq else 0, 1 if root_row else 0)
 
 
 def mcsd_attn_workspace_bytes(desc: AttnDesc) -> int:
@@ -201,8 +201,10 @@ def mcsd_attn_workspace_bytes(desc: AttnDesc) -> int:
 def attn_args(q, k_prefix, v_prefix, prefix_len, k_tree, v_tree, parent, out, scale,
               workspace: Optional[torch.Tensor] = None) -> AttnArgs:
     """Shapes: q/out [B][N][H_q][d]; k/v_prefix [B][H_kv][L_stride][d]; k/v_tree [B][H_kv][N][d];
-    prefix_len int32 [B]; parent int32 [N] or [B][N]."""
+    prefix_len int32 [B]; parent int32 [N] or [B][N].  If q, out, k_tree and v_tree have one row
+    more than parent has entries, row 0 is the root (root_row = 1 in the descriptor)."""
     B, N, H_q, d = q.shape
+    root_row = parent.shape[-1] == N - 1
     H_kv, L_stride = k_prefix.shape[1], k_prefix.shape[2]
     if q.dtype == torch.float32:
         dt = DTYPE_FP32
@@ -216,9 +218,10 @@ def attn_args(q, k_prefix, v_prefix, prefix_len, k_tree, v_tree, parent, out, sc
         raise ValueError("k_tree / v_tree shape mismatch")
     if tuple(out.shape) != (B, N, H_q, d) or tuple(prefix_len.shape) != (B,):
         raise ValueError("out / prefix_len shape mismatch")
-    if tuple(parent.shape) not in ((N,), (B, N)):
+    Np = N - 1 if root_row else N
+    if tuple(parent.shape) not in ((Np,), (B, Np)):
         raise ValueError("parent must be [N] or [B][N]")
-    desc = attn_desc(B, N, H_q, H_kv, d, dt, L_stride, scale, parent.dim() == 2)
+    desc = attn_desc(B, Np, H_q, H_kv, d, dt, L_stride, scale, parent.dim() == 2, root_row)
     bufs = AttnBufs(C.sizeof(AttnBufs), _ptr(q, q.dtype, "q"), _ptr(k_prefix, q.dtype, "k_prefix"),
                     _ptr(v_prefix, q.dtype, "v_prefix"), _ptr(prefix_len, torch.int32, "prefix_len"),
                     _ptr(k_tree, q.dtype, "k_tree"), _ptr(v_tree, q.dtype, "v_tree"),
@@ -386,7 +389,7 @@ def mcsd_tree_size(kconfig) -> tuple:
 
 def mcsd_tree_build(kconfig, parent, depth, q_row, prefix_len=None, position_ids=None, stream=None) -> None:
     """kconfig: host sequence; parent/depth int32 [N], q_row int32 [1+N] device tensors;
-    position_ids int32 [B][N] (optional, needs prefix_len int32 [B])."""
+    position_ids int32 [B][N], or [B][1+N] with the root as entry 0 (optional, needs prefix_len int32 [B])."""
     import numpy as np
     kc = np.ascontiguousarray(kconfig, dtype=np.int32)
     N, _ = mcsd_tree_size(kc)
@@ -394,13 +397,15 @@ def mcsd_tree_build(kconfig, parent, depth, q_row, prefix_len=None, position_ids
     if tuple(parent.shape) != (N,) or tuple(depth.shape) != (N,) or tuple(q_row.shape) != (N + 1,):
         raise ValueError("parent / depth must be [N], q_row [1+N]")
     B = 1
+    root_row = 0
     if position_ids is not None:
         B = position_ids.shape[0]
-        if tuple(position_ids.shape) != (B, N) or prefix_len is None or tuple(prefix_len.shape) != (B,):
-            raise ValueError("position_ids must be [B][N] with prefix_len [B]")
+        root_row = 1 if position_ids.shape[1] == N + 1 else 0
+        if tuple(position_ids.shape) != (B, N + root_row) or prefix_len is None or tuple(prefix_len.shape) != (B,):
+            raise ValueError("position_ids must be [B][N] (or [B][1+N] with a root row) with prefix_len [B]")
     _check(lib().mcsd_tree_build(kc.ctypes.data_as(C.c_void_p), kc.shape[0], B, _ptr(prefix_len, i32, "prefix_len"),
                                  _ptr(parent, i32, "parent"), _ptr(depth, i32, "depth"), _ptr(q_row, i32, "q_row"),
-                                 _ptr(position_ids, i32, "position_ids"), _stream(stream)))
+                                 _ptr(position_ids, i32, "position_ids"), root_row, _stream(stream)))
 
 
 @dataclass
@@ -411,17 +416,17 @@ class CommitArgs:
 
 
 def commit_args(k_prefix, v_prefix, k_tree, v_tree, n_accepted, accepted_path, out_tokens, prefix_len,
-                next_root, flags) -> CommitArgs:
-    """k/v_prefix [n_layers][B][H_kv][L_stride][d] (or 4-D for one layer), k/v_tree [...][N][d];
-    n_accepted [B], accepted_path [B][gamma_max], out_tokens [B][gamma_max+1], prefix_len [B] (in/out),
-    next_root [B], flags [B]."""
+                next_root, flags, root_row: bool = False) -> CommitArgs:
+    """k/v_prefix [n_layers][B][H_kv][L_stride][d] (or 4-D for one layer), k/v_tree [...][N][d]
+    ([...][1+N][d] with root_row: row 0 = the root); n_accepted [B], accepted_path [B][gamma_max],
+    out_tokens [B][gamma_max+1], prefix_len [B] (in/out), next_root [B], flags [B]."""
     if k_prefix.dim() == 4:
         n_layers, (B, H_kv, L_stride, d) = 1, k_prefix.shape
     else:
         n_layers, B, H_kv, L_stride, d = k_prefix.shape
-    N = k_tree.shape[-2]
+    N = k_tree.shape[-2] - (1 if root_row else 0)
     lead = () if k_prefix.dim() == 4 else (n_layers,)
-    if tuple(v_prefix.shape) != tuple(k_prefix.shape) or tuple(k_tree.shape) != lead + (B, H_kv, N, d) or \
+    if tuple(v_prefix.shape) != tuple(k_prefix.shape) or tuple(k_tree.shape) != lead + (B, H_kv, N + (1 if root_row else 0), d) or \
             tuple(v_tree.shape) != tuple(k_tree.shape):
         raise ValueError("cache shape mismatch")
     gamma_max = accepted_path.shape[1]
@@ -436,7 +441,7 @@ def commit_args(k_prefix, v_prefix, k_tree, v_tree, n_accepted, accepted_path, o
     else:
         raise ValueError(f"unsupported dtype {k_prefix.dtype}")
     i32 = torch.int32
-    desc = CommitDesc(C.sizeof(CommitDesc), B, N, H_kv, d, dt, L_stride, gamma_max, n_layers)
+    desc = CommitDesc(C.sizeof(CommitDesc), B, N, H_kv, d, dt, L_stride, gamma_max, n_layers, 1 if root_row else 0)
     bufs = CommitBufs(C.sizeof(CommitBufs), _ptr(k_prefix, k_prefix.dtype, "k_prefix"),
                       _ptr(v_prefix, k_prefix.dtype, "v_prefix"), _ptr(k_tree, k_prefix.dtype, "k_tree"),
                       _ptr(v_tree, k_prefix.dtype, "v_tree"), _ptr(n_accepted, i32, "n_accepted"),
@@ -452,14 +457,14 @@ def mcsd_kv_commit(args: CommitArgs, stream=None) -> None:
 
 
 def paged_commit_args(k_pool, v_pool, block_table, k_tree, v_tree, n_accepted, accepted_path, out_tokens, prefix_len,
-                      next_root, flags, L_stride: int):
+                      next_root, flags, L_stride: int, root_row: bool = False):
     """Like commit_args with the destination in pools [n_layers][n_pages][H_kv][page_size][d] (or 4-D
     for one layer) and block_table int32 [B][max_pages_per_seq].  Returns (CommitArgs, PagedKV)."""
     if k_pool.dim() == 4:
         n_layers, (n_pages, H_kv, page_size, d) = 1, k_pool.shape
     else:
         n_layers, n_pages, H_kv, page_size, d = k_pool.shape
-    B, N = k_tree.shape[-4], k_tree.shape[-2]
+    B, N = k_tree.shape[-4], k_tree.shape[-2] - (1 if root_row else 0)
     gamma_max = accepted_path.shape[1]
     if k_pool.dtype == torch.float32:
         dt = DTYPE_FP32
@@ -472,7 +477,7 @@ def paged_commit_args(k_pool, v_pool, block_table, k_tree, v_tree, n_accepted, a
     if block_table.dim() != 2 or block_table.shape[0] != B:
         raise ValueError("block_table must be [B][max_pages_per_seq]")
     i32 = torch.int32
-    desc = CommitDesc(C.sizeof(CommitDesc), B, N, H_kv, d, dt, L_stride, gamma_max, n_layers)
+    desc = CommitDesc(C.sizeof(CommitDesc), B, N, H_kv, d, dt, L_stride, gamma_max, n_layers, 1 if root_row else 0)
     bufs = CommitBufs(C.sizeof(CommitBufs), _ptr(k_pool, k_pool.dtype, "k_pool"), _ptr(v_pool, k_pool.dtype, "v_pool"),
                       _ptr(k_tree, k_pool.dtype, "k_tree"), _ptr(v_tree, k_pool.dtype, "v_tree"),
                       _ptr(n_accepted, i32, "n_accepted"), _ptr(accepted_path, i32, "accepted_path"),

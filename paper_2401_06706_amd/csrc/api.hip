@@ -114,7 +114,8 @@ static int32_t check_attn(const mcsd_attn_desc *d, const mcsd_attn_bufs *b, Attn
     if (d->struct_size != sizeof(mcsd_attn_desc)) { set_error("attn desc struct_size %u != %zu", d->struct_size, sizeof(mcsd_attn_desc)); return MCSD_E_SHAPE; }
     if (d->B < 1 || d->H_q < 1 || d->H_kv < 1 || d->d < 1 || d->L_stride < 0) { set_error("attn: non-positive size"); return MCSD_E_SHAPE; }
     if (d->L_stride > (1 << 22)) { set_error("attn: L_stride %d > %d", d->L_stride, 1 << 22); return MCSD_E_UNSUPPORTED; }
-    if (d->N < 1 || d->N > MCSD_MAX_NODES) { set_error("attn: N %d outside 1..%d", d->N, MCSD_MAX_NODES); return MCSD_E_TREE; }
+    if (d->root_row != 0 && d->root_row != 1) { set_error("attn: root_row must be 0 or 1"); return MCSD_E_SHAPE; }
+    if (d->N < 1 || d->N + d->root_row > MCSD_MAX_NODES) { set_error("attn: N %d (+ root row) outside 1..%d", d->N, MCSD_MAX_NODES); return MCSD_E_TREE; }
     if (d->H_q % d->H_kv != 0) { set_error("attn: H_q %d not a multiple of H_kv %d", d->H_q, d->H_kv); return MCSD_E_SHAPE; }
     if (d->dtype != MCSD_DTYPE_FP32 && d->dtype != MCSD_DTYPE_BF16) { set_error("attn: unknown dtype %d", d->dtype); return MCSD_E_UNSUPPORTED; }
     if (d->d > MCSD_MAX_HEAD_DIM || d->d % (d->dtype == MCSD_DTYPE_BF16 ? 8 : 4) != 0) { set_error("attn: head dim %d unsupported", d->d); return MCSD_E_UNSUPPORTED; }
@@ -307,15 +308,16 @@ int32_t mcsd_tree_size(const int32_t *kconfig, int32_t gamma, int32_t *n_nodes, 
 }
 
 int32_t mcsd_tree_build(const int32_t *kconfig, int32_t gamma, int32_t B, const int32_t *prefix_len, int32_t *parent,
-                        int32_t *depth, int32_t *q_row, int32_t *position_ids, void *stream)
+                        int32_t *depth, int32_t *q_row, int32_t *position_ids, int32_t root_row, void *stream)
 {
+    if (root_row != 0 && root_row != 1) { set_error("tree: root_row must be 0 or 1"); return MCSD_E_SHAPE; }
     int32_t n = 0;
     int32_t rc = mcsd_tree_size(kconfig, gamma, &n, nullptr);
     if (rc != MCSD_OK) return rc;
     if (!parent || !depth || !q_row) { set_error("tree: NULL output"); return MCSD_E_NULL; }
     if (position_ids && !prefix_len) { set_error("tree: position_ids needs prefix_len"); return MCSD_E_NULL; }
     if (position_ids && (B < 1 || B > 65535)) { set_error("tree: B %d outside 1..65535", B); return MCSD_E_SHAPE; }
-    return launch_tree_build(kconfig, gamma, n, B, prefix_len, parent, depth, q_row, position_ids, (hipStream_t)stream);
+    return launch_tree_build(kconfig, gamma, n, B, prefix_len, parent, depth, q_row, position_ids, root_row, (hipStream_t)stream);
 }
 
 static int32_t check_commit(const mcsd_commit_desc *d, const mcsd_commit_bufs *b)
@@ -323,7 +325,8 @@ static int32_t check_commit(const mcsd_commit_desc *d, const mcsd_commit_bufs *b
     if (!d) { set_error("commit desc is NULL"); return MCSD_E_NULL; }
     if (d->struct_size != sizeof(mcsd_commit_desc)) { set_error("commit desc struct_size %u != %zu", d->struct_size, sizeof(mcsd_commit_desc)); return MCSD_E_SHAPE; }
     if (d->B < 1 || d->H_kv < 1 || d->d < 1 || d->L_stride < 1 || d->gamma_max < 1 || d->n_layers < 1) { set_error("commit: non-positive size"); return MCSD_E_SHAPE; }
-    if (d->N < 1 || d->N > MCSD_MAX_NODES) { set_error("commit: N %d outside 1..%d", d->N, MCSD_MAX_NODES); return MCSD_E_TREE; }
+    if (d->root_row != 0 && d->root_row != 1) { set_error("commit: root_row must be 0 or 1"); return MCSD_E_SHAPE; }
+    if (d->N < 1 || d->N + d->root_row > MCSD_MAX_NODES) { set_error("commit: N %d (+ root row) outside 1..%d", d->N, MCSD_MAX_NODES); return MCSD_E_TREE; }
     if (d->dtype != MCSD_DTYPE_FP32 && d->dtype != MCSD_DTYPE_BF16) { set_error("commit: unknown dtype %d", d->dtype); return MCSD_E_UNSUPPORTED; }
     const int esize = d->dtype == MCSD_DTYPE_FP32 ? 4 : 2;
     if ((d->d * esize) % 16 != 0) { set_error("commit: d * element size must be a multiple of 16 bytes"); return MCSD_E_SHAPE; }

@@ -106,7 +106,7 @@ int32_t launch_draft_sample(const mcsd_draft_desc &d, const mcsd_draft_bufs &b, 
 // ---- candidate tree and KV commit -----------------------------------------
 constexpr int MAX_GAMMA = 16;
 int32_t launch_tree_build(const int32_t *kconfig, int gamma, int n_nodes, int B, const int32_t *prefix_len,
-                          int32_t *parent, int32_t *depth, int32_t *q_row, int32_t *position_ids, hipStream_t stream);
+                          int32_t *parent, int32_t *depth, int32_t *q_row, int32_t *position_ids, int root_row, hipStream_t stream);
 int32_t launch_kv_commit(const mcsd_commit_desc &d, const mcsd_commit_bufs &b, hipStream_t stream,
                          const mcsd_paged_kv *paged = nullptr);
 

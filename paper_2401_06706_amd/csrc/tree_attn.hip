@@ -53,6 +53,7 @@ struct AttnParams {
     float *part_m, *part_l, *part_o;
     int B, N, H_q, H_kv, G, d, L_stride, M;
     int n_row_tiles, chunk_tiles, n_chunks_max, tiles_tree, parent_per_seq, dtype;
+    int root_row;         // 1: row 0 of the tree block is the root, N counts it
     int R;                // rows per (b, g) in the partial buffers
     int split_bias;       // see split_tiles
     float scale_log2;     // scale * log2(e)
@@ -108,11 +109,20 @@ __device__ __forceinline__ void split_tiles(int T, int chunk_tiles, int bias, in
 
 // anc[i] = {i} U anc[parent[i]]: one 128-bit mask per node, built by walking up.  The parent
 // array is copied to LDS with one coalesced load first, so that the walk (one dependent read
-// per level) does not pay a global-memory latency per step.  Contains a workgroup barrier;
-// the caller adds the one that publishes the masks.
-__device__ __forceinline__ void build_ancestor_masks(const int32_t *parent, int N, uint32_t (*s_anc)[4], int *s_parent)
+// per level) does not pay a global-memory latency per step.  With a root row the tree block has
+// N rows of which row 0 is the root and row 1 + i candidate i: the root is every candidate's
+// ancestor, and the caller's array (N - 1 entries, -1 = child of the root) is shifted by one.
+// Contains a workgroup barrier; the caller adds the one that publishes the masks.
+__device__ __forceinline__ void build_ancestor_masks(const int32_t *parent, int N, int root_row, uint32_t (*s_anc)[4], int *s_parent)
 {
-    for (int i = threadIdx.x; i < MCSD_MAX_NODES; i += blockDim.x) s_parent[i] = (i < N) ? parent[i] : -1;
+    for (int i = threadIdx.x; i < MCSD_MAX_NODES; i += blockDim.x) {
+        int pa = -1;
+        if (i < N) {
+            if (!root_row) pa = parent[i];
+            else if (i > 0) pa = max(parent[i - 1], -1) + 1;
+        }
+        s_parent[i] = pa;
+    }
     __syncthreads();
     for (int i = threadIdx.x; i < MCSD_MAX_NODES; i += blockDim.x) {
         uint32_t m[4] = {0u, 0u, 0u, 0u};
@@ -432,7 +442,7 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
         const bool wave_active = !COOP || row0 + WROWS * rh < p.M;     // a wave whose rows all lie past M only helps to load
         // the masks are needed from the first tree tile on; built while the first loads are in flight
         if (t_end > tilesP) {
-            build_ancestor_masks(p.parent + (p.parent_per_seq ? (size_t)b * p.N : 0), p.N, s_anc, s_parent);
+            build_ancestor_masks(p.parent + (p.parent_per_seq ? (size_t)b * (p.N - p.root_row) : 0), p.N, p.root_row, s_anc, s_parent);
             __syncthreads();
         }
         auto tile_step = [&](const int t, auto stage) __attribute__((always_inline)) {
@@ -879,7 +889,7 @@ __global__ __launch_bounds__(256) void tree_attn_generic_kernel(AttnParams p)
     __shared__ uint32_t s_anc[MCSD_MAX_NODES][4];
     __shared__ int s_parent[MCSD_MAX_NODES];
 
-    build_ancestor_masks(p.parent + (p.parent_per_seq ? (size_t)b * p.N : 0), p.N, s_anc, s_parent);
+    build_ancestor_masks(p.parent + (p.parent_per_seq ? (size_t)b * (p.N - p.root_row) : 0), p.N, p.root_row, s_anc, s_parent);
     const T *qp = static_cast<const T *>(p.q) + (((size_t)b * p.N + node) * p.H_q + h) * (size_t)d;
     for (int c = tid; c < d; c += 256) s_q[c] = load_as_float<T>(qp, c);
     __syncthreads();
@@ -962,7 +972,8 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
 {
     AttnPlan pl = {};
     const int G = d.H_q / d.H_kv;
-    pl.rows_per_kv = d.N * G;
+    const int n_rows_tree = d.N + (d.root_row ? 1 : 0);      // rows of the tree block
+    pl.rows_per_kv = n_rows_tree * G;
     pl.use_mfma = (d.dtype == MCSD_DTYPE_BF16 && d.d == 128);
     if (!pl.use_mfma) {
         if (d.d > MCSD_MAX_HEAD_DIM) return false;
@@ -983,7 +994,7 @@ bool make_attn_plan(const mcsd_attn_desc &d, AttnPlan *plan)
     const int key_streams = 4 >> pl.variant;
     pl.n_row_tiles = (pl.rows_per_kv + pl.row_tile - 1) / pl.row_tile;
     pl.tiles_prefix_max = (d.L_stride + KT - 1) / KT;
-    pl.tiles_tree = (d.N + KT - 1) / KT;
+    pl.tiles_tree = (n_rows_tree + KT - 1) / KT;
     const long total_max = pl.tiles_prefix_max + pl.tiles_tree;
     const long units = (long)d.B * d.H_kv * pl.n_row_tiles;
     // Every segment pays a fixed prologue (Q, first tiles) and epilogue (merge, possibly one
@@ -1038,13 +1049,14 @@ int32_t launch_tree_attn(const mcsd_attn_desc &d, const mcsd_attn_bufs &b, const
     }
     p.q = b.q; p.k_prefix = b.k_prefix; p.v_prefix = b.v_prefix; p.k_tree = b.k_tree; p.v_tree = b.v_tree;
     p.prefix_len = b.prefix_len; p.parent = b.parent; p.out = b.out;
-    p.B = d.B; p.N = d.N; p.H_q = d.H_q; p.H_kv = d.H_kv; p.G = d.H_q / d.H_kv; p.d = d.d;
+    p.root_row = d.root_row ? 1 : 0;
+    p.B = d.B; p.N = d.N + p.root_row; p.H_q = d.H_q; p.H_kv = d.H_kv; p.G = d.H_q / d.H_kv; p.d = d.d;
     p.L_stride = d.L_stride; p.M = plan.rows_per_kv; p.parent_per_seq = d.parent_per_seq; p.dtype = d.dtype;
     p.scale_log2 = d.scale * LOG2E_F;
     hipError_t e;
     if (!plan.use_mfma) {
-        if (d.H_q > 2147483647 || d.N > 65535 || d.B > 65535) { set_error("attn: grid too large"); return MCSD_E_UNSUPPORTED; }
-        dim3 grid(d.H_q, d.N, d.B), block(256);
+        if (d.H_q > 2147483647 || d.B > 65535) { set_error("attn: grid too large"); return MCSD_E_UNSUPPORTED; }
+        dim3 grid(d.H_q, p.N, d.B), block(256);
         if (d.dtype == MCSD_DTYPE_FP32)
             launch_kernel(K_ATTN_GENERIC, tree_attn_generic_kernel<float>, grid, block, stream, p);
         else

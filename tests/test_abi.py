@@ -39,7 +39,7 @@ def test_exports_every_declared_symbol(lib):
 
 def test_struct_layout_matches_header(tmp_path):
     """Compile a C program against the header and compare sizeof/offsetof with ctypes."""
-    fields = {"mcsd_attn_desc": (M.AttnDesc, ["struct_size", "B", "d", "L_stride", "scale", "parent_per_seq"]),
+    fields = {"mcsd_attn_desc": (M.AttnDesc, ["struct_size", "B", "d", "L_stride", "scale", "parent_per_seq", "root_row"]),
               "mcsd_attn_bufs": (M.AttnBufs, ["q", "prefix_len", "out", "workspace", "workspace_bytes"]),
               "mcsd_verify_desc": (M.VerifyDesc, ["V", "P", "variant", "gamma_max", "near_tie_eps", "parent_per_seq"]),
               "mcsd_verify_bufs": (M.VerifyBufs, ["target_logits", "temperature", "acc_child", "ratio",
@@ -47,7 +47,7 @@ def test_struct_layout_matches_header(tmp_path):
               "mcsd_paged_kv": (M.PagedKV, ["page_size", "n_pages", "max_pages_per_seq", "block_table"]),
               "mcsd_draft_desc": (M.DraftDesc, ["B", "V", "P", "variant", "near_tie_eps", "parent_per_seq"]),
               "mcsd_draft_bufs": (M.DraftBufs, ["draft_logits", "q_row", "u_draw", "temperature", "cand_tok", "flags"]),
-              "mcsd_commit_desc": (M.CommitDesc, ["B", "H_kv", "dtype", "L_stride", "gamma_max", "n_layers"]),
+              "mcsd_commit_desc": (M.CommitDesc, ["B", "H_kv", "dtype", "L_stride", "gamma_max", "n_layers", "root_row"]),
               "mcsd_commit_bufs": (M.CommitBufs, ["k_prefix", "v_tree", "n_accepted", "out_tokens", "prefix_len",
                                                   "next_root", "flags"])}
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "mcsd.h"', "int main(void){"]
@@ -198,9 +198,10 @@ def test_tree_size_and_build_errors(lib):
     kc = np.array([2, 2], np.int32)
     kp = kc.ctypes.data_as(C.c_void_p)
     assert lib.mcsd_tree_size(None, 2, None, None) == -1
-    assert lib.mcsd_tree_build(kp, 2, 1, None, None, 4096, 4096, None, None) == -1      # NULL output
-    assert lib.mcsd_tree_build(kp, 2, 1, None, 4096, 4096, 4096, 4096, None) == -1      # position ids without prefix_len
-    assert lib.mcsd_tree_build(kp, 2, 0, 4096, 4096, 4096, 4096, 4096, None) == -2      # B = 0 with position ids
+    assert lib.mcsd_tree_build(kp, 2, 1, None, None, 4096, 4096, None, 0, None) == -1      # NULL output
+    assert lib.mcsd_tree_build(kp, 2, 1, None, 4096, 4096, 4096, 4096, 0, None) == -1      # position ids without prefix_len
+    assert lib.mcsd_tree_build(kp, 2, 0, 4096, 4096, 4096, 4096, 4096, 0, None) == -2      # B = 0 with position ids
+    assert lib.mcsd_tree_build(kp, 2, 1, 4096, 4096, 4096, 4096, 4096, 2, None) == -2      # root_row is 0 or 1
 
 
 def test_commit_descriptor_errors(lib):

@@ -235,3 +235,49 @@ def test_plan_override_rejects_bad_values():
     with pytest.raises(M.McsdError):
         M.mcsd_attn_plan_override(0, -1, 0)
     M.mcsd_attn_plan_override(0, 0, 0)
+
+
+def add_root_rows(ai, rng):
+    """The same problem with the root as row 0 of the tree block (q, k_tree, v_tree get one more row)."""
+    def one_more(a, axis):
+        shape = list(a.shape)
+        shape[axis] = 1
+        if ai.dtype == "bf16":
+            extra = W.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
+        else:
+            extra = rng.standard_normal(shape).astype(np.float32)
+        return np.ascontiguousarray(np.concatenate([extra, a], axis=axis))
+    return one_more(ai.q, 1), one_more(ai.k_tree, 2), one_more(ai.v_tree, 2)
+
+
+@pytest.mark.parametrize("H_q,H_kv,kconfig,prefix", [(4, 4, (4, 2, 2), (100, 300)), (8, 1, (4, 2, 2), (0, 900)),
+                                                     (2, 2, (127,), (40, 40)), (6, 2, (3, 2, 1), (2000, 2100)), (2, 2, (2, 2), (5, 9))])
+def test_root_row(H_q, H_kv, kconfig, prefix):
+    """root_row = 1: the root is row 0 of the tree block and every candidate's ancestor.  Equal, bit
+    for bit, to the same tree written out with the root as an ordinary node 0, and to the oracle
+    on that tree; 128 rows (127 candidates) is the largest tree block."""
+    rng = np.random.default_rng(H_q * 100 + len(kconfig))
+    dtype = "fp32" if kconfig == (2, 2) else "bf16"
+    ai = W.gen_attn_inputs(wl(H_q=H_q, H_kv=H_kv, kconfig=kconfig, prefix=prefix, B=3, dtype=dtype, d=128), rng,
+                           L_stride=prefix[1])
+    q, kt, vt = add_root_rows(ai, rng)
+    parent_ext = np.concatenate([[-1], ai.parent.astype(np.int64) + 1]).astype(np.int32)
+    ref = O.tree_attn(q, ai.k_prefix, ai.v_prefix, ai.prefix_len, kt, vt, parent_ext, ai.scale,
+                      O.FP32 if dtype == "fp32" else O.BF16, n_threads=16)
+    base = D.make_attn_call(ai)
+    t = base.tensors
+    to_dev = lambda a: D._to_device(a, dtype, "cuda:0")
+    tq, tkt, tvt = to_dev(q), to_dev(kt), to_dev(vt)
+    outs = []
+    for parent in (ai.parent.astype(np.int32), parent_ext):           # root row / root as node 0
+        out = torch.full_like(tq, 7.0)
+        tp = torch.from_numpy(parent).to("cuda:0")
+        desc_probe = M.attn_args(tq, t["k_prefix"], t["v_prefix"], t["prefix_len"], tkt, tvt, tp, out, ai.scale).desc
+        ws = torch.empty(max(M.mcsd_attn_workspace_bytes(desc_probe), 256), dtype=torch.uint8, device="cuda:0")
+        args = M.attn_args(tq, t["k_prefix"], t["v_prefix"], t["prefix_len"], tkt, tvt, tp, out, ai.scale, workspace=ws)
+        assert args.desc.root_row == (1 if parent is not parent_ext else 0) and args.desc.N + args.desc.root_row == ai.N + 1
+        M.mcsd_tree_attn(args)
+        torch.cuda.synchronize()
+        outs.append(out)
+    assert torch.equal(outs[0].view(torch.int16) if dtype == "bf16" else outs[0], outs[1].view(torch.int16) if dtype == "bf16" else outs[1])
+    assert_attn_close(outs[0].float().cpu().numpy().astype(np.float64), ref, dtype, f"root row {kconfig} {H_q}/{H_kv}")

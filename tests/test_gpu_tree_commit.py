@@ -119,7 +119,12 @@ def test_kv_commit_flags_bad_path_entries():
 
 def test_decode_loop_three_steps_matches_oracle_loop():
     """tree build -> draft sample -> attention + verification -> commit, three times, all on one
-    stream with no host reads in between; then the same loop through the oracle."""
+    stream with no host reads in between; then the same loop through the oracle.  The root of a
+    step (the endpoint token of the step before) goes through the step's forward pass with the
+    candidates: it is row 0 of the tree block (root_row = 1), every candidate attends to it, and
+    the commit appends it ahead of the accepted path.  From the second step on, the attention of
+    every row is also compared with textbook causal attention over the sequence generated so
+    far (context, earlier roots and accepted tokens, this step's root, the row's own path)."""
     rng = np.random.default_rng(77)
     kconfig = (3, 2, 2)
     B, H_q, H_kv, d, Ls, V, steps = 3, 4, 2, 128, 64, 2048, 3
@@ -138,8 +143,8 @@ def test_decode_loop_three_steps_matches_oracle_loop():
             if tree.q_row[row] >= 0:
                 zq[:, tree.q_row[row]] = zp[:, row] + rng.standard_normal((B, V)).astype(np.float32)
         per_step.append(dict(
-            q=bf(rng.standard_normal((B, N, H_q, d))), kt=bf(rng.standard_normal((B, H_kv, N, d))),
-            vt=bf(rng.standard_normal((B, H_kv, N, d))),
+            q=bf(rng.standard_normal((B, 1 + N, H_q, d))), kt=bf(rng.standard_normal((B, H_kv, 1 + N, d))),
+            vt=bf(rng.standard_normal((B, H_kv, 1 + N, d))),
             zp=zp, zq=zq,
             u_draw=W.open_uniform(rng, (B, N)), u_acc=W.open_uniform(rng, (B, N)), u_end=W.open_uniform(rng, (B, 1 + N))))
     variant = W.WITHOUT_REPLACEMENT
@@ -152,7 +157,7 @@ def test_decode_loop_three_steps_matches_oracle_loop():
     parent = torch.empty(N, dtype=torch.int32, device=DEV)
     depth = torch.empty(N, dtype=torch.int32, device=DEV)
     q_row = torch.empty(N + 1, dtype=torch.int32, device=DEV)
-    pos = torch.empty((B, N), dtype=torch.int32, device=DEV)
+    pos = torch.empty((B, 1 + N), dtype=torch.int32, device=DEV)
     t_temp = torch.from_numpy(temp).to(DEV)
     i32 = dict(dtype=torch.int32, device=DEV)
     gpu_log = []
@@ -162,9 +167,10 @@ def test_decode_loop_three_steps_matches_oracle_loop():
         M.mcsd_tree_build(kconfig, parent, depth, q_row, prefix_len=t_L, position_ids=pos)
         t_q, t_kt, t_vt = up_bf(x["q"]), up_bf(x["kt"]), up_bf(x["vt"])
         out = torch.empty_like(t_q)
-        desc = M.attn_desc(B, N, H_q, H_kv, d, M.DTYPE_BF16, Ls, 1.0 / np.sqrt(d))
+        desc = M.attn_desc(B, N, H_q, H_kv, d, M.DTYPE_BF16, Ls, 1.0 / np.sqrt(d), root_row=True)
         ws = torch.empty(max(M.mcsd_attn_workspace_bytes(desc), 256), dtype=torch.uint8, device=DEV)
         a_args = M.attn_args(t_q, t_kp, t_vp, t_L, t_kt, t_vt, parent, out, 1.0 / np.sqrt(d), workspace=ws)
+        assert a_args.desc.root_row == 1 and a_args.desc.N == N
         t_zq = torch.from_numpy(x["zq"]).to(DEV)
         cand = torch.full((B, N), -5, **i32)
         dfl = torch.empty((B, N), **i32)
@@ -175,7 +181,8 @@ def test_decode_loop_three_steps_matches_oracle_loop():
                                torch.from_numpy(x["u_acc"]).to(DEV), torch.from_numpy(x["u_end"]).to(DEV), t_temp,
                                n_acc, path, otok, acc, endp, vfl, variant)
         nxt = torch.empty((B,), **i32); cfl = torch.empty((B,), **i32)
-        c_args = M.commit_args(t_kp, t_vp, t_kt, t_vt, n_acc, path, otok, t_L, nxt, cfl)
+        c_args = M.commit_args(t_kp, t_vp, t_kt, t_vt, n_acc, path, otok, t_L, nxt, cfl, root_row=True)
+        assert c_args.desc.root_row == 1 and c_args.desc.N == N
         M.mcsd_draft_sample(d_args)
         M.mcsd_verify_step(a_args, v_args)
         M.mcsd_kv_commit(c_args)
@@ -189,13 +196,34 @@ def test_decode_loop_three_steps_matches_oracle_loop():
         x = per_step[s]
         out, cand, n_acc, path, otok, nxt, cfl, pos_s, dfl, vfl = [t.cpu() for t in gpu_log[s]]
         rp, rd, rq = O.tree_build(kconfig)
-        np.testing.assert_array_equal(pos_s.numpy(), L[:, None] + rd[None, :] - 1)
+        np.testing.assert_array_equal(pos_s.numpy()[:, 0], L)                       # the root: first token after the cache
+        np.testing.assert_array_equal(pos_s.numpy()[:, 1:], L[:, None] + rd[None, :])
+        rp_ext = np.concatenate([[-1], rp.astype(np.int64) + 1]).astype(np.int32)   # the tree with its root as node 0
         r_cand, r_dm = O.draft_sample(x["zq"], rq, rp, x["u_draw"], temp, variant)
         assert (r_dm >= 1e-6).all(), "pick another seed: a draw sits on a CDF edge"
         np.testing.assert_array_equal(cand.numpy(), r_cand)
-        ref_attn = O.tree_attn(x["q"], kp, vp, L, x["kt"], x["vt"], rp, 1.0 / np.sqrt(d), O.BF16, n_threads=8)
+        ref_attn = O.tree_attn(x["q"], kp, vp, L, x["kt"], x["vt"], rp_ext, 1.0 / np.sqrt(d), O.BF16, n_threads=8)
         got_attn = W.bf16_bits_to_f32(out.view(torch.int16).numpy().view(np.uint16))
         assert_attn_close(got_attn, ref_attn, "bf16", f"decode loop step {s}")
+        if s >= 1:
+            # causal attention over the generated sequence: cache rows [0, L) hold context, the
+            # earlier roots and accepted tokens; then this step's root and the row's path
+            f64 = lambda a: W.bf16_bits_to_f32(a).astype(np.float64)
+            seq_ref = np.zeros((1 + N, d))
+            b0, h0 = 0, 1
+            g0 = h0 // (H_q // H_kv)
+            for r in range(1 + N):
+                chain, a = [], r
+                while a >= 0:
+                    chain.append(a)
+                    a = int(rp_ext[a])
+                K = np.concatenate([f64(kp[b0, g0, :L[b0]]), f64(x["kt"][b0, g0, chain[::-1]])])
+                Vv = np.concatenate([f64(vp[b0, g0, :L[b0]]), f64(x["vt"][b0, g0, chain[::-1]])])
+                sc = (K @ f64(x["q"][b0, r, h0])) / np.sqrt(d)
+                wgt = np.exp(sc - sc.max())
+                seq_ref[r] = (wgt / wgt.sum()) @ Vv
+            assert np.abs(seq_ref - ref_attn[b0, :, h0]).max() < 1e-12
+            assert_attn_close(got_attn[b0, :, h0], seq_ref, "bf16", f"step {s}: causal attention over the generated sequence")
         rv = O.verify(x["zp"], x["zq"], rq, rp, r_cand, x["u_acc"], x["u_end"], temp, variant, gamma_max=gamma, n_threads=8)
         on_path_rows = [[0] + [1 + int(c) for c in rv.accepted_path[b] if c >= 0] for b in range(B)]
         for b in range(B):
@@ -204,14 +232,14 @@ def test_decode_loop_three_steps_matches_oracle_loop():
         np.testing.assert_array_equal(path.numpy(), rv.accepted_path)
         np.testing.assert_array_equal(otok.numpy(), rv.out_tokens)
         kp1, vp1, L1, r_nxt, r_full = O.kv_commit(kp[None], vp[None], x["kt"][None], x["vt"][None], rv.n_accepted,
-                                                  rv.accepted_path, rv.out_tokens, L)
+                                                  rv.accepted_path, rv.out_tokens, L, root_row=True)
         kp, vp, L = kp1[0], vp1[0], L1
         np.testing.assert_array_equal(nxt.numpy(), r_nxt)
         assert (cfl.numpy() == 0).all() and (r_full == 0).all()
     np.testing.assert_array_equal(t_L.cpu().numpy(), L)
     np.testing.assert_array_equal(t_kp.view(torch.int16).cpu().numpy().view(np.uint16), kp)
     np.testing.assert_array_equal(t_vp.view(torch.int16).cpu().numpy().view(np.uint16), vp)
-    assert (L > L0).all() and (L - L0).sum() >= 6
+    assert (L >= L0 + steps).all() and (L - L0).sum() >= 6 + B * steps
 
 
 @pytest.mark.parametrize("page_size,n_layers", [(32, 1), (64, 3)])
@@ -280,3 +308,60 @@ def test_kv_commit_paged_stops_at_a_table_entry_outside_the_pool():
     np.testing.assert_array_equal(got[0, 0, :, 31], kt[0, 0, :, paths[0, 1]])
     np.testing.assert_array_equal(got[0, 1, :, 10:13], kt[0, 1][:, paths[1]])
     assert not got[0, 2].any()
+
+
+@pytest.mark.parametrize("dtype,n_layers,B,H_kv,d,kconfig", [("bf16", 2, 5, 4, 128, (4, 2, 2, 1)), ("fp32", 1, 3, 2, 16, (2, 2))])
+def test_kv_commit_with_root_row_matches_oracle(dtype, n_layers, B, H_kv, d, kconfig):
+    """The tree block carries the root as row 0: the commit appends the root, then the path; a cache
+    with room for the path but not for the root as well is left alone; contiguous and paged."""
+    rng = np.random.default_rng(B * 7 + d)
+    gamma = len(kconfig)
+    Ls = 64
+    L = rng.integers(0, Ls - gamma - 1, B).astype(np.int32)
+    n_acc = rng.integers(0, gamma + 1, B).astype(np.int32)
+    L[0], n_acc[0] = Ls - gamma, gamma                 # the path alone would fit, root + path does not
+    L[1], n_acc[1] = Ls - 1, 0                          # exactly room for the root
+    kp, vp, kt0, vt0, paths, out_tok, N, _ = make_commit_case(rng, n_layers, B, H_kv, d, Ls, kconfig, dtype, L, n_acc)
+    def root_first(a):
+        extra = rng.standard_normal((n_layers, B, H_kv, 1, d)).astype(np.float32) if dtype == "fp32" else \
+            rng.integers(0, 0x7f7f, (n_layers, B, H_kv, 1, d)).astype(np.uint16)
+        return np.ascontiguousarray(np.concatenate([extra, a], axis=3))
+    kt, vt = root_first(kt0), root_first(vt0)
+    ref = O.kv_commit(kp, vp, kt, vt, n_acc, paths, out_tok, L, root_row=True)
+    assert ref[4][0] == 1 and ref[4][1] == 0 and ref[2][1] == Ls
+    def up(a):
+        t = torch.from_numpy(a.view(np.int16) if dtype == "bf16" else a).to(DEV)
+        return t.view(torch.bfloat16) if dtype == "bf16" else t
+    def down(t):
+        return t.view(torch.int16).cpu().numpy().view(np.uint16) if dtype == "bf16" else t.cpu().numpy()
+    t_kp, t_vp, t_L = up(kp), up(vp), dev_i32(L)
+    nxt = torch.full((B,), -9, dtype=torch.int32, device=DEV)
+    fl = torch.full((B,), -9, dtype=torch.int32, device=DEV)
+    args = M.commit_args(t_kp, t_vp, up(kt), up(vt), dev_i32(n_acc), dev_i32(paths), dev_i32(out_tok), t_L, nxt, fl, root_row=True)
+    M.mcsd_kv_commit(args)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(down(t_kp), ref[0])
+    np.testing.assert_array_equal(down(t_vp), ref[1])
+    np.testing.assert_array_equal(t_L.cpu().numpy(), ref[2])
+    np.testing.assert_array_equal(nxt.cpu().numpy(), ref[3])
+    np.testing.assert_array_equal(fl.cpu().numpy() != 0, ref[4] != 0)
+    # the same into a page pool
+    page_size, per_seq = 32, 2
+    n_pages = B * per_seq + 1
+    table = rng.permutation(n_pages)[: B * per_seq].reshape(B, per_seq).astype(np.int32)
+    kpool = np.zeros((n_layers, n_pages, H_kv, page_size, d), kp.dtype)
+    vpool = np.zeros_like(kpool)
+    for layer in range(n_layers):
+        for b in range(B):
+            for pg in range(per_seq):
+                kpool[layer, table[b, pg]] = kp[layer, b, :, pg * page_size:(pg + 1) * page_size]
+                vpool[layer, table[b, pg]] = vp[layer, b, :, pg * page_size:(pg + 1) * page_size]
+    t_kpool, t_vpool, t_L2 = up(kpool), up(vpool), dev_i32(L)
+    pargs, paged = M.paged_commit_args(t_kpool, t_vpool, dev_i32(table), up(kt), up(vt), dev_i32(n_acc), dev_i32(paths),
+                                       dev_i32(out_tok), t_L2, nxt, fl, Ls, root_row=True)
+    M.mcsd_kv_commit_paged(pargs, paged)
+    torch.cuda.synchronize()
+    for layer in range(n_layers):
+        np.testing.assert_array_equal(O.gather_pages(down(t_kpool)[layer], table, Ls), ref[0][layer])
+        np.testing.assert_array_equal(O.gather_pages(down(t_vpool)[layer], table, Ls), ref[1][layer])
+    np.testing.assert_array_equal(t_L2.cpu().numpy(), ref[2])

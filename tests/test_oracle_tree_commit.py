@@ -139,3 +139,92 @@ def test_tree_build_agrees_with_the_input_generator():
         np.testing.assert_array_equal(parent, t.parent)
         np.testing.assert_array_equal(depth, t.depth)
         np.testing.assert_array_equal(q_row, t.q_row)
+
+
+def with_root(parent):
+    """The tree with its root as node 0: what root_row = 1 means for tree attention."""
+    return np.concatenate([[-1], np.asarray(parent, np.int64) + 1]).astype(np.int32)
+
+
+def test_root_row_two_decode_steps_equal_causal_attention_over_the_generated_sequence():
+    """Sec. 3.3 / Sec. 3: the root of a step is the endpoint token of the step before and goes
+    through the same forward pass as the candidates.  With the root as row 0 of the tree block:
+    (1) tree attention of step 1 for the root and every candidate equals textbook causal attention
+    over [context ; root ; path]; (2) after the commit the cache holds context, root, accepted
+    tokens in sequence order; (3) in step 2 every candidate's attention equals causal attention
+    over the whole generated sequence so far: context, root 1, accepted tokens of step 1, root 2
+    (the endpoint of step 1), its own path."""
+    rng = np.random.default_rng(33)
+    B, H_q, H_kv, d, Ls = 2, 4, 2, 16, 40
+    parent, depth, _ = O.tree_build((2, 2, 1))
+    N = parent.shape[0]
+    pr = with_root(parent)
+    scale = 0.25
+    L0 = np.array([7, 13], np.int32)
+    kp = rng.standard_normal((B, H_kv, Ls, d)).astype(np.float32)
+    vp = rng.standard_normal((B, H_kv, Ls, d)).astype(np.float32)
+    G = H_q // H_kv
+
+    def step_inputs():
+        return (rng.standard_normal((B, 1 + N, H_q, d)).astype(np.float32),
+                rng.standard_normal((B, H_kv, 1 + N, d)).astype(np.float32),
+                rng.standard_normal((B, H_kv, 1 + N, d)).astype(np.float32))
+
+    def check_against_sequences(q, kt, vt, kc, vc, L):
+        out = O.tree_attn(q, kc, vc, L, kt, vt, pr, scale, O.FP32)
+        for b in range(B):
+            for r in range(1 + N):
+                # rows of the tree block on the way from the root to r (row 0 = root, row 1 + i = candidate i)
+                chain, a = [], r
+                while a >= 0:
+                    chain.append(a)
+                    a = int(pr[a])
+                chain = chain[::-1]
+                assert chain[0] == 0
+                for h in range(H_q):
+                    g = h // G
+                    K = np.concatenate([kc[b, g, :L[b]], kt[b, g, chain]])
+                    V = np.concatenate([vc[b, g, :L[b]], vt[b, g, chain]])
+                    np.testing.assert_allclose(out[b, r, h], _attention(q[b, r, h], K, V, scale), rtol=0, atol=1e-12)
+        return out
+
+    # step 1
+    q1, kt1, vt1 = step_inputs()
+    check_against_sequences(q1, kt1, vt1, kp, vp, L0)
+    paths = np.array([[1, 4, 8], [0, 3, -1]], np.int32)
+    n_acc = np.array([3, 2], np.int32)
+    out_tok = np.array([[11, 12, 13, 99], [21, 22, 77, -1]], np.int32)
+    k2, v2, L1, nxt, full = O.kv_commit(kp[None], vp[None], kt1[None], vt1[None], n_acc, paths, out_tok, L0, root_row=True)
+    assert L1.tolist() == [7 + 1 + 3, 13 + 1 + 2] and nxt.tolist() == [99, 77] and full.tolist() == [0, 0]
+    for b in range(B):
+        # the cache now holds: context, root, accepted path, in that order; nothing else moved
+        np.testing.assert_array_equal(k2[0, b, :, :L0[b]], kp[b, :, :L0[b]])
+        np.testing.assert_array_equal(k2[0, b, :, L0[b]], kt1[b, :, 0])
+        np.testing.assert_array_equal(v2[0, b, :, L0[b]], vt1[b, :, 0])
+        for j in range(n_acc[b]):
+            np.testing.assert_array_equal(k2[0, b, :, L0[b] + 1 + j], kt1[b, :, 1 + paths[b, j]])
+            np.testing.assert_array_equal(v2[0, b, :, L0[b] + 1 + j], vt1[b, :, 1 + paths[b, j]])
+        np.testing.assert_array_equal(k2[0, b, :, L1[b]:], kp[b, :, L1[b]:])
+    # step 2: new root (the endpoint of step 1) and new candidates against the grown cache
+    q2, kt2, vt2 = step_inputs()
+    check_against_sequences(q2, kt2, vt2, k2[0], v2[0], L1)
+
+
+def test_root_row_commit_full_cache_and_zero_accepted():
+    rng = np.random.default_rng(34)
+    nl, B, H_kv, d, Ls, N = 2, 3, 2, 8, 10, 6
+    kp = rng.integers(0, 60000, (nl, B, H_kv, Ls, d)).astype(np.uint16)
+    vp = rng.integers(0, 60000, (nl, B, H_kv, Ls, d)).astype(np.uint16)
+    kt = rng.integers(0, 60000, (nl, B, H_kv, 1 + N, d)).astype(np.uint16)
+    vt = rng.integers(0, 60000, (nl, B, H_kv, 1 + N, d)).astype(np.uint16)
+    L = np.array([8, 4, 10], np.int32)
+    n_acc = np.array([2, 0, 0], np.int32)     # 8 + 1 + 2 > 10: full; only the root; a full cache has no room for the root
+    paths = np.array([[1, 4], [-1, -1], [-1, -1]], np.int32)
+    out_tok = np.array([[5, 6, 7], [8, -1, -1], [9, -1, -1]], np.int32)
+    k2, v2, L2, nxt, full = O.kv_commit(kp, vp, kt, vt, n_acc, paths, out_tok, L, root_row=True)
+    assert full.tolist() == [1, 0, 1] and L2.tolist() == [8, 5, 10] and nxt.tolist() == [7, 8, 9]
+    for layer in range(nl):
+        np.testing.assert_array_equal(k2[layer, 1, :, 4], kt[layer, 1, :, 0])
+        np.testing.assert_array_equal(v2[layer, 1, :, 4], vt[layer, 1, :, 0])
+    changed = (k2 != kp) | (v2 != vp)
+    assert not changed[:, 0].any() and not changed[:, 2].any() and not changed[:, 1, :, :4].any() and not changed[:, 1, :, 5:].any()
