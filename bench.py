@@ -33,7 +33,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 # HBM traffic per launch of the tree-attention kernel measured with rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see the
 # summaries under profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {"c4": 657899304, "c5": 349682381, "c3": 50845169, "c2": 9498164}   # profiles/step_<workload>.md
+MEASURED_TRAFFIC_BYTES = {"c4": 662623456, "c5": 350057247, "c3": 50838947, "c2": 9502259}   # profiles/step_<workload>.md
 
 
 def parse_args():
