@@ -445,9 +445,19 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
             build_ancestor_masks(p.parent + (p.parent_per_seq ? (size_t)b * (p.N - p.root_row) : 0), p.N, p.root_row, s_anc, s_parent);
             __syncthreads();
         }
-        auto tile_step = [&](const int t, auto stage) __attribute__((always_inline)) {
+        // PLAIN (a promise of the caller): tile t and the tile requested during this step are whole
+        // tiles of a contiguous prefix inside the segment.  Their references are then plain offsets,
+        // nothing is masked, and the step is one straight run of instructions up to the (rare)
+        // raise of the running maxima.
+        auto plain_ref = [&](int t) {
+            TileRef r;
+            r.off = t * TILE_BYTES; r.nvalid = KT; r.tree = false; r.tt = 0; r.page_off = 0; r.paged = false;
+            return r;
+        };
+        auto tile_step = [&](const int t, auto stage, auto plain) __attribute__((always_inline)) {
             constexpr int ST = decltype(stage)::value;      // COOP: register stage and LDS buffer of this tile
-            const TileRef cur = tile_ref(t);
+            constexpr bool PLAIN = decltype(plain)::value;
+            const TileRef cur = PLAIN ? plain_ref(t) : tile_ref(t);
             // Both K and V run one tile ahead of their use: K(t) goes from its load registers to LDS
             // (operand order) and K(t + KS) is requested into the same registers; V(t + KS) is
             // requested further down, as soon as V(t) has left its registers.
@@ -460,11 +470,8 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
                 const uint32_t *cb = s_big + ST * COOP_BUF_WORDS;
                 uint32_t *nb = s_big + (ST ^ 1) * COOP_BUF_WORDS;
                 const int blk_next = blk_ahead, row_next = row_ahead;
-                if (PAGED) table_lookup_next(t + 4);
+                if (PAGED && !PLAIN) table_lookup_next(t + 4);
                 __syncthreads();
-                // The wave's two 16-row tiles are taken through the tile one after the other, in the
-                // order QK(0) QK(1) softmax(0) PV(0) softmax(1) PV(1): the matrix cores work on
-                // QK(1) and PV(0) while the vector ALU does the softmax of the other row tile.
                 typedef short v4i16 __attribute__((ext_vector_type(4)));
                 typedef v4i16 __attribute__((address_space(3))) *lds_v4i16_ptr;
                 f32x4 sacc[2][MT];
@@ -491,7 +498,7 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
                     *reinterpret_cast<u32x4 *>(nb + coop_kst[j]) = kraw[2 * (ST ^ 1) + j];
                     *reinterpret_cast<u32x4 *>(nb + coop_vst[j]) = vcur[2 * (ST ^ 1) + j];
                 }
-                load_kv_coop(tile_ref_blk(t + 3, blk_next, row_next), ST ^ 1);
+                load_kv_coop(PLAIN ? plain_ref(t + 3) : tile_ref_blk(t + 3, blk_next, row_next), ST ^ 1);
                 if (!wave_active) return;
                 // V^T operands by transposing LDS reads, requested now: they arrive during the first softmax
                 bf16x8 vop[8];
@@ -501,28 +508,37 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
                     const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_ptr)(cb + coop_vld + 16 * 72 + nt * 8));
                     vop[nt] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
                 }
-                const bool masked = cur.nvalid < KT || cur.tree;
+                const bool masked = !PLAIN && (cur.nvalid < KT || cur.tree);
+                uint32_t vis[MT];
+                float lmax[MT];
+                bool raise = false;
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    uint32_t vis = 0xffffffffu;
+                    vis[mt] = 0xffffffffu;
                     if (masked) {
                         const int node_m = min(row0 + WROWS * rh + 16 * mt + lc, p.M - 1) / p.G;
-                        if (cur.tree) vis = s_anc[node_m][cur.tt];
-                        if (cur.nvalid < KT) vis &= (1u << cur.nvalid) - 1u;
+                        if (cur.tree) vis[mt] = s_anc[node_m][cur.tt];
+                        if (cur.nvalid < KT) vis[mt] &= (1u << cur.nvalid) - 1u;
 #pragma unroll
                         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
                             for (int i = 0; i < 4; ++i)
-                                if (!((vis >> (16 * sub + 4 * lj + i)) & 1u)) sacc[sub][mt][i] = -INFINITY;
+                                if (!((vis[mt] >> (16 * sub + 4 * lj + i)) & 1u)) sacc[sub][mt][i] = -INFINITY;
                     }
                     // online softmax with a lazily raised running max (scaled, base-2 domain)
                     const float m0 = max3_raw(sacc[0][mt][0], sacc[0][mt][1], sacc[0][mt][2]);
                     const float m1 = max3_raw(sacc[0][mt][3], sacc[1][mt][0], sacc[1][mt][1]);
                     const float mr = max3_raw(max3_raw(m0, m1, sacc[1][mt][2]), sacc[1][mt][3], sacc[1][mt][3]);
-                    const float lmax = (mr == -INFINITY) ? -INFINITY : mr * c2;
-                    if (__any(lmax > m_used[mt] + RESCALE_GAP)) {
-                        float rm = lmax;
+                    lmax[mt] = (mr == -INFINITY) ? -INFINITY : mr * c2;
+                    raise |= lmax[mt] > m_used[mt] + RESCALE_GAP;
+                }
+                // one test for both row tiles: everything from here to the end of the step is one
+                // straight run, in which the scheduler can place the vector work of one row tile
+                // between the matrix instructions of the other
+                if (__any(raise)) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        float rm = lmax[mt];
                         rm = fmaxf(rm, __shfl_xor(rm, 16));
                         rm = fmaxf(rm, __shfl_xor(rm, 32));
                         const float m_new = fmaxf(m_used[mt], rm);
@@ -532,6 +548,9 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
 #pragma unroll
                         for (int nt = 0; nt < 8; ++nt) oacc[nt][mt] *= alpha;
                     }
+                }
+                // weights of one row tile: p = 2^(s c2 - m), masked keys 0; returns the lane's share of the row sum
+                auto weights = [&](const int mt, bf16x8 &pop) __attribute__((always_inline)) {
                     float pv[8];
 #pragma unroll
                     for (int sub = 0; sub < 2; ++sub)
@@ -543,16 +562,37 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
                         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
                             for (int i = 0; i < 4; ++i)
-                                if (!((vis >> (16 * sub + 4 * lj + i)) & 1u)) pv[4 * sub + i] = 0.f;
+                                if (!((vis[mt] >> (16 * sub + 4 * lj + i)) & 1u)) pv[4 * sub + i] = 0.f;
                     }
-                    l_part[mt] += ((pv[0] + pv[1]) + (pv[2] + pv[3])) + ((pv[4] + pv[5]) + (pv[6] + pv[7]));
                     const u32x4 pk = {pack_bf16(pv[0], pv[1]), pack_bf16(pv[2], pv[3]), pack_bf16(pv[4], pv[5]), pack_bf16(pv[6], pv[7])};
-                    const bf16x8 pop = __builtin_bit_cast(bf16x8, pk);
-                    // O^T[d][row] += sum_key V[key][d] P[row][key]
+                    pop = __builtin_bit_cast(bf16x8, pk);
+                    return ((pv[0] + pv[1]) + (pv[2] + pv[3])) + ((pv[4] + pv[5]) + (pv[6] + pv[7]));
+                };
+                // A wave issues in order, and vector instructions placed behind a matrix instruction
+                // run while the matrix pipe works on it.  So: the weights of the first row tile; then
+                // its eight PV matrix instructions, each followed by a share of the second row tile's
+                // weights; then the second row tile's PV.  (O^T[d][row] += sum_key V[key][d] P[row][key])
+                static_assert(MT == 2, "the schedule below is written for two row tiles per wave");
+                bf16x8 pop0, pop1;
+                const float sum0 = weights(0, pop0);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int nt = 0; nt < 8; ++nt)
-                        oacc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[nt], pop, oacc[nt][mt], 0, 0, 0);
+                for (int nt = 0; nt < 8; ++nt)
+                    oacc[nt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[nt], pop0, oacc[nt][0], 0, 0, 0);
+                const float sum1 = weights(1, pop1);
+                l_part[0] += sum0;
+                if (!masked) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x402, 4, 0);
+                    }
                 }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int nt = 0; nt < 8; ++nt)
+                    oacc[nt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[nt], pop1, oacc[nt][1], 0, 0, 0);
+                l_part[1] += sum1;
                 return;
             } else {
 #pragma unroll
@@ -694,13 +734,23 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
             // branch around its second half: with one, the wait for a stage's data at the top of
             // the loop would have to cover the path on which no younger loads are in flight, that
             // is, wait for everything.  An odd last tile is handled after the loop.
-            for (; t + 1 < t_end; t += 2) {
-                tile_step(t, std::integral_constant<int, 0>());
-                tile_step(t + 1, std::integral_constant<int, 1>());
+            // The bulk of a long contiguous prefix goes through the plain step: while t + 4 is
+            // still a whole prefix tile of this segment, so are t, t + 1 and the two tiles requested
+            // during the pair.
+            if (!PAGED) {
+                const int t_plain = min(t_end, L / KT);
+                for (; t + 4 < t_plain; t += 2) {
+                    tile_step(t, std::integral_constant<int, 0>(), std::true_type());
+                    tile_step(t + 1, std::integral_constant<int, 1>(), std::true_type());
+                }
             }
-            if (t < t_end) tile_step(t, std::integral_constant<int, 0>());
+            for (; t + 1 < t_end; t += 2) {
+                tile_step(t, std::integral_constant<int, 0>(), std::false_type());
+                tile_step(t + 1, std::integral_constant<int, 1>(), std::false_type());
+            }
+            if (t < t_end) tile_step(t, std::integral_constant<int, 0>(), std::false_type());
         } else {
-            for (; t < t_end; t += KS) tile_step(t, std::integral_constant<int, 0>());
+            for (; t < t_end; t += KS) tile_step(t, std::integral_constant<int, 0>(), std::false_type());
         }
 
         // ---- epilogue: merge the key streams.  (m, l) per row through LDS; O in two halves of d:
