@@ -78,12 +78,31 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *ptr, uin
 }
 
 // max(a, b, c) as the one hardware instruction: fmaxf() on values the compiler knows nothing
-// about (MFMA results) costs an extra NaN-quieting v_max_f32 x, x per operand.
+// about (matrix-instruction results) costs an extra NaN-quieting v_max_f32 x, x per operand.
 __device__ __forceinline__ float max3_raw(float a, float b, float c)
 {
     float r;
     asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
     return r;
+}
+
+// A vector instruction that reads the result of a matrix instruction has to keep a distance
+// from it (seven wait states for v_mfma_f32_16x16x32_bf16) which the hardware does not enforce.
+// The compiler keeps it for the instructions it selects itself, but not for the text of an asm
+// statement: the four score accumulators pass through this statement before max3_raw reads
+// them, so every matrix instruction that writes them has been issued before its wait states
+// and every reader stands behind them.
+__device__ __forceinline__ void settle_scores(f32x4 &a, f32x4 &b, f32x4 &c, f32x4 &d)
+{
+    asm volatile("s_nop 7\n\ts_nop 1" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+}
+
+// the largest of the eight scores a lane holds for one row (two accumulators of four)
+__device__ __forceinline__ float max_of_scores(const f32x4 &s0, const f32x4 &s1)
+{
+    const float m0 = max3_raw(s0[0], s0[1], s0[2]);
+    const float m1 = max3_raw(s0[3], s1[0], s1[1]);
+    return max3_raw(max3_raw(m0, m1, s1[2]), s1[3], s1[3]);
 }
 
 __device__ __forceinline__ float fast_exp2(float x)
@@ -512,6 +531,7 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
                 uint32_t vis[MT];
                 float lmax[MT];
                 bool raise = false;
+                settle_scores(sacc[0][0], sacc[0][1], sacc[1][0], sacc[1][1]);
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
                     vis[mt] = 0xffffffffu;
@@ -526,9 +546,7 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
                                 if (!((vis[mt] >> (16 * sub + 4 * lj + i)) & 1u)) sacc[sub][mt][i] = -INFINITY;
                     }
                     // online softmax with a lazily raised running max (scaled, base-2 domain)
-                    const float m0 = max3_raw(sacc[0][mt][0], sacc[0][mt][1], sacc[0][mt][2]);
-                    const float m1 = max3_raw(sacc[0][mt][3], sacc[1][mt][0], sacc[1][mt][1]);
-                    const float mr = max3_raw(max3_raw(m0, m1, sacc[1][mt][2]), sacc[1][mt][3], sacc[1][mt][3]);
+                    const float mr = max_of_scores(sacc[0][mt], sacc[1][mt]);
                     lmax[mt] = (mr == -INFINITY) ? -INFINITY : mr * c2;
                     raise |= lmax[mt] > m_used[mt] + RESCALE_GAP;
                 }
@@ -598,7 +616,7 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
                     *reinterpret_cast<u32x4 *>(area + 4 * (kst_pos[i & 3] + (i >> 2) * 256)) = kraw[i];
-                load_k(tile_ref(t + KS));
+                load_k(PLAIN ? plain_ref(t + KS) : tile_ref(t + KS));
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -628,7 +646,7 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
                     }
             }
             // lane (lj, lc) now holds, for its row 16 mt + lc, keys 16 sub + 4 lj + i
-            const bool masked = cur.nvalid < KT || cur.tree;
+            const bool masked = !PLAIN && (cur.nvalid < KT || cur.tree);
             uint32_t onmask[MT];
             if (masked) {
 #pragma unroll
@@ -647,13 +665,12 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
                 }
             }
             // online softmax with a lazily raised running max (scaled, base-2 domain)
+            settle_scores(sacc[0][0], sacc[0][1], sacc[1][0], sacc[1][1]);
             bool raise = false;
             float lmax[MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                const float m0 = max3_raw(sacc[0][mt][0], sacc[0][mt][1], sacc[0][mt][2]);
-                const float m1 = max3_raw(sacc[0][mt][3], sacc[1][mt][0], sacc[1][mt][1]);
-                const float mr = max3_raw(max3_raw(m0, m1, sacc[1][mt][2]), sacc[1][mt][3], sacc[1][mt][3]);
+                const float mr = max_of_scores(sacc[0][mt], sacc[1][mt]);
                 lmax[mt] = (mr == -INFINITY) ? -INFINITY : mr * c2;
                 raise |= lmax[mt] > m_used[mt] + RESCALE_GAP;
             }
@@ -707,7 +724,7 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
                 o[3] = __builtin_amdgcn_perm(vcur[7][w], vcur[6][w], sel);
                 *reinterpret_cast<u32x4 *>(area + 4 * (vst_base + (vst_x ^ e))) = o;
             }
-            load_v(tile_ref(t + KS));
+            load_v(PLAIN ? plain_ref(t + KS) : tile_ref(t + KS));
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -750,6 +767,10 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
             }
             if (t < t_end) tile_step(t, std::integral_constant<int, 0>(), std::false_type());
         } else {
+            if (!PAGED) {
+                const int t_plain = min(t_end, L / KT);
+                for (; t + KS < t_plain; t += KS) tile_step(t, std::integral_constant<int, 0>(), std::true_type());
+            }
             for (; t < t_end; t += KS) tile_step(t, std::integral_constant<int, 0>(), std::false_type());
         }
 
