@@ -33,7 +33,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 # HBM traffic per launch of the tree-attention kernel measured with rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see the
 # summaries under profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {"c4": 662623456, "c5": 350057247, "c3": 50838947, "c2": 9502259}   # profiles/step_<workload>.md
+MEASURED_TRAFFIC_BYTES = {"c4": 655631815, "c5": 348566826, "c3": 50875781, "c2": 9534005}   # profiles/step_<workload>.md
 
 
 def parse_args():
