@@ -465,9 +465,9 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
             __syncthreads();
         }
         // PLAIN (a promise of the caller): tile t and the tile requested during this step are whole
-        // tiles of a contiguous prefix inside the segment.  Their references are then plain offsets,
-        // nothing is masked, and the step is one straight run of instructions up to the (rare)
-        // raise of the running maxima.
+        // prefix tiles inside the segment.  Nothing is masked, the step is one straight run of
+        // instructions up to the (rare) raise of the running maxima, and with a contiguous cache
+        // the tile references are plain offsets (a paged cache still looks its pages up).
         auto plain_ref = [&](int t) {
             TileRef r;
             r.off = t * TILE_BYTES; r.nvalid = KT; r.tree = false; r.tt = 0; r.page_off = 0; r.paged = false;
@@ -489,7 +489,7 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
                 const uint32_t *cb = s_big + ST * COOP_BUF_WORDS;
                 uint32_t *nb = s_big + (ST ^ 1) * COOP_BUF_WORDS;
                 const int blk_next = blk_ahead, row_next = row_ahead;
-                if (PAGED && !PLAIN) table_lookup_next(t + 4);
+                if (PAGED) table_lookup_next(t + 4);
                 __syncthreads();
                 typedef short v4i16 __attribute__((ext_vector_type(4)));
                 typedef v4i16 __attribute__((address_space(3))) *lds_v4i16_ptr;
@@ -517,7 +517,7 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
                     *reinterpret_cast<u32x4 *>(nb + coop_kst[j]) = kraw[2 * (ST ^ 1) + j];
                     *reinterpret_cast<u32x4 *>(nb + coop_vst[j]) = vcur[2 * (ST ^ 1) + j];
                 }
-                load_kv_coop(PLAIN ? plain_ref(t + 3) : tile_ref_blk(t + 3, blk_next, row_next), ST ^ 1);
+                load_kv_coop(PLAIN && !PAGED ? plain_ref(t + 3) : tile_ref_blk(t + 3, blk_next, row_next), ST ^ 1);
                 if (!wave_active) return;
                 // V^T operands by transposing LDS reads, requested now: they arrive during the first softmax
                 bf16x8 vop[8];
@@ -616,7 +616,7 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
                     *reinterpret_cast<u32x4 *>(area + 4 * (kst_pos[i & 3] + (i >> 2) * 256)) = kraw[i];
-                load_k(PLAIN ? plain_ref(t + KS) : tile_ref(t + KS));
+                load_k(PLAIN && !PAGED ? plain_ref(t + KS) : tile_ref(t + KS));
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -724,7 +724,7 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
                 o[3] = __builtin_amdgcn_perm(vcur[7][w], vcur[6][w], sel);
                 *reinterpret_cast<u32x4 *>(area + 4 * (vst_base + (vst_x ^ e))) = o;
             }
-            load_v(PLAIN ? plain_ref(t + KS) : tile_ref(t + KS));
+            load_v(PLAIN && !PAGED ? plain_ref(t + KS) : tile_ref(t + KS));
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -754,7 +754,7 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
             // The bulk of a long contiguous prefix goes through the plain step: while t + 4 is
             // still a whole prefix tile of this segment, so are t, t + 1 and the two tiles requested
             // during the pair.
-            if (!PAGED) {
+            {
                 const int t_plain = min(t_end, L / KT);
                 for (; t + 4 < t_plain; t += 2) {
                     tile_step(t, std::integral_constant<int, 0>(), std::true_type());
@@ -767,7 +767,7 @@ void tree_attn_mfma_kernel(AttnParams p, WalkParams w)
             }
             if (t < t_end) tile_step(t, std::integral_constant<int, 0>(), std::false_type());
         } else {
-            if (!PAGED) {
+            {
                 const int t_plain = min(t_end, L / KT);
                 for (; t + KS < t_plain; t += KS) tile_step(t, std::integral_constant<int, 0>(), std::true_type());
             }
