@@ -229,6 +229,33 @@ def test_thousands_of_short_segments(plan_override, H_q, H_kv, kconfig, target):
         assert torch.equal(call.out.view(torch.int16), first.view(torch.int16)), rep
 
 
+@pytest.mark.parametrize("H_q,H_kv,kconfig", [(4, 4, (4, 2, 2)), (8, 4, (4, 2, 2)), (32, 4, (4, 2, 2))])
+def test_long_unsplit_prefix_is_the_same_bits_on_every_run(plan_override, H_q, H_kv, kconfig):
+    """One long segment per sequence: nearly every tile goes through the straight-line step, in
+    which the running-maximum update stands close behind the score matrix instructions.  Scores
+    that grow along the prefix make that update fire many times; a maximum read before the
+    matrix result has landed would move the raises around from run to run (the outputs stay
+    within tolerance then, so only the bit comparison sees it).  One case per kernel variant."""
+    plan_override(0, 400, 0)
+    ai = W.gen_attn_inputs(wl(H_q=H_q, H_kv=H_kv, kconfig=kconfig, prefix=(3000, 4096), B=3), np.random.default_rng(90 + H_q),
+                           L_stride=4096)
+    # keys later in the prefix score higher: K rows scaled by a ramp (bf16 bits rewritten)
+    k = W.bf16_bits_to_f32(ai.k_prefix)
+    ramp = np.linspace(0.2, 3.0, k.shape[2], dtype=np.float32)[None, None, :, None]
+    ai.k_prefix = W.f32_to_bf16_bits(k * ramp)
+    ref = oracle_rows(ai)
+    call = D.make_attn_call(ai)
+    M.mcsd_tree_attn(call.args)
+    torch.cuda.synchronize()
+    first = call.out.clone()
+    assert_attn_close(call.out_numpy(), ref, "bf16", f"ramp {H_q}/{H_kv}")
+    for rep in range(4):
+        call.out.fill_(3.0)
+        M.mcsd_tree_attn(call.args)
+        torch.cuda.synchronize()
+        assert torch.equal(call.out.view(torch.int16), first.view(torch.int16)), rep
+
+
 def test_plan_override_rejects_bad_values():
     with pytest.raises(M.McsdError):
         M.mcsd_attn_plan_override(4, 0, 0)
