@@ -220,6 +220,46 @@ __device__ __forceinline__ void load_row(const float *z, int V, float4 (&r)[ITEM
     }
 }
 
+// A logit row is read through a buffer resource whose extent is the row: the address of float4
+// number t + VT i is one per-thread offset plus a scalar, reads past the end return zero instead
+// of leaving the array, and no per-load address registers or bounds branches are needed.
+// Elements past V are then set to -inf (only in the float4s that can reach past V at all).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t row_resource(const float *row, int V)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(row), 0, V * 4, 0x00020000);
+}
+
+template <int VT, bool ALIGNED, bool NONTEMPORAL>
+__device__ __forceinline__ float4 load_row_piece(__amdgpu_buffer_rsrc_t rs, int i, int V, int tid)
+{
+    constexpr int AUX = NONTEMPORAL ? 2 : 0;
+    const int voff = tid * 16, soff = i * (VT * 16);
+    // the thread's first element of this piece lies past V iff 4 t >= V - 4 VT i: one per-thread
+    // value against a scalar, no per-piece index registers
+    const int e0 = 4 * tid, lim = V - 4 * VT * i;
+    const float ninf = -INFINITY;
+    float4 r;
+    if (ALIGNED) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, AUX);
+        const bool past = e0 >= lim;
+        r = make_float4(past ? ninf : __uint_as_float(v[0]), past ? ninf : __uint_as_float(v[1]),
+                        past ? ninf : __uint_as_float(v[2]), past ? ninf : __uint_as_float(v[3]));
+    } else {
+        // (row start and length are not multiples of 16 bytes: element by element)
+        r.x = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, voff, soff, AUX));
+        r.y = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, voff + 4, soff, AUX));
+        r.z = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, voff + 8, soff, AUX));
+        r.w = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, voff + 12, soff, AUX));
+        if (e0 + 0 >= lim) r.x = ninf;
+        if (e0 + 1 >= lim) r.y = ninf;
+        if (e0 + 2 >= lim) r.z = ninf;
+        if (e0 + 3 >= lim) r.w = ninf;
+    }
+    return r;
+}
+
 // max(a, b, c) as the one hardware instruction.  fmaxf() has to quiet signalling NaNs, and for
 // values the compiler knows nothing about (loaded from memory) it does so with an extra
 // v_max_f32 x, x per operand: three instructions per element instead of half of one.  The
